@@ -1,0 +1,234 @@
+"""Oracle batched search (TEST INFRASTRUCTURE ONLY; see package header).
+
+The steps follow Section 3.3 in the paper's order: rotate the batch (3.3.1),
+select clusters (3.3.2), prepare the per-query representation once (3.3.3),
+cluster-local two-stage estimation (3.3.4) with the bitwise inner product of
+Section 3.4.1(2), and the per-query merge (3.3.5).  Floating point is float64
+except where a stored format or an integer decision fixes fp32 (stated below).
+
+Readings taken where the paper is silent
+----------------------------------------
+* Query quantisation (Section 3.4.1(2) gives neither scale nor rounding):
+  ``delta = max|q'| / 7``, ``qhat = clamp(rint(q'/delta), -7, 7)`` (round half to
+  even), both evaluated in fp32 because they decide integers; 4 two's-complement
+  bit-planes, plane 3 weighted -8.
+* Refinement uses the unquantised fp32 ``q'`` (Section 3.4.2 says only "the
+  query").
+* Threshold (Section 3.3.4 "current K-th best distance"): the running value is
+  order dependent on a parallel machine, so it is fixed per query before the
+  scan.  In the query's nearest probed cluster holding at least K vectors, the K
+  vectors with the smallest 1-bit estimates are refined and ``tau`` is the largest
+  of their refined estimates (for B = 1: the K-th smallest 1-bit estimate).
+  Every probed cluster is then filtered with that one ``tau``: a vector survives
+  when its 1-bit lower bound (B = 1: its 1-bit estimate) is <= tau.  ``tau`` is
+  always >= the final K-th best key of the unpruned search.
+* Result: the K smallest (key, id) among survivors; L2 keys are estimated squared
+  distances, IP keys are negated estimated inner products.
+
+Parity status
+-------------
+rotate_queries, coarse_probe  pinned: direct ||q'-c'||^2 loop, full argsort.
+quantize_query, bitplanes     pinned: |delta*qhat - q'| <= delta/2, planes
+                              reassemble to qhat, storage size of Section 3.4.1.
+ip_bitplane                   pinned: exhaustive identity of Section 3.4.1(2).
+estimate_1bit / _refined      pinned via build.vector_factors pins; refined
+                              estimate error shrinking with B is a trend only
+                              ("parity unpinned" for its exact values).
+search                        pinned: brute force on tiny inputs (nprobe = nlist,
+                              B = 8 recovers exact kNN), pruned == unpruned
+                              whenever the oracle's own predicate holds.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from .build import short_words
+
+FLT_MAX = float(np.finfo(np.float32).max)
+BQ = 4  # query bits (Section 3.4.1(2) example)
+
+
+# ---- 3.3.1 -----------------------------------------------------------------
+def rotate_queries(Q: np.ndarray, P: np.ndarray) -> np.ndarray:
+    """``Q' = Q P`` evaluated in float64 and stored as fp32 [nq, D]."""
+    return (np.asarray(Q, np.float64) @ np.asarray(P, np.float64)).astype(np.float32)
+
+
+# ---- 3.3.2 -----------------------------------------------------------------
+def coarse_probe(Qr: np.ndarray, C_rot: np.ndarray, nprobe: int, metric: str):
+    """Nearest ``nprobe`` clusters per query by the matrix form
+    ``s_q 1^T + 1 s_c^T - 2 Q' C^T`` (Section 3.3.2); ties go to the lower
+    cluster id.  Returns (probe ids [nq,nprobe] i32, G [nq,nprobe] f64,
+    E [nq,nprobe] f64) where G is the additive term of the estimator
+    (L2: ||q'-c'||^2, IP: -<q',c'>) and E = ||q'-c'||."""
+    q = np.asarray(Qr, np.float64)
+    c = np.asarray(C_rot, np.float64)
+    sq = np.einsum("ij,ij->i", q, q)
+    sc = np.einsum("ij,ij->i", c, c)
+    dot = q @ c.T
+    d2 = sq[:, None] + sc[None, :] - 2.0 * dot
+    score = d2 if metric == "l2" else -dot
+    nlist = c.shape[0]
+    # lexicographic (score, cluster id): stable argsort on score
+    order = np.argsort(score, axis=1, kind="stable")[:, :nprobe]
+    G = np.take_along_axis(score, order, axis=1)
+    E = np.sqrt(np.maximum(np.take_along_axis(d2, order, axis=1), 0.0))
+    assert nprobe <= nlist
+    return order.astype(np.int32), G, E
+
+
+# ---- 3.3.3 / 3.4.1(2) --------------------------------------------------------
+def quantize_query(qr: np.ndarray):
+    """4-bit signed quantisation of one rotated query (fp32 arithmetic).
+    Returns (delta f32, qhat int8 [D], S = sum(qhat) int)."""
+    qr = np.asarray(qr, dtype=np.float32)
+    amax = np.float32(np.max(np.abs(qr)))
+    if amax == np.float32(0.0):
+        return np.float32(1.0), np.zeros(qr.shape[0], np.int8), 0
+    delta = np.float32(amax / np.float32(7.0))
+    t = (qr / delta).astype(np.float32)
+    qhat = np.clip(np.rint(t), -7, 7).astype(np.int8)
+    return delta, qhat, int(qhat.astype(np.int64).sum())
+
+
+def query_bitplanes(qhat: np.ndarray) -> np.ndarray:
+    """Two's-complement bit-planes [4, W] uint32; bit i of word w of plane j is
+    bit j of qhat[32w+i] (Figure 1's q^(j))."""
+    D = qhat.shape[0]
+    tc = (qhat.astype(np.int64) & 0xF).astype(np.uint32).reshape(D // 32, 32)
+    sh = np.arange(32, dtype=np.uint32)
+    planes = np.empty((BQ, D // 32), dtype=np.uint32)
+    for j in range(BQ):
+        planes[j] = (((tc >> np.uint32(j)) & np.uint32(1)) << sh[None, :]).sum(axis=1, dtype=np.uint64)
+    return planes
+
+
+def ip_bitplane(xb_words: np.ndarray, planes: np.ndarray) -> np.ndarray:
+    """``<x_b, qhat>`` for packed 1-bit codes [n, W] by AND + popcount over the
+    bit-planes: ``-8 pc(x & q3) + 4 pc(x & q2) + 2 pc(x & q1) + pc(x & q0)``."""
+    out = np.zeros(xb_words.shape[0], dtype=np.int64)
+    for j in range(BQ):
+        pc = np.bitwise_count(xb_words & planes[j][None, :]).sum(axis=1, dtype=np.int64)
+        w = -(1 << (BQ - 1)) if j == BQ - 1 else (1 << j)
+        out += w * pc
+    return out
+
+
+def estimate_1bit(G, E, short_factors, delta, I, S):
+    """1-bit estimate and its lower bound for one (query, cluster) pair.
+    ``<x_bar, q'> ~= delta * (I - S/2)`` with ``x_bar = u_b - 1/2``."""
+    f = short_factors.astype(np.float64)
+    ipq = float(delta) * (2.0 * I.astype(np.float64) - float(S)) / 2.0
+    est = G + f[:, 0] + f[:, 1] * ipq
+    lb = est - f[:, 2] * E
+    return est, lb
+
+
+def estimate_refined(G, long_factors, u, qr, total_bits):
+    """Refined estimate from the full code: ``<x, q'> = <u, q'> - c_B sum(q')``."""
+    f = long_factors.astype(np.float64)
+    q = qr.astype(np.float64)
+    cB = ((1 << total_bits) - 1) / 2.0
+    ipq = u.astype(np.float64) @ q - cB * q.sum()
+    return G + f[:, 0] + f[:, 1] * ipq
+
+
+def topk_pairs(keys: np.ndarray, ids: np.ndarray, k: int):
+    """The k smallest (key, id) pairs in ascending lexicographic order."""
+    order = np.lexsort((ids, keys))[:k]
+    return keys[order], ids[order]
+
+
+class Searcher:
+    """Holds an index (oracle.build.build_index output) and answers batches."""
+
+    def __init__(self, index: dict):
+        self.ix = index
+        self.words = short_words(index)  # [N, W] packed 1-bit codes
+        self.B = index["total_bits"]
+        self.metric = index["metric"]
+
+    # one (query, cluster) pair: all stage outputs
+    def pair(self, c, G, E, qr, delta, planes, S):
+        ix = self.ix
+        s, e = int(ix["offsets"][c]), int(ix["offsets"][c + 1])
+        I = ip_bitplane(self.words[s:e], planes)
+        est1, lb1 = estimate_1bit(G, E, ix["short_factors"][s:e], delta, I, S)
+        return s, e, I, est1, lb1
+
+    def refined(self, s, e, G, qr, sel=None):
+        ix = self.ix
+        rows = np.arange(s, e) if sel is None else s + sel
+        return estimate_refined(G, ix["long_factors"][rows], ix["u"][rows], qr, self.B)
+
+    def seed_threshold(self, probes, Gs, Es, qr, delta, planes, S, k):
+        """tau for one query (see module header)."""
+        ix = self.ix
+        for c, G, E in zip(probes, Gs, Es):
+            s, e = int(ix["offsets"][c]), int(ix["offsets"][c + 1])
+            if e - s < k:
+                continue
+            _, _, _, est1, _ = self.pair(c, G, E, qr, delta, planes, S)
+            ids = ix["ids"][s:e].astype(np.int64)
+            sel = np.lexsort((ids, est1))[:k]
+            if self.B == 1:
+                return float(est1[sel[-1]])
+            return float(np.max(self.refined(s, e, G, qr, sel)))
+        return FLT_MAX
+
+    def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False):
+        """Returns (ids [nq,k] i64, dists [nq,k] f64, info).  ``prune=False`` is
+        the unpruned definition (every vector of every probed cluster is ranked by
+        its final key).  ``info`` holds per-query tau, survivor counts, the probe
+        lists, and the count of unpruned top-k members the filter would drop."""
+        ix = self.ix
+        if Qr is None:
+            Qr = rotate_queries(Q, ix["P"])
+        nq = Qr.shape[0]
+        probes, G, E = coarse_probe(Qr, ix["centroids_rot"], nprobe, self.metric)
+        out_ids = np.full((nq, k), -1, dtype=np.int64)
+        out_d = np.full((nq, k), np.inf, dtype=np.float64)
+        taus = np.full(nq, FLT_MAX)
+        n_scanned = np.zeros(nq, np.int64)
+        n_surv = np.zeros(nq, np.int64)
+        dropped = np.zeros(nq, np.int64)
+        details = []
+        for qi in range(nq):
+            qr = Qr[qi]
+            delta, qhat, S = quantize_query(qr)
+            planes = query_bitplanes(qhat)
+            tau = self.seed_threshold(probes[qi], G[qi], E[qi], qr, delta, planes, S, k)
+            taus[qi] = tau
+            keys_all, ids_all, filt_all = [], [], []
+            for j in range(nprobe):
+                c = int(probes[qi, j])
+                s, e, I, est1, lb1 = self.pair(c, G[qi, j], E[qi, j], qr, delta, planes, S)
+                if e == s:
+                    continue
+                key = est1 if self.B == 1 else self.refined(s, e, G[qi, j], qr)
+                filt = est1 if self.B == 1 else lb1
+                keys_all.append(key)
+                ids_all.append(ix["ids"][s:e].astype(np.int64))
+                filt_all.append(filt)
+            if keys_all:
+                keys = np.concatenate(keys_all)
+                ids = np.concatenate(ids_all)
+                filt = np.concatenate(filt_all)
+            else:
+                keys = np.zeros(0); ids = np.zeros(0, np.int64); filt = np.zeros(0)
+            n_scanned[qi] = keys.shape[0]
+            surv = filt <= tau
+            n_surv[qi] = int(surv.sum())
+            fk, fi = topk_pairs(keys, ids, k)            # unpruned definition
+            pk, pi = topk_pairs(keys[surv], ids[surv], k)  # with the filter
+            dropped[qi] = len(fi) - np.isin(fi, pi).sum()
+            rk, ri = (pk, pi) if prune else (fk, fi)
+            out_ids[qi, :len(ri)] = ri
+            out_d[qi, :len(rk)] = rk
+            if detail:
+                details.append(dict(keys=keys, ids=ids, filt=filt, tau=tau))
+        if self.metric == "ip":
+            out_d = -out_d
+        info = dict(tau=taus, scanned=n_scanned, survivors=n_surv, dropped=dropped,
+                    probes=probes, G=G, E=E, Qr=Qr, details=details)
+        return out_ids, out_d, info

@@ -1,0 +1,123 @@
+"""Pins for the oracle's search pipeline (CPU only)."""
+import numpy as np
+import pytest
+
+from oracle import build, exact, search
+from paper_2602_23999_amd import synth
+
+
+def _tiny(n=3000, nq=40, B=1, nlist=16):
+    w = synth.WORKLOADS["tiny"].scaled(n=n, nq=nq, n_centres=16)
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    return X, Q, build.build_index(X, nlist, B)
+
+
+def test_rotation_orthogonal_and_distance_preserving():
+    P = build.random_rotation(128, 7).astype(np.float64)
+    assert np.abs(P @ P.T - np.eye(128)).max() < 1e-6
+    rng = np.random.default_rng(0)
+    a, b = rng.standard_normal((2, 128))
+    assert abs(np.linalg.norm(a @ P - b @ P) - np.linalg.norm(a - b)) < 1e-5
+    assert np.array_equal(build.random_rotation(64, 3), build.random_rotation(64, 3))
+
+
+def test_exact_knn_matches_python_loops():
+    rng = np.random.default_rng(1)
+    X = rng.standard_normal((60, 5)); Q = rng.standard_normal((4, 5))
+    X[7] = X[3]  # an exact tie
+    for metric in ("l2", "ip"):
+        ids, sc = exact.exact_knn(X, Q, 6, metric)
+        for qi in range(4):
+            key = [(sum((Q[qi, d] - X[i, d]) ** 2 for d in range(5)) if metric == "l2"
+                    else -sum(Q[qi, d] * X[i, d] for d in range(5)), i) for i in range(60)]
+            key.sort()
+            assert [i for _, i in key[:6]] == ids[qi].tolist()
+    assert exact.recall_at_k(np.array([[1, 2, 3], [4, 5, -1]]), np.array([[3, 2, 9], [5, 7, 8]])) == pytest.approx(0.5)
+
+
+def test_kmeans_assignment_is_nearest_centroid():
+    X, _, ix = _tiny()
+    C = ix["centroids"]
+    d = ((X[:200, None, :].astype(np.float64) - C[None]) ** 2).sum(2)
+    a = np.empty(X.shape[0], np.int64)
+    for c in range(ix["nlist"]):
+        a[ix["ids"][ix["offsets"][c]:ix["offsets"][c + 1]]] = c
+    assert np.array_equal(a[:200], d.argmin(1))
+    assert ix["offsets"][-1] == X.shape[0] and sorted(ix["ids"].tolist()) == list(range(X.shape[0]))
+
+
+def test_coarse_probe_matches_direct_loop():
+    X, Q, ix = _tiny()
+    Qr = search.rotate_queries(Q, ix["P"])
+    for metric in ("l2", "ip"):
+        p, G, E = search.coarse_probe(Qr, ix["centroids_rot"], 5, metric)
+        c = ix["centroids_rot"].astype(np.float64)
+        for qi in range(6):
+            d2 = np.array([np.sum((Qr[qi].astype(np.float64) - c[j]) ** 2) for j in range(c.shape[0])])
+            sc = d2 if metric == "l2" else -(c @ Qr[qi].astype(np.float64))
+            o = np.argsort(sc, kind="stable")[:5]
+            assert np.array_equal(o, p[qi])
+            assert np.allclose(G[qi], sc[o], rtol=1e-9, atol=1e-9)
+            assert np.allclose(E[qi], np.sqrt(d2[o]), rtol=1e-7)
+
+
+def test_rotation_does_not_change_exact_neighbours():
+    X, Q, ix = _tiny(n=800, nq=10)
+    P = ix["P"].astype(np.float64)
+    a, _ = exact.exact_knn(X, Q, 5)
+    b, _ = exact.exact_knn(X.astype(np.float64) @ P, Q.astype(np.float64) @ P, 5)
+    assert np.array_equal(a, b)
+
+
+def test_eight_bit_full_probe_recovers_exact_knn():
+    w = synth.WORKLOADS["tiny"].scaled(n=1500, nq=30, n_centres=8)
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    ix = build.build_index(X, 8, 8)
+    s = search.Searcher(ix)
+    ids, d, info = s.search(Q, 10, 8, prune=False)
+    gt, gd = exact.exact_knn(X, Q, 10)
+    assert exact.recall_at_k(ids, gt) >= 0.97
+    # estimated squared distances of the found true neighbours are close to exact ones
+    rel = np.abs(d[:, 0] - gd[:, 0]) / gd[:, 0]
+    assert np.median(rel) < 0.01
+
+
+def test_topk_order_and_padding():
+    X, Q, ix = _tiny(n=300, nq=5, nlist=8)
+    s = search.Searcher(ix)
+    ids, d, _ = s.search(Q, 10, 2, prune=False, detail=False)
+    assert np.all(np.diff(d, axis=1)[np.isfinite(np.diff(d, axis=1))] >= 0)
+    # k larger than everything scanned -> padded with -1 / +inf
+    ids, d, info = s.search(Q, 128, 1, prune=False)
+    for qi in range(5):
+        n = info["scanned"][qi]
+        assert np.all(ids[qi, n:] == -1) and np.all(np.isinf(d[qi, n:])) and np.all(ids[qi, :n] >= 0)
+
+
+@pytest.mark.parametrize("B", [1, 3])
+def test_pruned_equals_unpruned_when_no_winner_is_dropped(B):
+    X, Q, ix = _tiny(n=4000, nq=40, B=B)
+    s = search.Searcher(ix)
+    a, da, ia = s.search(Q, 10, 6, prune=True)
+    b, db, _ = s.search(Q, 10, 6, prune=False)
+    ok = ia["dropped"] == 0
+    assert ok.mean() > 0.8
+    assert np.array_equal(a[ok], b[ok]) and np.array_equal(da[ok], db[ok])
+    if B == 1:
+        assert ok.all()            # filtering the ranking key itself never drops a winner
+    assert np.all(ia["survivors"] <= ia["scanned"])
+    # tau is a valid upper bound of the final k-th key
+    assert np.all(db[:, -1] <= ia["tau"] * (1 + 1e-12) + 1e-12)
+
+
+def test_ip_metric_search_orders_by_inner_product():
+    w = synth.WORKLOADS["ip_768"].scaled(n=1200, nq=12, n_centres=8)
+    X, Q = synth.make_base(w)[:, :128].copy(), synth.make_queries(w)[:, :128].copy()
+    X /= np.linalg.norm(X, axis=1, keepdims=True); Q /= np.linalg.norm(Q, axis=1, keepdims=True)
+    ix = build.build_index(X, 8, 8, metric="ip")
+    s = search.Searcher(ix)
+    ids, d, _ = s.search(Q, 10, 8, prune=False)
+    gt, gs = exact.exact_knn(X, Q, 10, "ip")
+    assert exact.recall_at_k(ids, gt) >= 0.95
+    assert np.all(np.diff(d, axis=1) <= 0)
+    assert np.abs(d[:, 0] - gs[:, 0]).max() < 0.02
