@@ -1,0 +1,190 @@
+/*
+ * rabitq.h — C ABI of the MI355X (gfx950) IVF-RaBitQ batched-search library.
+ *
+ * The calls follow the paper's problem statement (Section 2.1: a batch of
+ * queries Q in R^{nq x D}, return the K approximate nearest neighbours of each
+ * among N indexed vectors) and its search pipeline (Section 3.3).  All entry
+ * points are plain C: pointers, sizes and an opaque handle.  No entry point
+ * throws or aborts; each returns RABITQ_OK (0) or a negative rabitq_status, and
+ * rabitq_last_error() describes the last failure of the calling thread.
+ *
+ * Pointer kinds are stated per argument: "host" = ordinary host memory,
+ * "device" = memory of the current HIP device (for example the data_ptr() of a
+ * torch tensor).  `stream` is a hipStream_t passed as void* (NULL = the default
+ * stream).  Unless stated otherwise a call only enqueues work on `stream` and
+ * returns; outputs are valid once the caller has synchronised the stream.
+ * A handle supports one in-flight rabitq_search at a time (the workspace it owns
+ * is reused); the stage-level calls use only caller-provided buffers.
+ */
+#ifndef RABITQ_H
+#define RABITQ_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define RABITQ_TILE 64        /* vectors per tile of the code layout (one wavefront)   */
+#define RABITQ_MAX_K 128      /* largest supported K                                    */
+#define RABITQ_QUERY_BITS 4   /* B_q of the bitwise scheme (Section 3.4.1(2))           */
+#define RABITQ_MAX_NPROBE 1024
+
+typedef enum {
+  RABITQ_OK = 0,
+  RABITQ_EINVAL = -1, /* null pointer, size out of range, dim not a multiple of 32 ... */
+  RABITQ_ENOMEM = -2, /* device or host allocation failed                              */
+  RABITQ_EHIP = -3    /* a HIP runtime call or kernel launch failed                    */
+} rabitq_status;
+
+typedef enum { RABITQ_L2 = 0, RABITQ_IP = 1 } rabitq_metric;
+
+typedef struct rabitq_index* rabitq_index_t; /* opaque; owns device copies of the index */
+
+/*
+ * Index description (Section 3.4.3: flattened CSR-like arrays, one offset array
+ * shared by all of them).  All pointers are HOST pointers owned by the caller;
+ * rabitq_index_upload copies them and the caller may free them afterwards.
+ *
+ * Interleaving unit: the paper interleaves the packed 1-bit words of a whole
+ * cluster per 32-dimension group; here the unit is a tile of 64 vectors (one
+ * wavefront).  Cluster c holds n_c = offsets[c+1]-offsets[c] vectors in
+ * ceil(n_c/64) tiles; tiles of consecutive clusters follow each other, and the
+ * slot of the j-th vector of cluster c is 64*first_tile(c) + j.  Slots past n_c
+ * in the last tile of a cluster are padding: code words 0, f_add = +inf, other
+ * factors 0, id = -1.  n_tiles = sum_c ceil(n_c/64), n_slots = 64*n_tiles.
+ * W = dim/32.  Bit i (LSB = 0) of word w is dimension 32*w+i, for codes and for
+ * query bit-planes alike.
+ */
+typedef struct {
+  int32_t dim;        /* D, multiple of 32, 32..2048                                   */
+  int32_t nlist;      /* n_k, number of inverted lists                                 */
+  int64_t n;          /* N, number of stored vectors                                   */
+  int32_t total_bits; /* B in 1..8: 1 sign bit + (B-1) ex bits per dimension           */
+  int32_t metric;     /* rabitq_metric                                                 */
+  const float* rotation;      /* [D*D] row-major P; rotated query q' = q P             */
+  const float* centroids;     /* [nlist*D] rotated centroids c'                         */
+  const int64_t* offsets;     /* [nlist+1] CSR over stored vectors, offsets[nlist]==n   */
+  const uint32_t* short_codes;  /* [n_tiles][W][64]  1-bit (sign) codes                 */
+  const float* short_factors;   /* [n_tiles][3][64]  f_add, f_rescale, f_err planes     */
+  const uint32_t* long_codes;   /* [n_slots][D*F/32] low F bits of each code, F-bit
+                                   little-endian fields, F = B-1 rounded up to 1,2,4,8;
+                                   NULL when B == 1                                     */
+  const float* long_factors;    /* [n_slots][2] f_add, f_rescale of the B-bit code;
+                                   NULL when B == 1                                     */
+  const int32_t* ids;           /* [n_slots] original id (Pid) of each stored vector    */
+} rabitq_index_desc;
+
+/* Estimator read by the search (Section 2.2 leaves the expressions to an external
+ * document; these follow from Eq. (1)-(3)).  With G the coarse term of the probed
+ * cluster (L2: ||q'-c'||^2, IP: -<q',c'>), E = ||q'-c'||, the 4-bit query qhat with
+ * scale delta and S = sum(qhat), and I = <x_b, qhat> by AND+popcount:
+ *   est1 = G + f_add1 + f_rescale1 * delta * (2I - S)/2,   lb1 = est1 - f_err1 * E
+ *   estB = G + f_addB + f_rescaleB * (<u, q'> - (2^B-1)/2 * sum(q'))
+ * Keys are "smaller is better" for both metrics (IP keys are negated products). */
+
+/* Copies the index to the current device.  Synchronises `stream` before returning.
+ * Errors: RABITQ_EINVAL (null pointer, bad dim/bits/metric, offsets not monotone or
+ * offsets[nlist] != n), RABITQ_ENOMEM, RABITQ_EHIP.  *out is untouched on error. */
+int rabitq_index_upload(const rabitq_index_desc* desc, rabitq_index_t* out, void* stream);
+
+/* Frees the handle and everything it owns (device-synchronising).  NULL is allowed. */
+int rabitq_index_free(rabitq_index_t index);
+
+/*
+ * Batched search (Sections 2.1, 3.3).
+ *   queries   device, [nq*D] fp32 row-major, unrotated
+ *   out_ids   device, [nq*k] int64: original ids, best first; -1 where fewer than k
+ *             candidates survived
+ *   out_dists device, [nq*k] fp32: L2 -> estimated squared distance ascending (not
+ *             clamped at 0); IP -> estimated inner product descending; +inf / -inf
+ *             beside id -1
+ * The handle's workspace grows on demand (growth synchronises the device).
+ * Errors: RABITQ_EINVAL (null pointer with nq > 0, nq < 0, k < 1 or k > RABITQ_MAX_K,
+ * nprobe < 1 or > min(nlist, RABITQ_MAX_NPROBE)), RABITQ_ENOMEM, RABITQ_EHIP.
+ * nq == 0 succeeds and does nothing.
+ */
+int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
+                  int64_t* out_ids, float* out_dists, void* stream);
+
+/* Options (host call, takes effect for later searches):
+ *   "prune"  1 (default): filter with the per-query seeded threshold (Section 3.3.4);
+ *            0: refine every vector of every probed cluster (the unpruned definition).
+ * Errors: RABITQ_EINVAL for an unknown name or value. */
+int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
+
+/* Host-visible sizes of an uploaded index: name in {"n_tiles","n_slots","dim","nlist",
+ * "total_bits","long_field_bits","metric"}.  Returns the value, or a negative status. */
+int64_t rabitq_index_info(rabitq_index_t index, const char* name);
+
+/* Duration in milliseconds of each stage of the LAST rabitq_search that ran with the
+ * option "profile" = 1 (HIP events on the caller's stream; the call then synchronises).
+ * out_ms: host, [8]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
+ * scan, merge.  Errors: RABITQ_EINVAL. */
+int rabitq_last_stage_ms(rabitq_index_t index, float* out_ms);
+
+/* ---- Stage-level entry points: the same kernels rabitq_search chains, with every
+ * buffer supplied by the caller (device pointers).  They exist so that each stage can
+ * be checked and profiled with the previous stage's reference output injected. ---- */
+
+/* Section 3.3.1: q_rot [nq*D] = queries [nq*D] x P (fp32 MFMA). */
+int rabitq_rotate(rabitq_index_t index, const float* queries, int64_t nq, float* q_rot, void* stream);
+
+/* Section 3.3.3 / 3.4.1(2): per-query representation, computed once per query.
+ *   planes   [nq][4][W] u32 two's-complement bit-planes of qhat (plane 3 weighs -8)
+ *   delta    [nq] fp32  = max|q'|/7 (1 if q' == 0);  qhat = clamp(rint(q'/delta),-7,7)
+ *   sum_qhat [nq] i32   = S;   sum_q [nq] fp32 = sum(q');   sq_norm [nq] fp32 = ||q'||^2 */
+int rabitq_query_prep(rabitq_index_t index, const float* q_rot, int64_t nq, uint32_t* planes, float* delta,
+                      int32_t* sum_qhat, float* sum_q, float* sq_norm, void* stream);
+
+/* Section 3.3.2: coarse scores by one GEMM (s_q 1^T + 1 s_c^T - 2 Q'C^T for L2, -Q'C^T
+ * for IP) and the nprobe best clusters per query, best first, ties to the lower id.
+ *   scores    [nq*nlist] fp32 scratch (the full score matrix)
+ *   probe_ids [nq*nprobe] i32, probe_G [nq*nprobe] fp32 (the score), probe_E fp32 (||q'-c'||) */
+int rabitq_coarse_probe(rabitq_index_t index, const float* q_rot, const float* sq_norm, int64_t nq,
+                        int32_t nprobe, float* scores, int32_t* probe_ids, float* probe_G, float* probe_E,
+                        void* stream);
+
+/* Section 3.3.3: regroup the (query, cluster) pairs by cluster (stable in query id).
+ *   pair_off [nlist+1] i32: pairs of cluster c are pair_ids[pair_off[c] .. pair_off[c+1])
+ *   pair_ids [nq*nprobe] i32: pair p = query*nprobe + rank
+ *   scratch  u32, at least rabitq_probe_list_scratch_words(nlist, nq) words */
+int64_t rabitq_probe_list_scratch_words(int32_t nlist, int64_t nq);
+int rabitq_build_probe_lists(rabitq_index_t index, const int32_t* probe_ids, int64_t nq, int32_t nprobe,
+                             int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, void* stream);
+
+/* Section 3.3.4 threshold: tau [nq] fp32.  In the query's nearest probed cluster with at
+ * least k vectors, the k smallest 1-bit estimates (ties: lower position) are refined and
+ * tau is the largest refined estimate (B == 1: the k-th smallest 1-bit estimate);
+ * FLT_MAX when no probed cluster has k vectors. */
+int rabitq_seed_threshold(rabitq_index_t index, const float* q_rot, const uint32_t* planes, const float* delta,
+                          const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids,
+                          const float* probe_G, const float* probe_E, int64_t nq, int32_t k, int32_t nprobe,
+                          float* tau, void* stream);
+
+/* Sections 3.3.4, 3.4.1(2), 3.4.2: the fused cluster-local search over all pairs.
+ * For every pair: 1-bit estimate of every vector of the cluster by AND+popcount, filter
+ * (B > 1: lb1 <= tau, B == 1: est1 <= tau), refinement of survivors, cluster-local top-k.
+ *   tau        [nq] fp32 (pass FLT_MAX everywhere to disable the filter)
+ *   cand_keys  [nq*nprobe*k] u64: (order-preserving bits of the key << 32) | id
+ *   cand_cnt   [nq*nprobe] i32: valid entries of each pair's k-slot region (unsorted)
+ *   dbg_ip     optional (may be NULL) [sum over pairs, in pair_ids order, of 64*tiles(c)] i32:
+ *              raw integer <x_b, qhat> of every slot; dbg_off [nq*nprobe+1] i64 gives each
+ *              pair's first entry (indexed by position in pair_ids).  For small inputs. */
+int rabitq_scan(rabitq_index_t index, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+                const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int32_t k,
+                int32_t nprobe, uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off,
+                void* stream);
+
+/* Section 3.3.5: per-query merge of the nprobe local lists into the final top-k. */
+int rabitq_merge(rabitq_index_t index, const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int32_t k,
+                 int32_t nprobe, int64_t* out_ids, float* out_dists, void* stream);
+
+/* Text of the last error raised on the calling thread ("" if none). */
+const char* rabitq_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RABITQ_H */

@@ -96,7 +96,7 @@ def assign_clusters(X: np.ndarray, C: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------
 # Exact RaBitQ B-bit code of a rotated unit vector (Section 2.2, Eq. (3))
 # --------------------------------------------------------------------------
-def encode_unit(o_rot: np.ndarray, B: int, chunk: int = 2048) -> np.ndarray:
+def encode_unit(o_rot: np.ndarray, B: int, chunk: int | None = None) -> np.ndarray:
     """Codes ``u`` [n, D] uint8 maximising ``<u - c_B, o'> / ||u - c_B||``.
 
     Follows the critical-rescaling-factor enumeration the paper recalls in
@@ -113,6 +113,8 @@ def encode_unit(o_rot: np.ndarray, B: int, chunk: int = 2048) -> np.ndarray:
     L = half - 1
     m = np.zeros((n, D), dtype=np.int64)
     if L > 0:
+        if chunk is None:
+            chunk = max(16, int(4_000_000 // (D * L)))  # bounds the [chunk, D*L] work arrays
         k = np.arange(1, L + 1, dtype=np.float64)
         dden = np.tile(2.0 * k, D)  # event e = i*L + (k-1)
         for s in range(0, n, chunk):
@@ -188,11 +190,7 @@ def vector_factors(x: np.ndarray, o_rot: np.ndarray, c_rot: np.ndarray,
         f[:, 2] = r * eps0 * spread
     else:
         raise ValueError(metric)
-    if metric == "l2":
-        f[~ok] = 0.0
-    else:
-        f[~ok, 1:] = 0.0
-        f[~ok, 0] = 0.0  # o_r == c  =>  <c, o_r - c> = 0
+    f[~ok] = 0.0  # o_r == c: every term vanishes (for IP, <c, o_r - c> = 0 too)
     return f
 
 

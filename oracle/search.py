@@ -176,11 +176,12 @@ class Searcher:
             return float(np.max(self.refined(s, e, G, qr, sel)))
         return FLT_MAX
 
-    def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False):
+    def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False, tau=None):
         """Returns (ids [nq,k] i64, dists [nq,k] f64, info).  ``prune=False`` is
         the unpruned definition (every vector of every probed cluster is ranked by
         its final key).  ``info`` holds per-query tau, survivor counts, the probe
-        lists, and the count of unpruned top-k members the filter would drop."""
+        lists, and the count of unpruned top-k members the filter would drop.
+        ``tau`` (optional [nq]) replaces the seeded thresholds (used by stage tests)."""
         ix = self.ix
         if Qr is None:
             Qr = rotate_queries(Q, ix["P"])
@@ -197,8 +198,11 @@ class Searcher:
             qr = Qr[qi]
             delta, qhat, S = quantize_query(qr)
             planes = query_bitplanes(qhat)
-            tau = self.seed_threshold(probes[qi], G[qi], E[qi], qr, delta, planes, S, k)
-            taus[qi] = tau
+            if tau is None:
+                tau_q = self.seed_threshold(probes[qi], G[qi], E[qi], qr, delta, planes, S, k)
+            else:
+                tau_q = float(tau[qi])
+            taus[qi] = tau_q
             keys_all, ids_all, filt_all = [], [], []
             for j in range(nprobe):
                 c = int(probes[qi, j])
@@ -217,7 +221,7 @@ class Searcher:
             else:
                 keys = np.zeros(0); ids = np.zeros(0, np.int64); filt = np.zeros(0)
             n_scanned[qi] = keys.shape[0]
-            surv = filt <= tau
+            surv = filt <= tau_q
             n_surv[qi] = int(surv.sum())
             fk, fi = topk_pairs(keys, ids, k)            # unpruned definition
             pk, pi = topk_pairs(keys[surv], ids[surv], k)  # with the filter
@@ -226,7 +230,7 @@ class Searcher:
             out_ids[qi, :len(ri)] = ri
             out_d[qi, :len(rk)] = rk
             if detail:
-                details.append(dict(keys=keys, ids=ids, filt=filt, tau=tau))
+                details.append(dict(keys=keys, ids=ids, filt=filt, tau=tau_q))
         if self.metric == "ip":
             out_d = -out_d
         info = dict(tau=taus, scanned=n_scanned, survivors=n_surv, dropped=dropped,

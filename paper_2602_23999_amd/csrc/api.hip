@@ -1,0 +1,387 @@
+// C ABI of librabitq_hip.so: handle management, argument checks, workspace, and the
+// chaining of the stage kernels on the caller's stream.
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "rq_internal.h"
+
+namespace rq {
+
+static thread_local std::string g_err;
+
+void set_error(const std::string& s) { g_err = s; }
+
+int hip_fail(hipError_t e, const char* what) {
+  g_err = std::string(what) + ": " + hipGetErrorString(e);
+  return RABITQ_EHIP;
+}
+
+static int field_bits_of(int B) {
+  const int ex = B - 1;
+  if (ex <= 0) return 0;
+  if (ex <= 1) return 1;
+  if (ex <= 2) return 2;
+  if (ex <= 4) return 4;
+  return 8;
+}
+
+template <typename T>
+static int dev_alloc(T** p, int64_t count) {
+  *p = nullptr;
+  if (count <= 0) count = 1;
+  hipError_t e = hipMalloc(reinterpret_cast<void**>(p), (size_t)count * sizeof(T));
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    set_error("hipMalloc failed: " + std::string(hipGetErrorString(e)));
+    return RABITQ_ENOMEM;
+  }
+  return RABITQ_OK;
+}
+
+template <typename T>
+static void dev_free(T*& p) {
+  if (p) (void)hipFree(p);
+  p = nullptr;
+}
+
+static void free_workspace(Workspace& w) {
+  dev_free(w.q_rot); dev_free(w.planes); dev_free(w.delta); dev_free(w.sum_qhat); dev_free(w.sum_q);
+  dev_free(w.sq_norm); dev_free(w.tau); dev_free(w.scores); dev_free(w.probe_ids); dev_free(w.probe_G);
+  dev_free(w.probe_E); dev_free(w.pair_off); dev_free(w.pair_ids); dev_free(w.list_scratch);
+  dev_free(w.cand_keys); dev_free(w.cand_cnt);
+  w.cap_nq = w.cap_pairs = w.cap_cand = w.cap_scratch = 0;
+}
+
+static void free_index(rabitq_index* ix) {
+  if (!ix) return;
+  dev_free(ix->rotation); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off);
+  dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
+  dev_free(ix->long_factors); dev_free(ix->ids);
+  free_workspace(ix->ws);
+  for (auto& e : ix->ev)
+    if (e) (void)hipEventDestroy(e);
+  delete ix;
+}
+
+// Grow the handle's workspace for (nq, nprobe, k).  Growth frees and reallocates
+// (device-synchronising); steady-state calls allocate nothing.
+static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
+  Workspace& w = ix->ws;
+  const int64_t pairs = nq * nprobe;
+  const int64_t cand = pairs * k;
+  const int64_t scratch = probe_list_scratch_words(ix->nlist, nq);
+  if (nq <= w.cap_nq && pairs <= w.cap_pairs && cand <= w.cap_cand && scratch <= w.cap_scratch) return RABITQ_OK;
+  hipError_t e = hipDeviceSynchronize();
+  if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
+  const int64_t c_nq = std::max(nq, w.cap_nq), c_pairs = std::max(pairs, w.cap_pairs);
+  const int64_t c_cand = std::max(cand, w.cap_cand), c_scr = std::max(scratch, w.cap_scratch);
+  free_workspace(w);
+  int rc;
+#define RQ_A(ptr, cnt) if ((rc = dev_alloc(&(ptr), (cnt))) != RABITQ_OK) { free_workspace(w); return rc; }
+  RQ_A(w.q_rot, c_nq * ix->dim);
+  RQ_A(w.planes, c_nq * 4 * ix->W);
+  RQ_A(w.delta, c_nq);
+  RQ_A(w.sum_qhat, c_nq);
+  RQ_A(w.sum_q, c_nq);
+  RQ_A(w.sq_norm, c_nq);
+  RQ_A(w.tau, c_nq);
+  RQ_A(w.scores, c_nq * ix->nlist);
+  RQ_A(w.probe_ids, c_pairs);
+  RQ_A(w.probe_G, c_pairs);
+  RQ_A(w.probe_E, c_pairs);
+  RQ_A(w.pair_off, ix->nlist + 1);
+  RQ_A(w.pair_ids, c_pairs);
+  RQ_A(w.list_scratch, c_scr);
+  RQ_A(w.cand_keys, c_cand);
+  RQ_A(w.cand_cnt, c_pairs);
+#undef RQ_A
+  w.cap_nq = c_nq; w.cap_pairs = c_pairs; w.cap_cand = c_cand; w.cap_scratch = c_scr;
+  return RABITQ_OK;
+}
+
+}  // namespace rq
+
+using namespace rq;
+
+extern "C" {
+
+const char* rabitq_last_error(void) { return g_err.c_str(); }
+
+int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* stream) {
+  if (!d || !out) { set_error("upload: null argument"); return RABITQ_EINVAL; }
+  if (d->dim < 32 || d->dim > 2048 || (d->dim % 32) != 0) { set_error("upload: dim must be a multiple of 32 in 32..2048"); return RABITQ_EINVAL; }
+  if (d->nlist < 1 || d->n < 0) { set_error("upload: bad nlist or n"); return RABITQ_EINVAL; }
+  if (d->total_bits < 1 || d->total_bits > 8) { set_error("upload: total_bits must be 1..8"); return RABITQ_EINVAL; }
+  if (d->metric != RABITQ_L2 && d->metric != RABITQ_IP) { set_error("upload: bad metric"); return RABITQ_EINVAL; }
+  if (!d->rotation || !d->centroids || !d->offsets || !d->short_codes || !d->short_factors || !d->ids) {
+    set_error("upload: null array"); return RABITQ_EINVAL;
+  }
+  if (d->total_bits > 1 && (!d->long_codes || !d->long_factors)) { set_error("upload: long arrays required when total_bits > 1"); return RABITQ_EINVAL; }
+  const int D = d->dim, nlist = d->nlist, W = D / 32;
+  if (d->offsets[0] != 0 || d->offsets[nlist] != d->n) { set_error("upload: offsets[0] must be 0 and offsets[nlist] == n"); return RABITQ_EINVAL; }
+  std::vector<int32_t> tile_off(nlist + 1), csize(nlist);
+  int64_t tiles = 0;
+  for (int c = 0; c < nlist; ++c) {
+    const int64_t nc = d->offsets[c + 1] - d->offsets[c];
+    if (nc < 0 || nc > 0x7fffffff) { set_error("upload: offsets not monotone"); return RABITQ_EINVAL; }
+    tile_off[c] = (int32_t)tiles;
+    csize[c] = (int32_t)nc;
+    tiles += (nc + TILE - 1) / TILE;
+    if (tiles > (0x7fffffff / TILE)) { set_error("upload: too many slots for 32-bit slot indices"); return RABITQ_EINVAL; }
+  }
+  tile_off[nlist] = (int32_t)tiles;
+
+  rabitq_index* ix = new (std::nothrow) rabitq_index();
+  if (!ix) { set_error("upload: out of host memory"); return RABITQ_ENOMEM; }
+  ix->dim = D; ix->W = W; ix->nlist = nlist; ix->n = d->n; ix->total_bits = d->total_bits; ix->metric = d->metric;
+  ix->F = field_bits_of(d->total_bits);
+  ix->LW = D * ix->F / 32;
+  ix->n_tiles = tiles; ix->n_slots = tiles * TILE;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  int rc = RABITQ_OK;
+  hipError_t he = hipGetDevice(&ix->device);
+  if (he != hipSuccess) { rc = hip_fail(he, "hipGetDevice"); free_index(ix); return rc; }
+
+  // transposed centroids [D][nlist] and their squared norms
+  std::vector<float> ct((size_t)D * nlist), csq(nlist);
+  for (int c = 0; c < nlist; ++c) {
+    double s = 0.0;
+    for (int i = 0; i < D; ++i) {
+      const float v = d->centroids[(size_t)c * D + i];
+      ct[(size_t)i * nlist + c] = v;
+      s += (double)v * (double)v;
+    }
+    csq[c] = (float)s;
+  }
+#define RQ_UP(dst, src, cnt, T)                                                                     \
+  if (rc == RABITQ_OK) rc = dev_alloc(&(dst), (int64_t)(cnt));                                       \
+  if (rc == RABITQ_OK && (cnt) > 0) {                                                                \
+    he = hipMemcpyAsync((dst), (src), (size_t)(cnt) * sizeof(T), hipMemcpyHostToDevice, st);         \
+    if (he != hipSuccess) rc = hip_fail(he, "hipMemcpyAsync");                                       \
+  }
+  RQ_UP(ix->rotation, d->rotation, (int64_t)D * D, float);
+  RQ_UP(ix->centroids_t, ct.data(), (int64_t)D * nlist, float);
+  RQ_UP(ix->centroid_sq, csq.data(), nlist, float);
+  if (rc == RABITQ_OK) rc = dev_alloc(&ix->tile_off, 2 * (int64_t)(nlist + 1));  // second half: scan work-item offsets
+  if (rc == RABITQ_OK) {
+    he = hipMemcpyAsync(ix->tile_off, tile_off.data(), (size_t)(nlist + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st);
+    if (he != hipSuccess) rc = hip_fail(he, "hipMemcpyAsync");
+  }
+  RQ_UP(ix->cluster_size, csize.data(), nlist, int32_t);
+  RQ_UP(ix->short_codes, d->short_codes, tiles * W * TILE, uint32_t);
+  RQ_UP(ix->short_factors, d->short_factors, tiles * 3 * TILE, float);
+  RQ_UP(ix->ids, d->ids, tiles * TILE, int32_t);
+  if (d->total_bits > 1) {
+    RQ_UP(ix->long_codes, d->long_codes, tiles * TILE * ix->LW, uint32_t);
+    RQ_UP(ix->long_factors, d->long_factors, tiles * TILE * 2, float);
+  }
+#undef RQ_UP
+  if (rc == RABITQ_OK) {
+    he = hipStreamSynchronize(st);  // host staging vectors die at return
+    if (he != hipSuccess) rc = hip_fail(he, "hipStreamSynchronize");
+  } else {
+    (void)hipStreamSynchronize(st);
+  }
+  if (rc != RABITQ_OK) { free_index(ix); return rc; }
+  *out = ix;
+  return RABITQ_OK;
+}
+
+int rabitq_index_free(rabitq_index_t ix) {
+  if (!ix) return RABITQ_OK;
+  (void)hipDeviceSynchronize();
+  free_index(ix);
+  return RABITQ_OK;
+}
+
+int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
+  if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
+  if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "profile") && (value == 0 || value == 1)) {
+    if (value == 1 && !ix->ev[0]) {
+      for (auto& e : ix->ev) RQ_HIP(hipEventCreate(&e));
+    }
+    ix->profile = (int)value;
+    return RABITQ_OK;
+  }
+  set_error("set_option: unknown option or value");
+  return RABITQ_EINVAL;
+}
+
+int64_t rabitq_index_info(rabitq_index_t ix, const char* name) {
+  if (!ix || !name) { set_error("index_info: null argument"); return RABITQ_EINVAL; }
+  if (!std::strcmp(name, "n_tiles")) return ix->n_tiles;
+  if (!std::strcmp(name, "n_slots")) return ix->n_slots;
+  if (!std::strcmp(name, "dim")) return ix->dim;
+  if (!std::strcmp(name, "nlist")) return ix->nlist;
+  if (!std::strcmp(name, "total_bits")) return ix->total_bits;
+  if (!std::strcmp(name, "long_field_bits")) return ix->F;
+  if (!std::strcmp(name, "metric")) return ix->metric;
+  set_error("index_info: unknown name");
+  return RABITQ_EINVAL;
+}
+
+int rabitq_last_stage_ms(rabitq_index_t ix, float* out_ms) {
+  if (!ix || !out_ms) { set_error("last_stage_ms: null argument"); return RABITQ_EINVAL; }
+  for (int i = 0; i < 8; ++i) out_ms[i] = ix->stage_ms[i];
+  return RABITQ_OK;
+}
+
+static int check_common(rabitq_index_t ix, int64_t nq, const char* who) {
+  if (!ix) { set_error(std::string(who) + ": null index"); return RABITQ_EINVAL; }
+  if (nq < 0) { set_error(std::string(who) + ": nq < 0"); return RABITQ_EINVAL; }
+  return RABITQ_OK;
+}
+
+static int check_k_nprobe(rabitq_index_t ix, int k, int nprobe, const char* who) {
+  if (k < 1 || k > RABITQ_MAX_K) { set_error(std::string(who) + ": k must be in 1..128"); return RABITQ_EINVAL; }
+  if (nprobe < 1 || nprobe > ix->nlist || nprobe > RABITQ_MAX_NPROBE) {
+    set_error(std::string(who) + ": nprobe must be in 1..min(nlist,1024)");
+    return RABITQ_EINVAL;
+  }
+  return RABITQ_OK;
+}
+
+int rabitq_rotate(rabitq_index_t ix, const float* queries, int64_t nq, float* q_rot, void* stream) {
+  int rc = check_common(ix, nq, "rotate");
+  if (rc) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!queries || !q_rot) { set_error("rotate: null pointer"); return RABITQ_EINVAL; }
+  return launch_gemm(queries, ix->rotation, q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int rabitq_query_prep(rabitq_index_t ix, const float* q_rot, int64_t nq, uint32_t* planes, float* delta,
+                      int32_t* sum_qhat, float* sum_q, float* sq_norm, void* stream) {
+  int rc = check_common(ix, nq, "query_prep");
+  if (rc) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !sq_norm) { set_error("query_prep: null pointer"); return RABITQ_EINVAL; }
+  return launch_query_prep(q_rot, nq, ix->dim, planes, delta, sum_qhat, sum_q, sq_norm, (hipStream_t)stream);
+}
+
+int rabitq_coarse_probe(rabitq_index_t ix, const float* q_rot, const float* sq_norm, int64_t nq, int32_t nprobe,
+                        float* scores, int32_t* probe_ids, float* probe_G, float* probe_E, void* stream) {
+  int rc = check_common(ix, nq, "coarse_probe");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, 1, nprobe, "coarse_probe"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!q_rot || !sq_norm || !scores || !probe_ids || !probe_G || !probe_E) { set_error("coarse_probe: null pointer"); return RABITQ_EINVAL; }
+  hipStream_t st = (hipStream_t)stream;
+  rc = launch_gemm(q_rot, ix->centroids_t, scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2, sq_norm,
+                   ix->centroid_sq, st);
+  if (rc) return rc;
+  return launch_select_probes(scores, sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, probe_ids, probe_G,
+                              probe_E, st);
+}
+
+int64_t rabitq_probe_list_scratch_words(int32_t nlist, int64_t nq) {
+  if (nlist < 1 || nq < 0) return RABITQ_EINVAL;
+  return probe_list_scratch_words(nlist, nq);
+}
+
+int rabitq_build_probe_lists(rabitq_index_t ix, const int32_t* probe_ids, int64_t nq, int32_t nprobe,
+                             int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, void* stream) {
+  int rc = check_common(ix, nq, "build_probe_lists");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, 1, nprobe, "build_probe_lists"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!probe_ids || !pair_off || !pair_ids || !scratch) { set_error("build_probe_lists: null pointer"); return RABITQ_EINVAL; }
+  if (nq * nprobe > 0x7fffffff) { set_error("build_probe_lists: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
+  return launch_build_lists(probe_ids, nq, nprobe, ix->nlist, pair_off, pair_ids, scratch, (hipStream_t)stream);
+}
+
+int rabitq_seed_threshold(rabitq_index_t ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                          const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids,
+                          const float* probe_G, const float* probe_E, int64_t nq, int32_t k, int32_t nprobe,
+                          float* tau, void* stream) {
+  int rc = check_common(ix, nq, "seed_threshold");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "seed_threshold"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !probe_ids || !probe_G || !probe_E || !tau) {
+    set_error("seed_threshold: null pointer"); return RABITQ_EINVAL;
+  }
+  return launch_seed(ix, q_rot, planes, delta, sum_qhat, sum_q, probe_ids, probe_G, probe_E, nq, k, nprobe, tau,
+                     (hipStream_t)stream);
+}
+
+int rabitq_scan(rabitq_index_t ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+                const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int32_t k,
+                int32_t nprobe, uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off,
+                void* stream) {
+  int rc = check_common(ix, nq, "scan");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "scan"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !probe_G || !probe_E || !pair_off || !pair_ids || !tau ||
+      !cand_keys || !cand_cnt || (dbg_ip && !dbg_off)) {
+    set_error("scan: null pointer"); return RABITQ_EINVAL;
+  }
+  if (nq * nprobe > 0x7fffffff) { set_error("scan: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
+  return launch_scan(ix, q_rot, planes, delta, sum_qhat, sum_q, probe_G, probe_E, pair_off, pair_ids, tau, nq, k,
+                     nprobe, cand_keys, cand_cnt, dbg_ip, dbg_off, (hipStream_t)stream);
+}
+
+int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int32_t k,
+                 int32_t nprobe, int64_t* out_ids, float* out_dists, void* stream) {
+  int rc = check_common(ix, nq, "merge");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "merge"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!cand_keys || !cand_cnt || !out_ids || !out_dists) { set_error("merge: null pointer"); return RABITQ_EINVAL; }
+  return launch_merge(cand_keys, cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, (hipStream_t)stream);
+}
+
+int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
+                  float* out_dists, void* stream) {
+  int rc = check_common(ix, nq, "search");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "search"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!queries || !out_ids || !out_dists) { set_error("search: null pointer"); return RABITQ_EINVAL; }
+  if (nq * nprobe > 0x7fffffff) { set_error("search: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
+  if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
+  Workspace& w = ix->ws;
+  hipStream_t st = (hipStream_t)stream;
+  const bool prof = ix->profile != 0;
+  int stage = 0;
+#define RQ_MARK() do { if (prof) RQ_HIP(hipEventRecord(ix->ev[stage++], st)); } while (0)
+#define RQ_RUN(call) do { if ((rc = (call)) != RABITQ_OK) return rc; } while (0)
+  RQ_MARK();
+  RQ_RUN(launch_gemm(queries, ix->rotation, w.q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, st));
+  RQ_MARK();
+  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, w.planes, w.delta, w.sum_qhat, w.sum_q, w.sq_norm, st));
+  RQ_MARK();
+  RQ_RUN(launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
+                     w.sq_norm, ix->centroid_sq, st));
+  RQ_MARK();
+  RQ_RUN(launch_select_probes(w.scores, w.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, w.probe_ids,
+                              w.probe_G, w.probe_E, st));
+  RQ_MARK();
+  RQ_RUN(launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, st));
+  RQ_MARK();
+  if (ix->prune) {
+    RQ_RUN(launch_seed(ix, w.q_rot, w.planes, w.delta, w.sum_qhat, w.sum_q, w.probe_ids, w.probe_G, w.probe_E, nq, k,
+                       nprobe, w.tau, st));
+  } else {
+    RQ_RUN(launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));
+  }
+  RQ_MARK();
+  RQ_RUN(launch_scan(ix, w.q_rot, w.planes, w.delta, w.sum_qhat, w.sum_q, w.probe_G, w.probe_E, w.pair_off, w.pair_ids,
+                     w.tau, nq, k, nprobe, w.cand_keys, w.cand_cnt, nullptr, nullptr, st));
+  RQ_MARK();
+  RQ_RUN(launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
+  RQ_MARK();
+#undef RQ_MARK
+#undef RQ_RUN
+  if (prof) {
+    RQ_HIP(hipEventSynchronize(ix->ev[8]));
+    for (int i = 0; i < 8; ++i) RQ_HIP(hipEventElapsedTime(&ix->stage_ms[i], ix->ev[i], ix->ev[i + 1]));
+  }
+  return RABITQ_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,197 @@
+// Device-side building blocks shared by the selection, seeding, scan and merge kernels.
+#pragma once
+#include "rq_internal.h"
+
+namespace rq {
+
+constexpr uint64_t KEY_NONE = ~0ull;
+
+__device__ inline uint64_t make_key(float v, uint32_t lo) { return ((uint64_t)f2ord(v) << 32) | lo; }
+
+// ---------------------------------------------------------------------------------
+// Bitonic sort (ascending) of n = 2^m u64 keys in LDS by the whole workgroup.
+// Ends with a barrier.
+// ---------------------------------------------------------------------------------
+__device__ inline void block_bitonic_sort(uint64_t* keys, int n) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      __syncthreads();
+      for (int t = tid; t < (n >> 1); t += nt) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const uint64_t a = keys[i], b = keys[l];
+        const bool up = (i & k) == 0;
+        if ((a > b) == up) {
+          keys[i] = b;
+          keys[l] = a;
+        }
+      }
+    }
+  }
+  __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------
+// Workgroup-wide selection of the K smallest of n u64 keys produced by key_at(i),
+// written in ascending order to out[0..Kpad) (Kpad = power of two >= K, the tail is
+// KEY_NONE).  Keys are expected to be distinct (their low word is an index or id), so
+// the result is unique.  MSB-first radix select, 8 bits per pass, stops as soon as the
+// bucket that holds the K-th key is taken whole.
+// sh: LDS scratch of at least 260 u32.  blockDim.x must be a multiple of 64.
+// ---------------------------------------------------------------------------------
+template <typename KeyFn>
+__device__ inline void block_select_smallest(int n, int K, int Kpad, KeyFn key_at, uint64_t* out, uint32_t* sh) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  uint32_t* hist = sh;              // [256]
+  uint32_t* s_digit = sh + 256;     // [1]
+  uint32_t* s_need = sh + 257;      // [1]
+  uint32_t* s_take_all = sh + 258;  // [1]
+  uint32_t* s_cnt = sh + 259;       // [1]
+  uint64_t bound = KEY_NONE;        // select keys <= bound
+  if (n > K) {
+    uint64_t prefix = 0;
+    uint32_t need = (uint32_t)K;
+    for (int shift = 56; shift >= 0; shift -= 8) {
+      for (int i = tid; i < 256; i += nt) hist[i] = 0;
+      __syncthreads();
+      const uint64_t hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
+      for (int i = tid; i < n; i += nt) {
+        const uint64_t key = key_at(i);
+        if ((key & hi_mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+      }
+      __syncthreads();
+      if (tid < 64) {
+        const uint32_t c0 = hist[4 * tid], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
+        const uint32_t s = c0 + c1 + c2 + c3;
+        uint32_t incl = s;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+          const uint32_t o = __shfl_up(incl, d, 64);
+          if (tid >= d) incl += o;
+        }
+        const uint32_t excl = incl - s;
+        if (excl < need && need <= incl) {
+          uint32_t rem = need - excl, digit, cnt;
+          if (rem <= c0) { digit = 0; cnt = c0; }
+          else if (rem <= c0 + c1) { digit = 1; cnt = c1; rem -= c0; }
+          else if (rem <= c0 + c1 + c2) { digit = 2; cnt = c2; rem -= c0 + c1; }
+          else { digit = 3; cnt = c3; rem -= c0 + c1 + c2; }
+          *s_digit = 4 * tid + digit;
+          *s_need = rem;
+          *s_take_all = (cnt == rem) ? 1u : 0u;
+        }
+      }
+      __syncthreads();
+      prefix |= (uint64_t)(*s_digit) << shift;
+      need = *s_need;
+      const bool take_all = (*s_take_all) != 0u;
+      __syncthreads();
+      if (take_all || shift == 0) {
+        bound = prefix | (shift == 0 ? 0ull : ((1ull << shift) - 1ull));
+        break;
+      }
+    }
+  }
+  if (tid == 0) *s_cnt = 0;
+  for (int i = tid; i < Kpad; i += nt) out[i] = KEY_NONE;
+  __syncthreads();
+  for (int i = tid; i < n; i += nt) {
+    const uint64_t key = key_at(i);
+    if (key <= bound && key != KEY_NONE) {
+      const uint32_t pos = atomicAdd(s_cnt, 1u);
+      if (pos < (uint32_t)Kpad) out[pos] = key;
+    }
+  }
+  block_bitonic_sort(out, Kpad);
+}
+
+__host__ __device__ inline int next_pow2(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+// ---------------------------------------------------------------------------------
+// Section 3.4.1(2): <x_b, qhat> = -8 pc(x&q3) + 4 pc(x&q2) + 2 pc(x&q1) + pc(x&q0),
+// 32 dimensions per AND + popcount.  `pl` points at the query's planes [4][W]; it is
+// wave-uniform, so the compiler keeps the plane words in scalar registers.
+// ---------------------------------------------------------------------------------
+typedef const uint32_t __attribute__((address_space(4)))* const_u32_ptr;
+
+// popcount(x) + acc in one VALU instruction (the compiler otherwise splits the add off)
+__device__ inline uint32_t bcnt_acc(uint32_t x, uint32_t acc) {
+  uint32_t d;
+  asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(x), "v"(acc));
+  return d;
+}
+
+template <int W>
+__device__ inline int ip_bitplanes(const uint32_t (&cw)[W], const_u32_ptr pl) {
+  uint32_t p0 = 0, p1 = 0, p2 = 0, p3 = 0;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    p0 = bcnt_acc(cw[w] & pl[0 * W + w], p0);
+    p1 = bcnt_acc(cw[w] & pl[1 * W + w], p1);
+    p2 = bcnt_acc(cw[w] & pl[2 * W + w], p2);
+    p3 = bcnt_acc(cw[w] & pl[3 * W + w], p3);
+  }
+  return (int)(p0 + 2u * p1 + 4u * p2) - (int)(8u * p3);
+}
+
+// ---------------------------------------------------------------------------------
+// Refinement (Section 3.4.2: lanes cooperate on one candidate).  16 lanes share one
+// candidate; lane t (0..15) takes the 8-dimension groups t, t+16, ... and returns its
+// partial <u, q'>.  long_row: the candidate's long-code words; short_col: address of
+// the candidate's word 0 in its tile (words are 64 apart); qf: q' in LDS.
+// The field holds the low F bits of the code; when F < B the sign bit is OR-ed in.
+// ---------------------------------------------------------------------------------
+template <int F>
+__device__ inline float refine_partial(const uint32_t* __restrict__ long_row, const uint32_t* __restrict__ short_col,
+                                       const float* qf, int D, int B, int t) {
+  float acc = 0.f;
+  const bool need_msb = F < B;
+  for (int b = t; b < (D >> 3); b += 16) {
+    uint32_t v[8];
+    if (F == 4) {
+      const uint32_t w = long_row[b];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = (w >> (4 * k)) & 15u;
+    } else if (F == 2) {
+      const uint32_t w = long_row[b >> 1] >> (16 * (b & 1));
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = (w >> (2 * k)) & 3u;
+    } else if (F == 1) {
+      const uint32_t w = long_row[b >> 2] >> (8 * (b & 3));
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = (w >> k) & 1u;
+    } else {
+      const uint32_t w0 = long_row[2 * b], w1 = long_row[2 * b + 1];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        v[k] = (w0 >> (8 * k)) & 255u;
+        v[4 + k] = (w1 >> (8 * k)) & 255u;
+      }
+    }
+    if (need_msb) {
+      const uint32_t m = short_col[(b >> 2) * TILE] >> (8 * (b & 3));
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] |= ((m >> k) & 1u) << (B - 1);
+    }
+    const float4 qa = *reinterpret_cast<const float4*>(qf + 8 * b);
+    const float4 qb = *reinterpret_cast<const float4*>(qf + 8 * b + 4);
+    acc += (float)v[0] * qa.x + (float)v[1] * qa.y + (float)v[2] * qa.z + (float)v[3] * qa.w;
+    acc += (float)v[4] * qb.x + (float)v[5] * qb.y + (float)v[6] * qb.z + (float)v[7] * qb.w;
+  }
+  return acc;
+}
+
+__device__ inline float group16_sum(float v) {
+  v += __shfl_xor(v, 8, 16);
+  v += __shfl_xor(v, 4, 16);
+  v += __shfl_xor(v, 2, 16);
+  v += __shfl_xor(v, 1, 16);
+  return v;
+}
+
+}  // namespace rq

@@ -1,0 +1,112 @@
+// Internal declarations shared by the translation units of librabitq_hip.so.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "rabitq.h"
+
+namespace rq {
+
+constexpr int TILE = RABITQ_TILE;
+constexpr int QW = 4;        // queries handled by one scan wavefront
+constexpr int POOL = 256;    // per-(wave, query) candidate pool entries in LDS
+
+struct Workspace {
+  // per query
+  float* q_rot = nullptr;
+  uint32_t* planes = nullptr;
+  float* delta = nullptr;
+  int32_t* sum_qhat = nullptr;
+  float* sum_q = nullptr;
+  float* sq_norm = nullptr;
+  float* tau = nullptr;
+  // coarse
+  float* scores = nullptr;
+  int32_t* probe_ids = nullptr;
+  float* probe_G = nullptr;
+  float* probe_E = nullptr;
+  // lists
+  int32_t* pair_off = nullptr;
+  int32_t* pair_ids = nullptr;
+  uint32_t* list_scratch = nullptr;
+  // candidates
+  uint64_t* cand_keys = nullptr;
+  int32_t* cand_cnt = nullptr;
+  // capacities the buffers were sized for
+  int64_t cap_nq = 0;
+  int64_t cap_pairs = 0;
+  int64_t cap_cand = 0;
+  int64_t cap_scratch = 0;
+};
+
+}  // namespace rq
+
+struct rabitq_index {
+  int32_t dim = 0, W = 0, nlist = 0, total_bits = 0, metric = 0, F = 0, LW = 0;  // LW = long words per slot
+  int64_t n = 0, n_tiles = 0, n_slots = 0;
+  int device = 0;
+  // device arrays
+  float* rotation = nullptr;        // [D][D]
+  float* centroids_t = nullptr;     // [D][nlist]  (transposed c')
+  float* centroid_sq = nullptr;     // [nlist]
+  int32_t* tile_off = nullptr;      // [nlist+1]
+  int32_t* cluster_size = nullptr;  // [nlist]
+  uint32_t* short_codes = nullptr;
+  float* short_factors = nullptr;
+  uint32_t* long_codes = nullptr;
+  float* long_factors = nullptr;
+  int32_t* ids = nullptr;
+  // options
+  int prune = 1;
+  int profile = 0;
+  float stage_ms[8] = {0};
+  hipEvent_t ev[9] = {nullptr};
+  rq::Workspace ws;
+};
+
+namespace rq {
+
+void set_error(const std::string& s);
+int hip_fail(hipError_t e, const char* what);
+
+#define RQ_HIP(call)                                  \
+  do {                                                \
+    hipError_t e__ = (call);                          \
+    if (e__ != hipSuccess) return rq::hip_fail(e__, #call); \
+  } while (0)
+
+// order-preserving map float -> uint32 (ascending floats give ascending unsigned ints)
+__host__ __device__ inline uint32_t f2ord(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__host__ __device__ inline float ord2f(uint32_t o) {
+  uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+  return __builtin_bit_cast(float, u);
+}
+
+// ---- launchers (each returns a rabitq_status) ----
+// C[M,N] = A[M,K] * B[K,N], row-major fp32.  mode 0: plain.  mode 1 (L2 coarse):
+// C = rowv[m] + colv[n] - 2*acc.  mode 2 (IP coarse): C = -acc.
+int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,
+                const float* colv, hipStream_t st);
+int launch_query_prep(const float* q_rot, int64_t nq, int D, uint32_t* planes, float* delta, int32_t* sum_qhat,
+                      float* sum_q, float* sq_norm, hipStream_t st);
+int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
+                         int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st);
+int64_t probe_list_scratch_words(int32_t nlist, int64_t nq);
+int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,
+                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st);
+int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids, const float* probe_G,
+                const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st);
+int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+                const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st);
+int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
+                 int64_t* out_ids, float* out_dists, hipStream_t st);
+int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
+
+}  // namespace rq

@@ -1,0 +1,49 @@
+// Argument block of the seeding and scan kernels (plain data, passed by value).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rq {
+
+struct ScanArgs {
+  // index
+  const uint32_t* short_codes;
+  const float* short_factors;
+  const uint32_t* long_codes;
+  const float* long_factors;
+  const int32_t* ids;
+  const int32_t* tile_off;
+  const int32_t* cluster_size;
+  int D, B, LW, nlist;
+  float cB;  // (2^B - 1) / 2
+  // per query
+  const float* q_rot;
+  const uint32_t* planes;
+  const float* delta;
+  const int32_t* sum_qhat;
+  const float* sum_q;
+  const float* tau;
+  // per pair
+  const float* probe_G;
+  const float* probe_E;
+  const int32_t* probe_ids;
+  const int32_t* pair_off;
+  const int32_t* pair_ids;
+  const int32_t* item_off;
+  int nprobe, k, pool;
+  // outputs
+  uint64_t* cand_keys;
+  int32_t* cand_cnt;
+  float* tau_out;
+  int32_t* dbg_ip;
+  const int64_t* dbg_off;
+};
+
+bool seed_part0(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
+bool seed_part1(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
+bool seed_part2(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
+bool scan_part0(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
+bool scan_part1(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
+bool scan_part2(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
+
+}  // namespace rq

@@ -1,0 +1,316 @@
+// Threshold seeding and the fused cluster-local search kernel (Sections 3.3.4, 3.4.1(2), 3.4.2).
+#include "rq_device.h"
+#include "rq_scan_args.h"
+
+namespace rq {
+
+
+// 1-bit estimate of one lane's vector for one query (Section 3.4.1(2) + factors):
+// est1 = G + f_add + f_rescale * delta * (2I - S)/2.
+template <int W>
+__device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float fa, float fr, float G, float hd,
+                                int S, int* I_out) {
+  const int I = ip_bitplanes<W>(cw, pl);
+  *I_out = I;
+  return G + fa + fr * (hd * (float)(2 * I - S));
+}
+
+// ---------------------------------------------------------------------------------
+// Seeding: one workgroup (256 threads) per query.  In the nearest probed cluster with
+// at least k vectors: k smallest (est1, position) -> refine -> tau = max refined.
+// ---------------------------------------------------------------------------------
+constexpr int SEED_CHUNK_TILES = 32;  // 2048 keys per selection round
+
+template <int W, int F>
+__global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
+  extern __shared__ unsigned char smem_raw[];
+  // layout: chunk keys [2048] u64 | best [kpad] u64 | out [kpad] u64 | qf [D] f32
+  const int kpad = next_pow2(a.k);
+  uint64_t* chunk = reinterpret_cast<uint64_t*>(smem_raw);
+  uint64_t* best = chunk + SEED_CHUNK_TILES * TILE;
+  uint64_t* out = best + kpad;
+  float* qf = reinterpret_cast<float*>(out + kpad);
+  __shared__ uint32_t sh[260];
+  __shared__ int s_rank;
+  __shared__ uint32_t s_max;
+
+  const int64_t q = blockIdx.x;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (tid == 0) {
+    int r = -1;
+    for (int j = 0; j < a.nprobe; ++j) {
+      if (a.cluster_size[a.probe_ids[q * a.nprobe + j]] >= a.k) { r = j; break; }
+    }
+    s_rank = r;
+    s_max = 0u;
+  }
+  for (int i = tid; i < kpad; i += 256) best[i] = KEY_NONE;
+  if (F > 0) for (int i = tid; i < a.D; i += 256) qf[i] = a.q_rot[q * a.D + i];
+  __syncthreads();
+  const int rank = s_rank;
+  if (rank < 0) {
+    if (tid == 0) a.tau_out[q] = 3.402823466e+38f;
+    return;
+  }
+  const int64_t p = q * a.nprobe + rank;
+  const int c = a.probe_ids[p];
+  const float G = a.probe_G[p];
+  const float hd = 0.5f * a.delta[q];
+  const int S = a.sum_qhat[q];
+  const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
+  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+
+  for (int tb = t0; tb < t1; tb += SEED_CHUNK_TILES) {
+    const int nt = min(SEED_CHUNK_TILES, t1 - tb);
+    for (int tl = wave; tl < nt; tl += 4) {
+      const int tile = tb + tl;
+      uint32_t cw[W];
+#pragma unroll
+      for (int w = 0; w < W; ++w) cw[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
+      const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
+      const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
+      int I;
+      const float e1 = est1_of<W>(cw, pl, fa, fr, G, hd, S, &I);
+      const bool real = a.ids[(int64_t)tile * TILE + lane] >= 0;
+      chunk[tl * TILE + lane] = real ? make_key(e1, (uint32_t)((tile - t0) * TILE + lane)) : KEY_NONE;
+    }
+    __syncthreads();
+    const int nc = nt * TILE;
+    auto key_at = [&](int i) -> uint64_t { return i < nc ? chunk[i] : best[i - nc]; };
+    block_select_smallest(nc + kpad, a.k, kpad, key_at, out, sh);
+    for (int i = tid; i < kpad; i += 256) best[i] = out[i];
+    __syncthreads();
+  }
+  if (F == 0) {
+    if (tid == 0) a.tau_out[q] = ord2f((uint32_t)(best[a.k - 1] >> 32));
+    return;
+  }
+  // refine the k seeds: 16 lanes per seed, 16 seeds per round
+  const int grp = tid >> 4, t = tid & 15;
+  for (int sidx = grp; sidx < a.k; sidx += 16) {
+    const uint32_t pos = (uint32_t)best[sidx];
+    const int64_t slot = (int64_t)t0 * TILE + pos;
+    const int tile = (int)(slot >> 6), ln = (int)(slot & 63);
+    float part = 0.f;
+    if (F > 0)
+      part = refine_partial<(F > 0 ? F : 1)>(a.long_codes + slot * a.LW,
+                                             a.short_codes + (int64_t)tile * W * TILE + ln, qf, a.D, a.B, t);
+    const float ip = group16_sum(part);
+    if (t == 0) {
+      const float eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - a.cB * a.sum_q[q]);
+      atomicMax(&s_max, f2ord(eB));
+    }
+  }
+  __syncthreads();
+  if (tid == 0) a.tau_out[q] = fminf(ord2f(s_max), 3.402823466e+38f);
+}
+
+// ---------------------------------------------------------------------------------
+// Fused cluster-local search.  One wavefront (= one 64-thread workgroup) per work item:
+// QW pairs of the same cluster.  Lane l owns vector l of the current 64-vector tile;
+// its code words stay in registers while the QW queries' plane words come from scalar
+// registers.  Survivors of the filter are refined by groups of 16 lanes and appended to
+// a per-query pool in LDS; a pool that fills up is cut back to its k best (exact, since
+// it only compares final keys).  Output: up to k unsorted keys per pair.
+// ---------------------------------------------------------------------------------
+__device__ inline void pool_compact(uint64_t* pool, int pool_n, int& cnt, int k) {
+  __syncthreads();
+  for (int i = cnt + (int)threadIdx.x; i < pool_n; i += 64) pool[i] = KEY_NONE;
+  block_bitonic_sort(pool, pool_n);
+  cnt = min(cnt, k);
+}
+
+template <int W, int F, bool DBG>
+__global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
+  extern __shared__ unsigned char smem_raw[];
+  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);                 // [QW][pool]
+  float* qf = reinterpret_cast<float*>(pools + (size_t)QW * a.pool);       // [QW][D] (F > 0)
+  const int lane = threadIdx.x;
+
+  // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
+  // contiguous range of work items; items of one cluster then share one L2.
+  const int nb = gridDim.x;
+  const int per = (nb + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  const int n_items = a.item_off[a.nlist];
+  if (item >= n_items) return;
+  // cluster of this item: largest c with item_off[c] <= item
+  int lo = 0, hi = a.nlist;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.item_off[mid] <= item) lo = mid; else hi = mid;
+  }
+  const int c = lo;
+  const int pbeg = a.pair_off[c] + (item - a.item_off[c]) * QW;
+  const int np = min(QW, a.pair_off[c + 1] - pbeg);
+
+  int pj[QW], Sj[QW], cnt[QW];
+  float Gj[QW], Ej[QW], hdj[QW], tauj[QW], csq[QW];
+  int64_t qj[QW];
+#pragma unroll
+  for (int j = 0; j < QW; ++j) {
+    const int pp = a.pair_ids[pbeg + min(j, np - 1)];
+    const int64_t q = pp / a.nprobe;
+    pj[j] = pp;
+    qj[j] = q;
+    Gj[j] = a.probe_G[pp];
+    Ej[j] = a.probe_E[pp];
+    hdj[j] = 0.5f * a.delta[q];
+    Sj[j] = a.sum_qhat[q];
+    csq[j] = a.cB * a.sum_q[q];
+    tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
+    cnt[j] = 0;
+    if (F > 0) {
+      for (int i = lane; i < a.D; i += 64) qf[j * a.D + i] = a.q_rot[q * a.D + i];
+    }
+  }
+  __syncthreads();
+
+  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  for (int tile = t0; tile < t1; ++tile) {
+    uint32_t cw[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) cw[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
+    const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
+    const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
+    const float fe = a.short_factors[((int64_t)tile * 3 + 2) * TILE + lane];
+    // The plane words are re-read through the scalar cache for every (tile, query): an
+    // opaque zero keeps the compiler from hoisting QW*4*W scalar registers out of the loop.
+    int opaque0;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
+#pragma unroll
+    for (int j = 0; j < QW; ++j) {
+      const_u32_ptr pl = (const_u32_ptr)(a.planes + qj[j] * 4 * W + opaque0);
+      int I;
+      const float e1 = est1_of<W>(cw, pl, fa, fr, Gj[j], hdj[j], Sj[j], &I);
+      if (DBG) {
+        if (j < np) a.dbg_ip[a.dbg_off[pbeg + j] + (int64_t)(tile - t0) * TILE + lane] = I;
+      }
+      const float filt = (F > 0) ? (e1 - fe * Ej[j]) : e1;
+      const bool surv = filt <= tauj[j];
+      uint64_t m = __ballot(surv);
+      if (m == 0ull) continue;
+      uint64_t* pool = pools + (size_t)j * a.pool;
+      if (cnt[j] + TILE > a.pool) pool_compact(pool, a.pool, cnt[j], a.k);
+      if (F == 0) {
+        if (surv) {
+          const int pos = cnt[j] + __popcll(m & ((1ull << lane) - 1ull));
+          pool[pos] = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + lane]);
+        }
+        cnt[j] += __popcll(m);
+      } else {
+        const int grp = lane >> 4, t = lane & 15;
+        while (m != 0ull) {
+          // up to four survivors per round, one per 16-lane group
+          int pick[4];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            pick[g] = (m != 0ull) ? (__ffsll((long long)m) - 1) : -1;
+            m &= (m - 1ull);
+          }
+          const int my = grp == 0 ? pick[0] : (grp == 1 ? pick[1] : (grp == 2 ? pick[2] : pick[3]));
+          float part = 0.f;
+          int64_t slot = 0;
+          if (my >= 0) {
+            slot = (int64_t)tile * TILE + my;
+            part = refine_partial<(F > 0 ? F : 1)>(a.long_codes + slot * a.LW,
+                                                   a.short_codes + (int64_t)tile * W * TILE + my, qf + j * a.D, a.D,
+                                                   a.B, t);
+          }
+          const float ip = group16_sum(part);
+          if (my >= 0 && t == 0) {
+            const float eB = Gj[j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq[j]);
+            pool[cnt[j] + grp] = make_key(eB, (uint32_t)a.ids[slot]);
+          }
+          cnt[j] += (pick[3] >= 0) ? 4 : ((pick[2] >= 0) ? 3 : ((pick[1] >= 0) ? 2 : 1));
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int j = 0; j < QW; ++j) {
+    if (j >= np) break;
+    uint64_t* pool = pools + (size_t)j * a.pool;
+    if (cnt[j] > a.k) pool_compact(pool, a.pool, cnt[j], a.k);
+    __syncthreads();
+    if (lane == 0) a.cand_cnt[pj[j]] = cnt[j];
+    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.k + e] = pool[e];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Instantiations.  This file is compiled once per RQ_PART; each part holds the kernels
+// of a few code widths W = dim/32 so that the parts build in parallel.
+// ---------------------------------------------------------------------------------
+#ifndef RQ_PART
+#error "compile with -DRQ_PART=0..2"
+#endif
+#if RQ_PART == 0
+#define RQ_W_LIST(X) X(1) X(2) X(3) X(4)
+#define RQ_PART_NAME(f) f##_part0
+#elif RQ_PART == 1
+#define RQ_W_LIST(X) X(8) X(16) X(24)
+#define RQ_PART_NAME(f) f##_part1
+#else
+#define RQ_W_LIST(X) X(30) X(32)
+#define RQ_PART_NAME(f) f##_part2
+#endif
+
+template <int W, int F>
+static void launch_seed_wf(const ScanArgs& a, int64_t nq, hipStream_t st) {
+  const int kpad = next_pow2(a.k);
+  const size_t smem = (size_t)(SEED_CHUNK_TILES * TILE + 2 * kpad) * sizeof(uint64_t) + (size_t)a.D * sizeof(float);
+  hipLaunchKernelGGL((seed_kernel<W, F>), dim3((unsigned)nq), dim3(256), smem, st, a);
+}
+
+template <int W, int F>
+static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
+  const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + (F > 0 ? (size_t)QW * a.D * sizeof(float) : 0);
+  if (dbg)
+    hipLaunchKernelGGL((scan_kernel<W, F, true>), dim3(grid), dim3(64), smem, st, a);
+  else
+    hipLaunchKernelGGL((scan_kernel<W, F, false>), dim3(grid), dim3(64), smem, st, a);
+}
+
+template <int W>
+static void seed_by_f(const ScanArgs& a, int F, int64_t nq, hipStream_t st) {
+  switch (F) {
+    case 0: launch_seed_wf<W, 0>(a, nq, st); break;
+    case 1: launch_seed_wf<W, 1>(a, nq, st); break;
+    case 2: launch_seed_wf<W, 2>(a, nq, st); break;
+    case 4: launch_seed_wf<W, 4>(a, nq, st); break;
+    default: launch_seed_wf<W, 8>(a, nq, st); break;
+  }
+}
+
+template <int W>
+static void scan_by_f(const ScanArgs& a, int F, unsigned grid, bool dbg, hipStream_t st) {
+  switch (F) {
+    case 0: launch_scan_wf<W, 0>(a, grid, dbg, st); break;
+    case 1: launch_scan_wf<W, 1>(a, grid, dbg, st); break;
+    case 2: launch_scan_wf<W, 2>(a, grid, dbg, st); break;
+    case 4: launch_scan_wf<W, 4>(a, grid, dbg, st); break;
+    default: launch_scan_wf<W, 8>(a, grid, dbg, st); break;
+  }
+}
+
+// Return false when W is not one of this part's widths.
+bool RQ_PART_NAME(seed)(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st) {
+  switch (W) {
+#define RQ_X(W_) case W_: seed_by_f<W_>(a, F, nq, st); return true;
+    RQ_W_LIST(RQ_X)
+#undef RQ_X
+    default: return false;
+  }
+}
+
+bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st) {
+  switch (W) {
+#define RQ_X(W_) case W_: scan_by_f<W_>(a, F, grid, dbg, st); return true;
+    RQ_W_LIST(RQ_X)
+#undef RQ_X
+    default: return false;
+  }
+}
+
+}  // namespace rq

@@ -1,0 +1,119 @@
+// Host-side launchers of the seeding and scan kernels: argument block, work-item
+// offsets, and routing to the translation unit that holds the kernels for W = dim/32.
+#include "rq_internal.h"
+#include "rq_scan_args.h"
+
+namespace rq {
+
+// ---------------------------------------------------------------------------------
+// item_off[c] = first work item of cluster c; a work item is QW consecutive pairs of
+// one cluster.  (One workgroup.)
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off, int n,
+                                                          int32_t* __restrict__ item_off) {
+  __shared__ uint32_t part[256];
+  const int tid = threadIdx.x;
+  const int per = (n + 255) / 256;
+  const int s = tid * per, e = min(n, s + per);
+  uint32_t sum = 0;
+  for (int i = s; i < e; ++i) sum += (uint32_t)(pair_off[i + 1] - pair_off[i] + QW - 1) / QW;
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    const uint32_t o = (tid >= d) ? part[tid - d] : 0u;
+    __syncthreads();
+    part[tid] += o;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - sum;
+  for (int i = s; i < e; ++i) {
+    item_off[i] = (int32_t)run;
+    run += (uint32_t)(pair_off[i + 1] - pair_off[i] + QW - 1) / QW;
+  }
+  if (tid == 255) item_off[n] = (int32_t)part[255];
+}
+
+
+static int field_bits(int B) {
+  const int ex = B - 1;
+  if (ex <= 0) return 0;
+  if (ex <= 1) return 1;
+  if (ex <= 2) return 2;
+  if (ex <= 4) return 4;
+  return 8;
+}
+
+static int next_pow2_host(int v) {
+  int p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+
+static ScanArgs base_args(const rabitq_index* ix) {
+  ScanArgs a{};
+  a.short_codes = ix->short_codes;
+  a.short_factors = ix->short_factors;
+  a.long_codes = ix->long_codes;
+  a.long_factors = ix->long_factors;
+  a.ids = ix->ids;
+  a.tile_off = ix->tile_off;
+  a.cluster_size = ix->cluster_size;
+  a.D = ix->dim;
+  a.B = ix->total_bits;
+  a.LW = ix->LW;
+  a.nlist = ix->nlist;
+  a.cB = (float)(((1 << ix->total_bits) - 1) * 0.5);
+  return a;
+}
+
+static int bad_width() {
+  set_error("dim/32 must be one of 1,2,3,4,8,16,24,30,32 in this build");
+  return RABITQ_EINVAL;
+}
+
+int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids, const float* probe_G,
+                const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  ScanArgs a = base_args(ix);
+  a.q_rot = q_rot; a.planes = planes; a.delta = delta; a.sum_qhat = sum_qhat; a.sum_q = sum_q;
+  a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
+  a.nprobe = nprobe; a.k = k; a.tau_out = tau;
+  const int W = ix->W, F = field_bits(ix->total_bits);
+  if (!(seed_part0(a, W, F, nq, st) || seed_part1(a, W, F, nq, st) || seed_part2(a, W, F, nq, st))) return bad_width();
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
+                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+                const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  ScanArgs a = base_args(ix);
+  a.q_rot = q_rot; a.planes = planes; a.delta = delta; a.sum_qhat = sum_qhat; a.sum_q = sum_q;
+  a.probe_G = probe_G; a.probe_E = probe_E; a.pair_off = pair_off; a.pair_ids = pair_ids; a.tau = tau;
+  a.nprobe = nprobe; a.k = k; a.pool = next_pow2_host(k + TILE);
+  a.cand_keys = cand_keys; a.cand_cnt = cand_cnt; a.dbg_ip = dbg_ip; a.dbg_off = dbg_off;
+  // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
+  int32_t* item_off = ix->tile_off + (ix->nlist + 1);
+  a.item_off = item_off;
+  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->nlist, item_off);
+  // at most ceil(pairs/QW) + nlist work items; the kernel drops the excess
+  const int64_t npairs = nq * nprobe;
+  int64_t max_items = (npairs + QW - 1) / QW + ix->nlist;
+  max_items = ((max_items + 7) / 8) * 8;
+  if (max_items > 0x7fffffff) {
+    set_error("scan: too many work items");
+    return RABITQ_EINVAL;
+  }
+  const unsigned grid = (unsigned)max_items;
+  const bool dbg = dbg_ip != nullptr;
+  const int W = ix->W, F = field_bits(ix->total_bits);
+  if (!(scan_part0(a, W, F, grid, dbg, st) || scan_part1(a, W, F, grid, dbg, st) || scan_part2(a, W, F, grid, dbg, st)))
+    return bad_width();
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+}  // namespace rq

@@ -1,0 +1,273 @@
+// Small stages of the search path: per-query representation, probe selection,
+// probe-list regrouping and the per-query merge.
+#include "rq_device.h"
+
+namespace rq {
+
+// ---------------------------------------------------------------------------------
+// Section 3.3.3 / 3.4.1(2): 4-bit signed quantisation of q' and its bit-planes, once
+// per query.  One wavefront per query.  delta = max|q'|/7 and q'/delta use IEEE fp32
+// division and round-half-even, because they decide integers.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict__ q_rot, int64_t nq, int D,
+                                                        uint32_t* __restrict__ planes, float* __restrict__ delta,
+                                                        int32_t* __restrict__ sum_qhat, float* __restrict__ sum_q,
+                                                        float* __restrict__ sq_norm) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (q >= nq) return;
+  const float* x = q_rot + q * D;
+  const int W = D >> 5;
+  float amax = 0.f, s1 = 0.f, s2 = 0.f;
+  for (int i = lane; i < D; i += 64) {
+    const float v = x[i];
+    amax = fmaxf(amax, fabsf(v));
+    s1 += v;
+    s2 += v * v;
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) {
+    amax = fmaxf(amax, __shfl_xor(amax, d, 64));
+    s1 += __shfl_xor(s1, d, 64);
+    s2 += __shfl_xor(s2, d, 64);
+  }
+  const float dl = (amax == 0.f) ? 1.0f : __fdiv_rn(amax, 7.0f);
+  int S = 0;
+  uint32_t* pl = planes + q * 4 * W;
+  for (int base = 0; base < D; base += 64) {
+    const int i = base + lane;
+    int qh = 0;
+    if (i < D && amax != 0.f) {
+      const float t = rintf(__fdiv_rn(x[i], dl));
+      qh = (int)fminf(fmaxf(t, -7.f), 7.f);
+    }
+    S += qh;
+    const uint32_t tc = (uint32_t)qh & 15u;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const uint64_t m = __ballot((tc >> j) & 1u);
+      const int w = base >> 5;
+      if (lane == 0) pl[j * W + w] = (uint32_t)m;
+      if (lane == 0 && w + 1 < W) pl[j * W + w + 1] = (uint32_t)(m >> 32);
+    }
+  }
+#pragma unroll
+  for (int d = 32; d > 0; d >>= 1) S += __shfl_xor(S, d, 64);
+  if (lane == 0) {
+    delta[q] = dl;
+    sum_qhat[q] = S;
+    sum_q[q] = s1;
+    sq_norm[q] = s2;
+  }
+}
+
+int launch_query_prep(const float* q_rot, int64_t nq, int D, uint32_t* planes, float* delta, int32_t* sum_qhat,
+                      float* sum_q, float* sq_norm, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const unsigned grid = (unsigned)((nq + 3) / 4);
+  hipLaunchKernelGGL(query_prep_kernel, dim3(grid), dim3(256), 0, st, q_rot, nq, D, planes, delta, sum_qhat, sum_q,
+                     sq_norm);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Section 3.3.2: the nprobe best clusters of one score row, best first, ties to the
+// lower cluster id (the key's low word).  One workgroup per query.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void select_probes_kernel(const float* __restrict__ scores,
+                                                           const float* __restrict__ sq_norm,
+                                                           const float* __restrict__ centroid_sq, int nlist,
+                                                           int nprobe, int npad, int metric,
+                                                           int32_t* __restrict__ probe_ids,
+                                                           float* __restrict__ probe_G,
+                                                           float* __restrict__ probe_E) {
+  extern __shared__ uint64_t sel_out[];  // [npad]
+  __shared__ uint32_t sh[260];
+  const int64_t q = blockIdx.x;
+  const float* row = scores + q * nlist;
+  auto key_at = [&](int i) -> uint64_t { return make_key(row[i], (uint32_t)i); };
+  block_select_smallest(nlist, nprobe, npad, key_at, sel_out, sh);
+  for (int r = threadIdx.x; r < nprobe; r += blockDim.x) {
+    const uint64_t key = sel_out[r];
+    const int c = (int)(uint32_t)key;
+    const float s = ord2f((uint32_t)(key >> 32));
+    probe_ids[q * nprobe + r] = c;
+    probe_G[q * nprobe + r] = s;
+    const float d2 = (metric == RABITQ_L2) ? s : (sq_norm[q] + centroid_sq[c] + 2.0f * s);
+    probe_E[q * nprobe + r] = sqrtf(fmaxf(d2, 0.f));
+  }
+}
+
+int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
+                         int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const int npad = next_pow2(nprobe);
+  hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)nq), dim3(256), npad * sizeof(uint64_t), st, scores, sq_norm,
+                     centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Section 3.3.3: regroup (query, cluster) pairs by cluster, stable in query id.
+// A query probes a cluster at most once, so membership is one bit per (cluster, query):
+//   1. clear and set the bitmap  M[c][q]
+//   2. per cluster: running popcount of its bitmap row -> rank of every 32-query word
+//   3. exclusive scan of the cluster totals -> pair_off
+//   4. every pair computes its own destination: pair_off[c] + rank of q in row c
+// All integer, no order-dependent atomics: the output is unique.
+// scratch: bitmap [nlist][QWORDS] | word_rank [nlist][QWORDS] | total [nlist]
+// ---------------------------------------------------------------------------------
+__global__ void fill_u32_kernel(uint32_t* p, int64_t n, uint32_t v) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+__global__ void bitmap_set_kernel(const int32_t* __restrict__ probe_ids, int64_t npairs, int nprobe, int qwords,
+                                  uint32_t* __restrict__ bitmap) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < npairs; p += (int64_t)gridDim.x * blockDim.x) {
+    const int c = probe_ids[p];
+    const int64_t q = p / nprobe;
+    atomicOr(&bitmap[(int64_t)c * qwords + (q >> 5)], 1u << (q & 31));
+  }
+}
+
+__global__ __launch_bounds__(64) void row_rank_kernel(const uint32_t* __restrict__ bitmap, int qwords,
+                                                      uint32_t* __restrict__ word_rank,
+                                                      uint32_t* __restrict__ total) {
+  const int c = blockIdx.x, lane = threadIdx.x;
+  const uint32_t* row = bitmap + (int64_t)c * qwords;
+  uint32_t* out = word_rank + (int64_t)c * qwords;
+  uint32_t carry = 0;
+  for (int base = 0; base < qwords; base += 64) {
+    const int w = base + lane;
+    const uint32_t pc = (w < qwords) ? __popc(row[w]) : 0u;
+    uint32_t incl = pc;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const uint32_t o = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += o;
+    }
+    if (w < qwords) out[w] = carry + incl - pc;
+    carry += __shfl(incl, 63, 64);
+  }
+  if (lane == 0) total[c] = carry;
+}
+
+// out[0] = 0, out[i+1] = sum_{j<=i} f(in[j]); f = identity (div == 1) or ceil(x/div).  One workgroup.
+__global__ __launch_bounds__(256) void exclusive_scan_kernel(const uint32_t* __restrict__ in, int n, int div,
+                                                            int32_t* __restrict__ out) {
+  __shared__ uint32_t part[256];
+  const int tid = threadIdx.x;
+  const int per = (n + 255) / 256;
+  const int s = tid * per, e = min(n, s + per);
+  uint32_t sum = 0;
+  for (int i = s; i < e; ++i) sum += (in[i] + div - 1) / div;
+  part[tid] = sum;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    const uint32_t o = (tid >= d) ? part[tid - d] : 0u;
+    __syncthreads();
+    part[tid] += o;
+    __syncthreads();
+  }
+  uint32_t run = part[tid] - sum;
+  for (int i = s; i < e; ++i) {
+    out[i] = (int32_t)run;
+    run += (in[i] + div - 1) / div;
+  }
+  if (tid == 255) out[n] = (int32_t)part[255];
+}
+
+__global__ void scatter_pairs_kernel(const int32_t* __restrict__ probe_ids, int64_t npairs, int nprobe, int qwords,
+                                     const uint32_t* __restrict__ bitmap, const uint32_t* __restrict__ word_rank,
+                                     const int32_t* __restrict__ pair_off, int32_t* __restrict__ pair_ids) {
+  for (int64_t p = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; p < npairs; p += (int64_t)gridDim.x * blockDim.x) {
+    const int c = probe_ids[p];
+    const int64_t q = p / nprobe;
+    const int64_t wi = (int64_t)c * qwords + (q >> 5);
+    const uint32_t below = bitmap[wi] & ((1u << (q & 31)) - 1u);
+    pair_ids[pair_off[c] + word_rank[wi] + __popc(below)] = (int32_t)p;
+  }
+}
+
+int64_t probe_list_scratch_words(int32_t nlist, int64_t nq) {
+  const int64_t qwords = (nq + 31) / 32;
+  return 2 * (int64_t)nlist * qwords + nlist;
+}
+
+int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,
+                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const int qwords = (int)((nq + 31) / 32);
+  const int64_t npairs = nq * nprobe;
+  uint32_t* bitmap = scratch;
+  uint32_t* word_rank = scratch + (int64_t)nlist * qwords;
+  uint32_t* total = word_rank + (int64_t)nlist * qwords;
+  const int64_t bm_words = (int64_t)nlist * qwords;
+  const unsigned g1 = (unsigned)std::min<int64_t>((bm_words + 255) / 256, 4096);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(g1), dim3(256), 0, st, bitmap, bm_words, 0u);
+  const unsigned g2 = (unsigned)std::min<int64_t>((npairs + 255) / 256, 8192);
+  hipLaunchKernelGGL(bitmap_set_kernel, dim3(g2), dim3(256), 0, st, probe_ids, npairs, nprobe, qwords, bitmap);
+  hipLaunchKernelGGL(row_rank_kernel, dim3(nlist), dim3(64), 0, st, bitmap, qwords, word_rank, total);
+  hipLaunchKernelGGL(exclusive_scan_kernel, dim3(1), dim3(256), 0, st, total, nlist, 1, pair_off);
+  hipLaunchKernelGGL(scatter_pairs_kernel, dim3(g2), dim3(256), 0, st, probe_ids, npairs, nprobe, qwords, bitmap,
+                     word_rank, pair_off, pair_ids);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// Section 3.3.5: merge the nprobe cluster-local lists of one query into its top-k.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void merge_kernel(const uint64_t* __restrict__ cand_keys,
+                                                   const int32_t* __restrict__ cand_cnt, int k, int kpad, int nprobe,
+                                                   int metric, int64_t* __restrict__ out_ids,
+                                                   float* __restrict__ out_dists) {
+  extern __shared__ uint64_t sel_out[];  // [kpad]
+  __shared__ uint32_t sh[260];
+  const int64_t q = blockIdx.x;
+  const uint64_t* keys = cand_keys + q * nprobe * (int64_t)k;
+  const int32_t* cnt = cand_cnt + q * nprobe;
+  auto key_at = [&](int i) -> uint64_t {
+    const int j = i / k, e = i - j * k;
+    return (e < cnt[j]) ? keys[i] : KEY_NONE;
+  };
+  block_select_smallest(nprobe * k, k, kpad, key_at, sel_out, sh);
+  for (int r = threadIdx.x; r < k; r += blockDim.x) {
+    const uint64_t key = sel_out[r];
+    int64_t id = -1;
+    float d = (metric == RABITQ_L2) ? INFINITY : -INFINITY;
+    if (key != KEY_NONE) {
+      id = (int64_t)(int32_t)(uint32_t)key;
+      d = ord2f((uint32_t)(key >> 32));
+      if (metric == RABITQ_IP) d = -d;
+    }
+    out_ids[q * k + r] = id;
+    out_dists[q * k + r] = d;
+  }
+}
+
+int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
+                 int64_t* out_ids, float* out_dists, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const int kpad = next_pow2(k);
+  hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(256), kpad * sizeof(uint64_t), st, cand_keys, cand_cnt, k,
+                     kpad, nprobe, metric, out_ids, out_dists);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+__global__ void fill_f32_kernel(float* p, int64_t n, float v) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = v;
+}
+
+int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st) {
+  if (n <= 0) return RABITQ_OK;
+  const unsigned g = (unsigned)std::min<int64_t>((n + 255) / 256, 4096);
+  hipLaunchKernelGGL(fill_f32_kernel, dim3(g), dim3(256), 0, st, p, n, v);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+}  // namespace rq
