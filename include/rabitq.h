@@ -108,8 +108,9 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
                   int64_t* out_ids, float* out_dists, void* stream);
 
 /* Options (host call, takes effect for later searches):
- *   "prune"  1 (default): filter with the per-query seeded threshold (Section 3.3.4);
- *            0: refine every vector of every probed cluster (the unpruned definition).
+ *   "prune"   1 (default): filter with the per-query seeded threshold (Section 3.3.4);
+ *             0: refine every vector of every probed cluster (the unpruned definition).
+ *   "profile" n: see rabitq_stage_ms.
  * Errors: RABITQ_EINVAL for an unknown name or value. */
 int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
@@ -117,11 +118,16 @@ int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
  * "total_bits","long_field_bits","metric"}.  Returns the value, or a negative status. */
 int64_t rabitq_index_info(rabitq_index_t index, const char* name);
 
-/* Duration in milliseconds of each stage of the LAST rabitq_search that ran with the
- * option "profile" = 1 (HIP events on the caller's stream; the call then synchronises).
- * out_ms: host, [8]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
- * scan, merge.  Errors: RABITQ_EINVAL. */
-int rabitq_last_stage_ms(rabitq_index_t index, float* out_ms);
+/* Per-stage timing.  The option "profile" = n (0..4096) makes the next n searches record
+ * HIP events on the caller's stream around every stage (no synchronisation is added to the
+ * search itself); setting it again restarts the recording.  rabitq_stage_ms waits for the
+ * last recorded search and returns the MEAN duration in milliseconds of each stage over
+ * the recorded searches.
+ *   out_ms: host, [9]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
+ *           scan set-up (work-item offsets), scan kernel, merge
+ *   out_calls: host, number of searches the means were taken over (may be NULL)
+ * Errors: RABITQ_EINVAL (null pointer, nothing recorded), RABITQ_EHIP. */
+int rabitq_stage_ms(rabitq_index_t index, float* out_ms, int32_t* out_calls);
 
 /* ---- Stage-level entry points: the same kernels rabitq_search chains, with every
  * buffer supplied by the caller (device pointers).  They exist so that each stage can

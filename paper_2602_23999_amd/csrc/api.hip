@@ -60,8 +60,9 @@ static void free_index(rabitq_index* ix) {
   dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
   dev_free(ix->long_factors); dev_free(ix->ids);
   free_workspace(ix->ws);
-  for (auto& e : ix->ev)
-    if (e) (void)hipEventDestroy(e);
+  for (auto& set : ix->prof_sets)
+    for (auto& e : set.ev)
+      if (e) (void)hipEventDestroy(e);
   delete ix;
 }
 
@@ -199,11 +200,17 @@ int rabitq_index_free(rabitq_index_t ix) {
 int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
-  if (!std::strcmp(name, "profile") && (value == 0 || value == 1)) {
-    if (value == 1 && !ix->ev[0]) {
-      for (auto& e : ix->ev) RQ_HIP(hipEventCreate(&e));
+  if (!std::strcmp(name, "profile") && value >= 0 && value <= 4096) {
+    const size_t have = ix->prof_sets.size();
+    if ((size_t)value > have) {
+      ix->prof_sets.resize((size_t)value);
+      for (size_t i = have; i < (size_t)value; ++i)
+        for (auto& e : ix->prof_sets[i].ev) e = nullptr;
+      for (size_t i = have; i < (size_t)value; ++i)
+        for (auto& e : ix->prof_sets[i].ev) RQ_HIP(hipEventCreate(&e));
     }
-    ix->profile = (int)value;
+    ix->prof_used = 0;
+    ix->prof_limit = (int)value;
     return RABITQ_OK;
   }
   set_error("set_option: unknown option or value");
@@ -223,9 +230,21 @@ int64_t rabitq_index_info(rabitq_index_t ix, const char* name) {
   return RABITQ_EINVAL;
 }
 
-int rabitq_last_stage_ms(rabitq_index_t ix, float* out_ms) {
-  if (!ix || !out_ms) { set_error("last_stage_ms: null argument"); return RABITQ_EINVAL; }
-  for (int i = 0; i < 8; ++i) out_ms[i] = ix->stage_ms[i];
+int rabitq_stage_ms(rabitq_index_t ix, float* out_ms, int32_t* out_calls) {
+  if (!ix || !out_ms) { set_error("stage_ms: null argument"); return RABITQ_EINVAL; }
+  const int n = ix->prof_used;
+  if (n <= 0) { set_error("stage_ms: no search was recorded (set the option \"profile\" first)"); return RABITQ_EINVAL; }
+  RQ_HIP(hipEventSynchronize(ix->prof_sets[n - 1].ev[rabitq_index::N_STAGES]));
+  double acc[rabitq_index::N_STAGES] = {0};
+  for (int i = 0; i < n; ++i) {
+    for (int s = 0; s < rabitq_index::N_STAGES; ++s) {
+      float ms = 0.f;
+      RQ_HIP(hipEventElapsedTime(&ms, ix->prof_sets[i].ev[s], ix->prof_sets[i].ev[s + 1]));
+      acc[s] += ms;
+    }
+  }
+  for (int s = 0; s < rabitq_index::N_STAGES; ++s) out_ms[s] = (float)(acc[s] / n);
+  if (out_calls) *out_calls = n;
   return RABITQ_OK;
 }
 
@@ -346,9 +365,10 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
   Workspace& w = ix->ws;
   hipStream_t st = (hipStream_t)stream;
-  const bool prof = ix->profile != 0;
+  hipEvent_t* ev = nullptr;  // event set of this call when it is being recorded
+  if (ix->prof_used < ix->prof_limit) ev = ix->prof_sets[ix->prof_used++].ev;
   int stage = 0;
-#define RQ_MARK() do { if (prof) RQ_HIP(hipEventRecord(ix->ev[stage++], st)); } while (0)
+#define RQ_MARK() do { if (ev) RQ_HIP(hipEventRecord(ev[stage++], st)); } while (0)
 #define RQ_RUN(call) do { if ((rc = (call)) != RABITQ_OK) return rc; } while (0)
   RQ_MARK();
   RQ_RUN(launch_gemm(queries, ix->rotation, w.q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, st));
@@ -371,16 +391,12 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   }
   RQ_MARK();
   RQ_RUN(launch_scan(ix, w.q_rot, w.planes, w.delta, w.sum_qhat, w.sum_q, w.probe_G, w.probe_E, w.pair_off, w.pair_ids,
-                     w.tau, nq, k, nprobe, w.cand_keys, w.cand_cnt, nullptr, nullptr, st));
+                     w.tau, nq, k, nprobe, w.cand_keys, w.cand_cnt, nullptr, nullptr, st, ev ? ev[stage++] : nullptr));
   RQ_MARK();
   RQ_RUN(launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
   RQ_MARK();
 #undef RQ_MARK
 #undef RQ_RUN
-  if (prof) {
-    RQ_HIP(hipEventSynchronize(ix->ev[8]));
-    for (int i = 0; i < 8; ++i) RQ_HIP(hipEventElapsedTime(&ix->stage_ms[i], ix->ev[i], ix->ev[i + 1]));
-  }
   return RABITQ_OK;
 }
 

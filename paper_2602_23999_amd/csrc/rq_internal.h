@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string>
+#include <vector>
 
 #include "rabitq.h"
 
@@ -59,9 +60,10 @@ struct rabitq_index {
   int32_t* ids = nullptr;
   // options
   int prune = 1;
-  int profile = 0;
-  float stage_ms[8] = {0};
-  hipEvent_t ev[9] = {nullptr};
+  static constexpr int N_STAGES = 9;
+  struct EventSet { hipEvent_t ev[N_STAGES + 1]; };
+  std::vector<EventSet> prof_sets;  // one per recorded search
+  int prof_used = 0, prof_limit = 0;
   rq::Workspace ws;
 };
 
@@ -104,7 +106,8 @@ int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
 int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
                 const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
-                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st);
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
+                hipEvent_t after_setup = nullptr);
 int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
                  int64_t* out_ids, float* out_dists, hipStream_t st);
 int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);

@@ -88,7 +88,8 @@ int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
 int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
                 const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
-                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st) {
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
+                hipEvent_t after_setup) {
   if (nq <= 0) return RABITQ_OK;
   ScanArgs a = base_args(ix);
   a.q_rot = q_rot; a.planes = planes; a.delta = delta; a.sum_qhat = sum_qhat; a.sum_q = sum_q;
@@ -99,6 +100,7 @@ int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
   a.item_off = item_off;
   hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->nlist, item_off);
+  if (after_setup) RQ_HIP(hipEventRecord(after_setup, st));
   // at most ceil(pairs/QW) + nlist work items; the kernel drops the excess
   const int64_t npairs = nq * nprobe;
   int64_t max_items = (npairs + QW - 1) / QW + ix->nlist;

@@ -23,7 +23,7 @@ TILE = 64
 
 EXPORTS = [
     "rabitq_index_upload", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
-    "rabitq_last_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_coarse_probe",
+    "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_coarse_probe",
     "rabitq_probe_list_scratch_words", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
 ]
@@ -61,7 +61,7 @@ def load_library() -> C.CDLL:
     lib.rabitq_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.rabitq_index_info.argtypes = [vp, C.c_char_p]
     lib.rabitq_index_info.restype = i64
-    lib.rabitq_last_stage_ms.argtypes = [vp, C.POINTER(C.c_float)]
+    lib.rabitq_stage_ms.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.rabitq_rotate.argtypes = [vp, vp, i64, vp, vp]
     lib.rabitq_query_prep.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
     lib.rabitq_coarse_probe.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
@@ -165,11 +165,15 @@ class Index:
             _check(int(v))
         return int(v)
 
-    def last_stage_ms(self):
-        buf = (C.c_float * 8)()
-        _check(load_library().rabitq_last_stage_ms(self._h, buf))
-        names = ["rotate", "query_prep", "coarse_gemm", "probe_select", "list_build", "seed", "scan", "merge"]
-        return dict(zip(names, [float(x) for x in buf]))
+    STAGES = ["rotate", "query_prep", "coarse_gemm", "probe_select", "list_build", "seed", "scan_setup", "scan",
+              "merge"]
+
+    def stage_ms(self):
+        """Mean per-stage milliseconds over the searches recorded since set_option("profile", n)."""
+        buf = (C.c_float * 9)()
+        calls = C.c_int32(0)
+        _check(load_library().rabitq_stage_ms(self._h, buf, C.byref(calls)))
+        return dict(zip(self.STAGES, [float(x) for x in buf])), int(calls.value)
 
     # ---- stages -----------------------------------------------------------------
     def rotate(self, queries):

@@ -66,11 +66,11 @@ def _centres(w: Workload) -> np.ndarray:
         return r.standard_normal((w.n_centres, D))
     if w.name == "l2_128":
         # Two-level mixture with low intrinsic dimension: 32 coarse modes, each with
-        # its own 16-d subspace; components are scattered inside their mode's
+        # its own 12-d subspace; components are scattered inside their mode's
         # subspace, so neighbouring components overlap the way descriptor clusters do
         # and a query's neighbours spread over several inverted lists.
         modes, basis, which = _l2_128_modes(w)
-        z = r.standard_normal((w.n_centres, 16)) * 10.0
+        z = r.standard_normal((w.n_centres, L2_128_SUBDIM)) * L2_128_CENTRE_STD
         return modes[which] + np.einsum("nk,nkd->nd", z, basis[which])
     if w.name == "l2_960":
         return r.standard_normal((w.n_centres, D))
@@ -80,11 +80,19 @@ def _centres(w: Workload) -> np.ndarray:
     raise KeyError(w.name)
 
 
+# l2_128 recipe: std of the in-subspace component scatter, of the in-subspace point
+# scatter, and of the isotropic noise added in all 128 dimensions.
+L2_128_CENTRE_STD = 12.0
+L2_128_LOCAL_STD = 23.0
+L2_128_ISO_STD = 1.5
+L2_128_SUBDIM = 12
+
+
 def _l2_128_modes(w: Workload):
     r = _rng(w.seed_data, 7)
     D = w.dim
     modes = np.clip(r.normal(36.0, 26.0, (32, D)), 0.0, None)
-    basis = np.stack([np.linalg.qr(r.standard_normal((D, 16)))[0].T for _ in range(32)])
+    basis = np.stack([np.linalg.qr(r.standard_normal((D, L2_128_SUBDIM)))[0].T for _ in range(32)])
     which = r.integers(0, 32, w.n_centres)
     return modes, basis, which
 
@@ -105,8 +113,8 @@ def _draw(w: Workload, centres: np.ndarray, n: int, seed: int, stream: int, chun
         if w.name == "tiny":
             x = centres[comp] + 0.3 * g
         elif w.name == "l2_128":
-            z = r.standard_normal((m, 16)) * 20.0
-            x = centres[comp] + np.einsum("nk,nkd->nd", z, basis[which[comp]]) + 4.0 * g
+            z = r.standard_normal((m, L2_128_SUBDIM)) * L2_128_LOCAL_STD
+            x = centres[comp] + np.einsum("nk,nkd->nd", z, basis[which[comp]]) + L2_128_ISO_STD * g
             x = np.rint(np.clip(x, 0.0, 255.0))
         elif w.name == "l2_960":
             x = centres[comp] + scales[comp] * g
