@@ -101,6 +101,9 @@ def main():
     ap.add_argument("--nprobe", type=int, default=0, help="fix the operating point instead of choosing it by recall")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
+                         "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures the one-GPU path only: this build has no multi-GPU sharding (run with --gpus 1)")
@@ -162,10 +165,13 @@ def main():
     scan_ms = stage_ms["scan"]
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"scan_kernel_{w.name}_traffic.json")
+    # measured fabric traffic per launch (bytes), from the rocprofv3 --pmc summaries under profiles/
+    tpath = os.path.join(ROOT, "profiles", f"scan_kernel_{w.name}_traffic.txt")
     if os.path.exists(tpath):
-        with open(tpath) as f:
-            traffic = json.load(f).get(f"nprobe_{nprobe}")
+        for line in open(tpath):
+            f = line.split()
+            if len(f) >= 2 and f[0] == f"nprobe_{nprobe}":
+                traffic = int(f[1])
     res = {
         "metric": "queries/sec at recall@10~0.95 (1 GPU); code-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -184,6 +190,11 @@ def main():
         t0 = time.perf_counter()
         res["cpu_baseline"] = cpu_baseline(w, nprobe)
         log(f"[bench] cpu baseline: {res['cpu_baseline']['value']:.1f} q/s ({time.perf_counter() - t0:.1f}s)")
+    if args.pmc_calibration:
+        cal = torch.zeros(64 * 1024 * 1024, dtype=torch.float32, device="cuda")
+        cal2 = cal + 1.0
+        torch.cuda.synchronize()
+        del cal, cal2
     print(json.dumps(res), flush=True)
     gi.close()
 
