@@ -67,9 +67,10 @@ typedef struct {
   const int64_t* offsets;     /* [nlist+1] CSR over stored vectors, offsets[nlist]==n   */
   const uint32_t* short_codes;  /* [n_tiles][W][64]  1-bit (sign) codes                 */
   const float* short_factors;   /* [n_tiles][3][64]  f_add, f_rescale, f_err planes     */
-  const uint32_t* long_codes;   /* [n_slots][D*F/32] low F bits of each code, F-bit
-                                   little-endian fields, F = B-1 rounded up to 1,2,4,8;
-                                   NULL when B == 1                                     */
+  const uint32_t* long_codes;   /* [n_slots][D*F/32] the whole B-bit code of each dimension
+                                   in F-bit little-endian fields, F = B rounded up to
+                                   2, 4 or 8 (dimension i sits in word i/(32/F) at bit
+                                   F*(i mod 32/F)); NULL when B == 1                    */
   const float* long_factors;    /* [n_slots][2] f_add, f_rescale of the B-bit code;
                                    NULL when B == 1                                     */
   const int32_t* ids;           /* [n_slots] original id (Pid) of each stored vector    */

@@ -284,10 +284,10 @@ def unpack_bits(words: np.ndarray, D: int) -> np.ndarray:
 
 
 def long_field_bits(total_bits: int) -> int:
-    """Width F of one long-code field: (B-1) rounded up to 1, 2, 4 or 8."""
-    ex = total_bits - 1
-    for f in (1, 2, 4, 8):
-        if ex <= f:
+    """Width F of one long-code field: B rounded up to 2, 4 or 8 (the field holds the
+    whole code, sign bit included, so refinement reads one array)."""
+    for f in (2, 4, 8):
+        if total_bits <= f:
             return f
     raise ValueError(total_bits)
 
@@ -326,8 +326,8 @@ def pack_device_layout(index: dict) -> dict:
       cluster c owns ceil(n_c/64) tiles; tile_offsets[c] is its first tile.
       short_codes   u32 [n_tiles][W][64]   word w of lane l of tile t at (t*W+w)*64+l
       short_factors f32 [n_tiles][3][64]   (f_add, f_rescale, f_err) planes
-      long_codes    u32 [n_slots][D*F/32]  low F bits of the code per dim, F-bit fields
-                                           (F = B-1 rounded up to 1,2,4,8; absent if B=1)
+      long_codes    u32 [n_slots][D*F/32]  the full B-bit code per dim in F-bit fields
+                                           (F = B rounded up to 2,4,8; absent if B=1)
       long_factors  f32 [n_slots][2]       (f_add, f_rescale) of the full code
       ids           i32 [n_slots]
     Padding slots: codes 0, f_add = +inf, other factors 0, id = -1."""
@@ -358,7 +358,7 @@ def pack_device_layout(index: dict) -> dict:
                ids=ids, long_codes=None, long_factors=None, slot=slot)
     if B > 1:
         F = long_field_bits(B)
-        lw = pack_fields(index["u"] & ((1 << F) - 1), F)
+        lw = pack_fields(index["u"], F)
         lc = np.zeros((n_slots, lw.shape[1]), dtype=np.uint32)
         lc[slot] = lw
         lfa = np.zeros((n_slots, 2), dtype=np.float32)

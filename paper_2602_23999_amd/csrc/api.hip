@@ -18,12 +18,10 @@ int hip_fail(hipError_t e, const char* what) {
   return RABITQ_EHIP;
 }
 
-static int field_bits_of(int B) {
-  const int ex = B - 1;
-  if (ex <= 0) return 0;
-  if (ex <= 1) return 1;
-  if (ex <= 2) return 2;
-  if (ex <= 4) return 4;
+static int field_bits_of(int B) {  // long-code field width: B rounded up to 2, 4, 8 (0: no long code)
+  if (B <= 1) return 0;
+  if (B <= 2) return 2;
+  if (B <= 4) return 4;
   return 8;
 }
 

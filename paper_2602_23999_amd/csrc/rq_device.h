@@ -140,57 +140,78 @@ __device__ inline int ip_bitplanes(const uint32_t (&cw)[W], const_u32_ptr pl) {
 }
 
 // ---------------------------------------------------------------------------------
-// Refinement (Section 3.4.2: lanes cooperate on one candidate).  16 lanes share one
-// candidate; lane t (0..15) takes the 8-dimension groups t, t+16, ... and returns its
-// partial <u, q'>.  long_row: the candidate's long-code words; short_col: address of
-// the candidate's word 0 in its tile (words are 64 apart); qf: q' in LDS.
-// The field holds the low F bits of the code; when F < B the sign bit is OR-ed in.
+// Refinement (Section 3.4.2: lanes cooperate on one candidate).  The long code holds the
+// whole B-bit code of every dimension in F-bit fields (F = 2, 4, 8), LW = D*F/32 words per
+// vector.  G lanes share one candidate; lane t takes the words [t*WPL, (t+1)*WPL).
+//
+// A word is decoded byte-lane-wise: for each of the 8/F field positions s inside a byte,
+// (word >> s*F) & mask leaves one field in each of the four bytes, and a byte converts to
+// float in one instruction.  Byte b, position s of word w is dimension
+// w*(32/F) + b*(8/F) + s; the query is staged in LDS in that order (stage_index) so that
+// the four floats matching one masked word are one 16-byte read.
 // ---------------------------------------------------------------------------------
 template <int F>
-__device__ inline float refine_partial(const uint32_t* __restrict__ long_row, const uint32_t* __restrict__ short_col,
-                                       const float* qf, int D, int B, int t) {
+__host__ __device__ inline int stage_index(int d) {
+  constexpr int DPW = 32 / F, SPB = 8 / F;
+  const int w = d / DPW, r = d % DPW;
+  return w * DPW + (r % SPB) * 4 + (r / SPB);
+}
+
+template <int F>
+__device__ inline float dot_word(uint32_t word, const float* qw) {
+  constexpr int SPB = 8 / F;
+  constexpr uint32_t MASK = (F == 8) ? 0xffffffffu : (((1u << F) - 1u) * 0x01010101u);
   float acc = 0.f;
-  const bool need_msb = F < B;
-  for (int b = t; b < (D >> 3); b += 16) {
-    uint32_t v[8];
-    if (F == 4) {
-      const uint32_t w = long_row[b];
 #pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = (w >> (4 * k)) & 15u;
-    } else if (F == 2) {
-      const uint32_t w = long_row[b >> 1] >> (16 * (b & 1));
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = (w >> (2 * k)) & 3u;
-    } else if (F == 1) {
-      const uint32_t w = long_row[b >> 2] >> (8 * (b & 3));
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = (w >> k) & 1u;
-    } else {
-      const uint32_t w0 = long_row[2 * b], w1 = long_row[2 * b + 1];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        v[k] = (w0 >> (8 * k)) & 255u;
-        v[4 + k] = (w1 >> (8 * k)) & 255u;
-      }
-    }
-    if (need_msb) {
-      const uint32_t m = short_col[(b >> 2) * TILE] >> (8 * (b & 3));
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] |= ((m >> k) & 1u) << (B - 1);
-    }
-    const float4 qa = *reinterpret_cast<const float4*>(qf + 8 * b);
-    const float4 qb = *reinterpret_cast<const float4*>(qf + 8 * b + 4);
-    acc += (float)v[0] * qa.x + (float)v[1] * qa.y + (float)v[2] * qa.z + (float)v[3] * qa.w;
-    acc += (float)v[4] * qb.x + (float)v[5] * qb.y + (float)v[6] * qb.z + (float)v[7] * qb.w;
+  for (int s = 0; s < SPB; ++s) {
+    const uint32_t m = (word >> (s * F)) & MASK;
+    const float4 q = *reinterpret_cast<const float4*>(qw + 4 * s);
+    acc += (float)(m & 255u) * q.x + (float)((m >> 8) & 255u) * q.y + (float)((m >> 16) & 255u) * q.z +
+           (float)(m >> 24) * q.w;
   }
   return acc;
 }
 
-__device__ inline float group16_sum(float v) {
-  v += __shfl_xor(v, 8, 16);
-  v += __shfl_xor(v, 4, 16);
-  v += __shfl_xor(v, 2, 16);
-  v += __shfl_xor(v, 1, 16);
+template <int LW>
+struct RefineShape {
+  static constexpr int G = (LW > 32) ? 16 : 4;          // lanes per candidate
+  static constexpr int WPL = (LW + G - 1) / G;          // words per lane
+  static constexpr int NS = 64 / G;                     // candidates per wavefront round
+};
+
+// partial <u, q'> of lane t (0..G-1) of a candidate whose long-code row starts at `row`
+template <int F, int LW>
+__device__ inline float refine_lane(const uint32_t* __restrict__ row, const float* qf, int t) {
+  constexpr int WPL = RefineShape<LW>::WPL, DPW = 32 / F;
+  float acc = 0.f;
+  const int w0 = t * WPL;
+  if (w0 >= LW) return 0.f;
+  if (WPL % 4 == 0 && LW % 4 == 0) {
+#pragma unroll
+    for (int c = 0; c < WPL / 4; ++c) {
+      const uint4 v = *reinterpret_cast<const uint4*>(row + w0 + 4 * c);
+      const float* q = qf + (w0 + 4 * c) * DPW;
+      acc += dot_word<F>(v.x, q) + dot_word<F>(v.y, q + DPW) + dot_word<F>(v.z, q + 2 * DPW) +
+             dot_word<F>(v.w, q + 3 * DPW);
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < WPL; ++i) {
+      const int w = w0 + i;
+      if (w < LW) acc += dot_word<F>(row[w], qf + w * DPW);
+    }
+  }
+  return acc;
+}
+
+template <int G>
+__device__ inline float group_sum(float v) {
+  if (G >= 16) {
+    v += __shfl_xor(v, 8, 64);
+    v += __shfl_xor(v, 4, 64);
+  }
+  v += __shfl_xor(v, 2, 64);
+  v += __shfl_xor(v, 1, 64);
   return v;
 }
 

@@ -4,7 +4,6 @@
 
 namespace rq {
 
-
 // 1-bit estimate of one lane's vector for one query (Section 3.4.1(2) + factors):
 // est1 = G + f_add + f_rescale * delta * (2I - S)/2.
 template <int W>
@@ -13,6 +12,12 @@ __device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float
   const int I = ip_bitplanes<W>(cw, pl);
   *I_out = I;
   return G + fa + fr * (hd * (float)(2 * I - S));
+}
+
+// copy one rotated query into LDS in the order refine_lane reads it
+template <int F>
+__device__ inline void stage_query(float* dst, const float* __restrict__ src, int D, int tid, int nt) {
+  for (int i = tid; i < D; i += nt) dst[stage_index<(F > 0 ? F : 8)>(i)] = src[i];
 }
 
 // ---------------------------------------------------------------------------------
@@ -45,7 +50,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     s_max = 0u;
   }
   for (int i = tid; i < kpad; i += 256) best[i] = KEY_NONE;
-  if (F > 0) for (int i = tid; i < a.D; i += 256) qf[i] = a.q_rot[q * a.D + i];
+  if (F > 0) stage_query<F>(qf, a.q_rot + q * a.D, a.D, tid, 256);
   __syncthreads();
   const int rank = s_rank;
   if (rank < 0) {
@@ -85,18 +90,19 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     if (tid == 0) a.tau_out[q] = ord2f((uint32_t)(best[a.k - 1] >> 32));
     return;
   }
-  // refine the k seeds: 16 lanes per seed, 16 seeds per round
-  const int grp = tid >> 4, t = tid & 15;
-  for (int sidx = grp; sidx < a.k; sidx += 16) {
-    const uint32_t pos = (uint32_t)best[sidx];
-    const int64_t slot = (int64_t)t0 * TILE + pos;
-    const int tile = (int)(slot >> 6), ln = (int)(slot & 63);
+  // refine the k seeds, G lanes per seed
+  constexpr int FF = (F > 0 ? F : 8), LW = W * FF, GL = RefineShape<LW>::G;
+  const int grp = tid / GL, t = tid % GL;
+  for (int base = 0; base < a.k; base += 256 / GL) {
+    const int sidx = base + grp;
     float part = 0.f;
-    if (F > 0)
-      part = refine_partial<(F > 0 ? F : 1)>(a.long_codes + slot * a.LW,
-                                             a.short_codes + (int64_t)tile * W * TILE + ln, qf, a.D, a.B, t);
-    const float ip = group16_sum(part);
-    if (t == 0) {
+    int64_t slot = 0;
+    if (sidx < a.k) {
+      slot = (int64_t)t0 * TILE + (uint32_t)best[sidx];
+      part = refine_lane<FF, LW>(a.long_codes + slot * LW, qf, t);
+    }
+    const float ip = group_sum<GL>(part);
+    if (sidx < a.k && t == 0) {
       const float eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - a.cB * a.sum_q[q]);
       atomicMax(&s_max, f2ord(eB));
     }
@@ -107,24 +113,34 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 
 // ---------------------------------------------------------------------------------
 // Fused cluster-local search.  One wavefront (= one 64-thread workgroup) per work item:
-// QW pairs of the same cluster.  Lane l owns vector l of the current 64-vector tile;
-// its code words stay in registers while the QW queries' plane words come from scalar
-// registers.  Survivors of the filter are refined by groups of 16 lanes and appended to
-// a per-query pool in LDS; a pool that fills up is cut back to its k best (exact, since
-// it only compares final keys).  Output: up to k unsorted keys per pair.
+// QW pairs of the same cluster.  Lane l owns vector l of the current 64-vector tile; its
+// code words stay in registers while the plane words of the QW queries come through the
+// scalar cache.  Survivors of the filter are appended to a list in LDS; a full list (and
+// the list left at the end) is refined NS candidates per round, G lanes per candidate, and
+// the refined keys go to a per-query pool in LDS.  A pool that fills up is cut back to its
+// k best (exact: it only compares final keys) and its k-th key then rejects later keys.
+// Output: up to k unsorted keys per pair.
 // ---------------------------------------------------------------------------------
-__device__ inline void pool_compact(uint64_t* pool, int pool_n, int& cnt, int k) {
+constexpr int LIST_CAP = 512;
+
+__device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   __syncthreads();
   for (int i = cnt + (int)threadIdx.x; i < pool_n; i += 64) pool[i] = KEY_NONE;
   block_bitonic_sort(pool, pool_n);
-  cnt = min(cnt, k);
+  return min(cnt, k);
 }
 
 template <int W, int F, bool DBG>
 __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
+  constexpr int FF = (F > 0 ? F : 8), LW = W * FF;
+  constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
   extern __shared__ unsigned char smem_raw[];
-  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);                 // [QW][pool]
-  float* qf = reinterpret_cast<float*>(pools + (size_t)QW * a.pool);       // [QW][D] (F > 0)
+  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);             // [QW][pool]
+  uint64_t* pool_kth = pools + (size_t)QW * a.pool;                    // [QW] k-th best key so far
+  float* qs = reinterpret_cast<float*>(pool_kth + QW);                 // [QW][2]: G, cB*sum(q')
+  int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QW);                 // [QW]
+  uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QW);         // [LIST_CAP] (F > 0)
+  float* qf = reinterpret_cast<float*>(list + (F > 0 ? LIST_CAP : 0)); // [QW][D] (F > 0)
   const int lane = threadIdx.x;
 
   // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
@@ -145,7 +161,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int np = min(QW, a.pair_off[c + 1] - pbeg);
 
   int pj[QW], Sj[QW], cnt[QW];
-  float Gj[QW], Ej[QW], hdj[QW], tauj[QW], csq[QW];
+  float Gj[QW], Ej[QW], hdj[QW], tauj[QW];
   int64_t qj[QW];
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
@@ -157,16 +173,59 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     Ej[j] = a.probe_E[pp];
     hdj[j] = 0.5f * a.delta[q];
     Sj[j] = a.sum_qhat[q];
-    csq[j] = a.cB * a.sum_q[q];
     tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
     cnt[j] = 0;
-    if (F > 0) {
-      for (int i = lane; i < a.D; i += 64) qf[j * a.D + i] = a.q_rot[q * a.D + i];
+    if (lane == 0) {
+      pool_kth[j] = KEY_NONE;
+      pool_cnt[j] = 0;
+      qs[2 * j] = Gj[j];
+      qs[2 * j + 1] = a.cB * a.sum_q[q];
     }
+    if (F > 0) stage_query<F>(qf + j * a.D, a.q_rot + q * a.D, a.D, lane, 64);
   }
   __syncthreads();
 
   const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  int list_cnt = 0;
+
+  // refine everything in the list (F > 0 only); wave-uniform control flow throughout
+  auto flush = [&]() {
+    __syncthreads();
+    for (int base = 0; base < list_cnt; base += NS) {
+      const int idx = base + lane / G, t = lane % G;
+      const bool valid = idx < list_cnt;
+      const uint32_t e = valid ? list[idx] : 0u;
+      const int j = (int)(e >> 30);
+      const int64_t slot = (int64_t)t0 * TILE + (e & 0x3fffffffu);
+      float part = 0.f;
+      if (valid) part = refine_lane<FF, LW>(a.long_codes + slot * LW, qf + j * a.D, t);
+      const float ip = group_sum<G>(part);
+      if (valid && t == 0) {
+        const float eB = qs[2 * j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - qs[2 * j + 1]);
+        const uint64_t key = make_key(eB, (uint32_t)a.ids[slot]);
+        if (key <= pool_kth[j]) {
+          const int pos = atomicAdd(&pool_cnt[j], 1);
+          pools[(size_t)j * a.pool + pos] = key;
+        }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int jj = 0; jj < QW; ++jj) {
+        const int cj = pool_cnt[jj];
+        if (cj + NS > a.pool) {
+          uint64_t* pool = pools + (size_t)jj * a.pool;
+          const int nc = pool_compact(pool, a.pool, cj, a.k);
+          if (lane == 0) {
+            pool_cnt[jj] = nc;
+            if (nc >= a.k) pool_kth[jj] = pool[a.k - 1];
+          }
+          __syncthreads();
+        }
+      }
+    }
+    list_cnt = 0;
+  };
+
   for (int tile = t0; tile < t1; ++tile) {
     uint32_t cw[W];
 #pragma unroll
@@ -188,50 +247,37 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       }
       const float filt = (F > 0) ? (e1 - fe * Ej[j]) : e1;
       const bool surv = filt <= tauj[j];
-      uint64_t m = __ballot(surv);
+      const uint64_t m = __ballot(surv);
       if (m == 0ull) continue;
-      uint64_t* pool = pools + (size_t)j * a.pool;
-      if (cnt[j] + TILE > a.pool) pool_compact(pool, a.pool, cnt[j], a.k);
+      const int ns = __popcll(m);
+      const int before = __popcll(m & ((1ull << lane) - 1ull));
       if (F == 0) {
-        if (surv) {
-          const int pos = cnt[j] + __popcll(m & ((1ull << lane) - 1ull));
-          pool[pos] = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + lane]);
+        // B == 1: the 1-bit estimate is the final key
+        uint64_t* pool = pools + (size_t)j * a.pool;
+        if (cnt[j] + TILE > a.pool) {
+          cnt[j] = pool_compact(pool, a.pool, cnt[j], a.k);
+          // exact tightening: keys above the k-th best of this pair cannot be in its top-k
+          if (cnt[j] >= a.k) tauj[j] = fminf(tauj[j], ord2f((uint32_t)(pool[a.k - 1] >> 32)));
         }
-        cnt[j] += __popcll(m);
+        if (surv) pool[cnt[j] + before] = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + lane]);
+        cnt[j] += ns;
       } else {
-        const int grp = lane >> 4, t = lane & 15;
-        while (m != 0ull) {
-          // up to four survivors per round, one per 16-lane group
-          int pick[4];
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            pick[g] = (m != 0ull) ? (__ffsll((long long)m) - 1) : -1;
-            m &= (m - 1ull);
-          }
-          const int my = grp == 0 ? pick[0] : (grp == 1 ? pick[1] : (grp == 2 ? pick[2] : pick[3]));
-          float part = 0.f;
-          int64_t slot = 0;
-          if (my >= 0) {
-            slot = (int64_t)tile * TILE + my;
-            part = refine_partial<(F > 0 ? F : 1)>(a.long_codes + slot * a.LW,
-                                                   a.short_codes + (int64_t)tile * W * TILE + my, qf + j * a.D, a.D,
-                                                   a.B, t);
-          }
-          const float ip = group16_sum(part);
-          if (my >= 0 && t == 0) {
-            const float eB = Gj[j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq[j]);
-            pool[cnt[j] + grp] = make_key(eB, (uint32_t)a.ids[slot]);
-          }
-          cnt[j] += (pick[3] >= 0) ? 4 : ((pick[2] >= 0) ? 3 : ((pick[1] >= 0) ? 2 : 1));
-        }
+        if (list_cnt + ns > LIST_CAP) flush();
+        if (surv) list[list_cnt + before] = ((uint32_t)j << 30) | (uint32_t)((tile - t0) * TILE + lane);
+        list_cnt += ns;
       }
     }
+  }
+  if (F > 0) {
+    flush();
+#pragma unroll
+    for (int j = 0; j < QW; ++j) cnt[j] = pool_cnt[j];
   }
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
     uint64_t* pool = pools + (size_t)j * a.pool;
-    if (cnt[j] > a.k) pool_compact(pool, a.pool, cnt[j], a.k);
+    if (cnt[j] > a.k) cnt[j] = pool_compact(pool, a.pool, cnt[j], a.k);
     __syncthreads();
     if (lane == 0) a.cand_cnt[pj[j]] = cnt[j];
     for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.k + e] = pool[e];
@@ -265,7 +311,8 @@ static void launch_seed_wf(const ScanArgs& a, int64_t nq, hipStream_t st) {
 
 template <int W, int F>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
-  const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + (F > 0 ? (size_t)QW * a.D * sizeof(float) : 0);
+  const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
+                      (F > 0 ? LIST_CAP * sizeof(uint32_t) + (size_t)QW * a.D * sizeof(float) : 0);
   if (dbg)
     hipLaunchKernelGGL((scan_kernel<W, F, true>), dim3(grid), dim3(64), smem, st, a);
   else
@@ -276,7 +323,6 @@ template <int W>
 static void seed_by_f(const ScanArgs& a, int F, int64_t nq, hipStream_t st) {
   switch (F) {
     case 0: launch_seed_wf<W, 0>(a, nq, st); break;
-    case 1: launch_seed_wf<W, 1>(a, nq, st); break;
     case 2: launch_seed_wf<W, 2>(a, nq, st); break;
     case 4: launch_seed_wf<W, 4>(a, nq, st); break;
     default: launch_seed_wf<W, 8>(a, nq, st); break;
@@ -287,7 +333,6 @@ template <int W>
 static void scan_by_f(const ScanArgs& a, int F, unsigned grid, bool dbg, hipStream_t st) {
   switch (F) {
     case 0: launch_scan_wf<W, 0>(a, grid, dbg, st); break;
-    case 1: launch_scan_wf<W, 1>(a, grid, dbg, st); break;
     case 2: launch_scan_wf<W, 2>(a, grid, dbg, st); break;
     case 4: launch_scan_wf<W, 4>(a, grid, dbg, st); break;
     default: launch_scan_wf<W, 8>(a, grid, dbg, st); break;

@@ -34,12 +34,10 @@ __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __rest
 }
 
 
-static int field_bits(int B) {
-  const int ex = B - 1;
-  if (ex <= 0) return 0;
-  if (ex <= 1) return 1;
-  if (ex <= 2) return 2;
-  if (ex <= 4) return 4;
+static int field_bits(int B) {  // long-code field width: B rounded up to 2, 4, 8 (0: no long code)
+  if (B <= 1) return 0;
+  if (B <= 2) return 2;
+  if (B <= 4) return 4;
   return 8;
 }
 

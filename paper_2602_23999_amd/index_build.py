@@ -22,8 +22,8 @@ N_FINE = 32
 
 
 def _field_bits(total_bits: int) -> int:
-    ex = total_bits - 1
-    return 0 if ex <= 0 else next(f for f in (1, 2, 4, 8) if ex <= f)
+    """Long-code field width: B rounded up to 2, 4 or 8 (0 when there is no long code)."""
+    return 0 if total_bits <= 1 else next(f for f in (2, 4, 8) if total_bits <= f)
 
 
 def random_rotation(dim: int, seed: int, device) -> torch.Tensor:
@@ -176,7 +176,7 @@ def build_index(x: torch.Tensor, nlist: int, total_bits: int, metric: str = "l2"
         sf[sl] = f1.float()
         if B > 1:
             fB = _factors(u.double() - cB, o_rot, c_rot, r, metric, eps0, odc)
-            lc[sl] = _pack_fields(u & ((1 << F) - 1), F)
+            lc[sl] = _pack_fields(u, F)
             lf[sl] = fB[:, :2].float()
 
     def u32(t):

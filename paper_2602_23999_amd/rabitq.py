@@ -115,7 +115,7 @@ class Index:
         counts = np.diff(k["offsets"])
         n_tiles = int(((counts + TILE - 1) // TILE).sum())
         W = dim // 32
-        F = 0 if total_bits == 1 else next(f for f in (1, 2, 4, 8) if total_bits - 1 <= f)
+        F = 0 if total_bits == 1 else next(f for f in (2, 4, 8) if total_bits <= f)
         want = dict(short_codes=n_tiles * W * TILE, short_factors=n_tiles * 3 * TILE, ids=n_tiles * TILE)
         if total_bits > 1:
             want.update(long_codes=n_tiles * TILE * dim * F // 32, long_factors=n_tiles * TILE * 2)

@@ -26,10 +26,8 @@ def test_builder_matches_oracle(wl, B):
     msb = build.unpack_bits(sc, D)
     if B > 1:
         F = build.long_field_bits(B)
-        low = build.unpack_fields(out["long_codes"].reshape(n_tiles * 64, -1)[real], F, D)
-        u = low if F >= B else ((msb.astype(np.uint8) << (B - 1)) | low)
-        if F >= B:
-            assert np.array_equal(u >> (B - 1), msb)
+        u = build.unpack_fields(out["long_codes"].reshape(n_tiles * 64, -1)[real], F, D)
+        assert np.array_equal(u >> (B - 1), msb)
     else:
         u = msb
     # recompute the rotated unit vectors the builder quantised

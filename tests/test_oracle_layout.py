@@ -37,7 +37,7 @@ def test_layout_small_fixture():
         else:
             assert int(arr[int(idx)]) == int(val, 0), (name, idx)
     # everything not listed in the fixture is padding
-    assert np.count_nonzero(dev["short_codes"]) == 4 and np.count_nonzero(dev["long_codes"]) == 4
+    assert np.count_nonzero(dev["short_codes"]) == 4 and np.count_nonzero(dev["long_codes"]) == 5
     assert np.isinf(dev["short_factors"].reshape(2, 3, 64)[:, 0, :]).sum() == 128 - 3
     assert (dev["ids"] == -1).sum() == 125
 
@@ -55,10 +55,10 @@ def test_layout_roundtrip_ragged():
     slot = dev["slot"]
     assert dev["tile_offsets"].tolist() == [0, 2, 2, 3, 4, 7]
     msb = build.unpack_bits(sc[slot], D)
-    low = build.unpack_fields(lc[slot], F, D)
+    full = build.unpack_fields(lc[slot], F, D)
+    assert F == 8 and lc.shape[1] == D * F // 32
     assert np.array_equal(msb, ix["u"] >> (B - 1))
-    assert np.array_equal(low, ix["u"] & ((1 << F) - 1))
-    assert np.array_equal((msb.astype(int) << (B - 1)) | low, ix["u"])   # F=4 >= B-1: msb + low bits give u
+    assert np.array_equal(full, ix["u"])                      # the long code holds the whole code
     assert np.array_equal(sf[slot], ix["short_factors"])
     assert np.array_equal(dev["long_factors"].reshape(-1, 2)[slot], ix["long_factors"])
     assert np.array_equal(dev["ids"][slot], ix["ids"])
