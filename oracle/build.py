@@ -200,7 +200,7 @@ def vector_factors(x: np.ndarray, o_rot: np.ndarray, c_rot: np.ndarray,
 def build_index(X: np.ndarray, nlist: int, total_bits: int, metric: str = "l2",
                 seed_rotation: int = 7, seed_kmeans: int = 99, kmeans_iters: int = 10,
                 train_size: int | None = None, eps0: float = 1.9,
-                centroids: np.ndarray | None = None) -> dict:
+                centroids: np.ndarray | None = None, workers: int = 1) -> dict:
     """Build the flat IVF-RaBitQ index over raw vectors ``X`` [N, D].
 
     Steps in the paper's order (Section 3.1): learn centroids and assign; per
@@ -237,7 +237,8 @@ def build_index(X: np.ndarray, nlist: int, total_bits: int, metric: str = "l2",
     rr = np.empty(N, dtype=np.float64)
     cB = ((1 << B) - 1) / 2.0
     chunk = 16384
-    for s in range(0, N, chunk):
+
+    def do_chunk(s):
         rows = order[s:s + chunk]
         cid = assign[rows]
         c = C[cid]
@@ -261,6 +262,17 @@ def build_index(X: np.ndarray, nlist: int, total_bits: int, metric: str = "l2",
             lf[s:s + chunk] = f1[:, :2].astype(np.float32)
         u[s:s + chunk] = uu
         rr[s:s + chunk] = r
+
+    starts = range(0, N, chunk)
+    if workers > 1:
+        # chunks are independent and numpy releases the GIL in its heavy loops; threads only
+        # spread the same arithmetic over the host cores
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=workers) as ex:
+            list(ex.map(do_chunk, starts))
+    else:
+        for s in starts:
+            do_chunk(s)
     return dict(dim=D, nlist=nlist, n=N, total_bits=B, metric=metric, eps0=eps0,
                 P=P, centroids=C, centroids_rot=C_rot, offsets=offsets,
                 ids=order.astype(np.int32), u=u, short_factors=sf, long_factors=lf, r=rr)

@@ -1,0 +1,63 @@
+"""Parity at the benchmark's full size (N = 1e6, D = 128, nlist = 1024, B = 4, nq = 10000,
+k = 10) in the launch configuration bench.py times: the whole batch goes through
+rabitq_search once, and a seeded sample of its queries is checked one by one against the
+oracle on the oracle-built index; properties that hold at any size are checked on all rows."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import build, exact, search
+from paper_2602_23999_amd import synth
+
+from gpu_helpers import compare_topk, upload
+
+pytestmark = pytest.mark.gpu
+
+
+def test_l2_128_full_size_sampled_parity():
+    w = synth.WORKLOADS["l2_128"]
+    k, nprobe = w.k, 16
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    workers = min(16, len(os.sched_getaffinity(0)))
+    ix = build.build_index(X, w.nlist, w.total_bits, train_size=w.n // 10, kmeans_iters=5, workers=workers)
+    gi = upload(ix)
+    Qd = torch.from_numpy(Q).cuda()
+    ids, dist = gi.search(Qd, k, nprobe)
+    ids2, dist2 = gi.search(Qd, k, nprobe)
+    torch.cuda.synchronize()
+    assert torch.equal(ids, ids2) and torch.equal(dist, dist2)          # deterministic
+    ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
+    # properties on every row
+    assert ids.min() >= 0 and ids.max() < w.n
+    assert np.all(np.diff(dist, axis=1) >= 0)
+    srt = np.sort(ids, axis=1)
+    assert np.all(srt[:, 1:] != srt[:, :-1])                            # no duplicate ids in a row
+    # probe lists at full size: a permutation of all pairs, grouped by cluster
+    qr = gi.rotate(Qd)
+    prep = gi.query_prep(qr)
+    probes = gi.coarse_probe(qr, prep["sq_norm"], nprobe)
+    off, pid = gi.build_probe_lists(probes["probe_ids"])
+    off, pid = off.cpu().numpy(), pid.cpu().numpy()
+    assert off[0] == 0 and off[-1] == w.nq * nprobe and np.all(np.diff(off) >= 0)
+    assert np.array_equal(np.sort(pid), np.arange(w.nq * nprobe))
+    cl = probes["probe_ids"].cpu().numpy().reshape(-1)[pid]
+    assert np.all(np.diff(cl) >= 0)
+    for c in (0, 17, 1023):                                              # stable in pair (= query) order
+        seg = pid[off[c]:off[c + 1]]
+        assert np.all(np.diff(seg) > 0)
+    # sampled queries against the oracle
+    rng = np.random.default_rng(5)
+    sample = np.sort(rng.choice(w.nq, size=48, replace=False))
+    s = search.Searcher(ix)
+    o_ids, o_d, info = s.search(Q[sample], k, nprobe)
+    same = np.array([np.array_equal(a, b) for a, b in zip(ids[sample], o_ids)])
+    assert same.mean() >= 0.9, same.mean()
+    atol = 1e-4 * (info["G"].max(axis=1) + 1e-6)
+    n_exact = compare_topk(ids[sample][same], dist[sample][same], o_ids[same], o_d[same], atol[same])
+    assert n_exact == same.sum()
+    gt, _ = exact.exact_knn(X, Q[sample], k)
+    r_gpu, r_ora = exact.recall_at_k(ids[sample], gt), exact.recall_at_k(o_ids, gt)
+    assert abs(r_gpu - r_ora) <= 0.02 and r_gpu > 0.85, (r_gpu, r_ora)
+    gi.close()
