@@ -173,11 +173,15 @@ int rabitq_seed_threshold(rabitq_index_t index, const float* q_rot, const uint32
  * For every pair: 1-bit estimate of every vector of the cluster by AND+popcount, filter
  * (B > 1: lb1 <= tau, B == 1: est1 <= tau), refinement of survivors, cluster-local top-k.
  *   tau        [nq] fp32 (pass FLT_MAX everywhere to disable the filter)
- *   cand_keys  [nq*nprobe*k] u64: (order-preserving bits of the key << 32) | id
- *   cand_cnt   [nq*nprobe] i32: valid entries of each pair's k-slot region (unsorted)
+ *   cand_keys  [nq*nprobe*cap] u64, cap = rabitq_cand_capacity(k): (order-preserving bits of
+ *              the key << 32) | id.  Pair p owns the cap-slot region starting at p*cap.
+ *   cand_cnt   [nq*nprobe] i32: valid entries of each pair's region (unsorted).  A region
+ *              holds every surviving key of the pair unless more than cap-16 survived, in
+ *              which case it holds at least the k best of them.
  *   dbg_ip     optional (may be NULL) [sum over pairs, in pair_ids order, of 64*tiles(c)] i32:
  *              raw integer <x_b, qhat> of every slot; dbg_off [nq*nprobe+1] i64 gives each
  *              pair's first entry (indexed by position in pair_ids).  For small inputs. */
+int32_t rabitq_cand_capacity(int32_t k); /* = smallest power of two >= k + 64; negative status if k is out of range */
 int rabitq_scan(rabitq_index_t index, const float* q_rot, const uint32_t* planes, const float* delta,
                 const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int32_t k,

@@ -35,8 +35,9 @@ def _run(cmd, verbose):
 
 def build(verbose: bool = True, jobs: int = 7) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    extra = os.environ.get("RQ_EXTRA_FLAGS", "").split()  # e.g. -DRQ_STATS for development counters
     os.makedirs(OBJ, exist_ok=True)
-    cmds = [[hipcc, *FLAGS, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ, obj)]
+    cmds = [[hipcc, *FLAGS, *extra, *defs, "-c", os.path.join(CSRC, src), "-o", os.path.join(OBJ, obj)]
             for src, defs, obj in UNITS]
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         list(ex.map(lambda c: _run(c, verbose), cmds))

@@ -69,7 +69,9 @@ static void free_index(rabitq_index* ix) {
 static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   Workspace& w = ix->ws;
   const int64_t pairs = nq * nprobe;
-  const int64_t cand = pairs * k;
+  int cap = 1;
+  while (cap < k + TILE) cap <<= 1;
+  const int64_t cand = pairs * cap;
   const int64_t scratch = probe_list_scratch_words(ix->nlist, nq);
   if (nq <= w.cap_nq && pairs <= w.cap_pairs && cand <= w.cap_cand && scratch <= w.cap_scratch) return RABITQ_OK;
   hipError_t e = hipDeviceSynchronize();
@@ -291,6 +293,13 @@ int rabitq_coarse_probe(rabitq_index_t ix, const float* q_rot, const float* sq_n
   if (rc) return rc;
   return launch_select_probes(scores, sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, probe_ids, probe_G,
                               probe_E, st);
+}
+
+int32_t rabitq_cand_capacity(int32_t k) {
+  if (k < 1 || k > RABITQ_MAX_K) return RABITQ_EINVAL;
+  int cap = 1;
+  while (cap < k + TILE) cap <<= 1;
+  return cap;
 }
 
 int64_t rabitq_probe_list_scratch_words(int32_t nlist, int64_t nq) {

@@ -119,9 +119,16 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 // the list left at the end) is refined NS candidates per round, G lanes per candidate, and
 // the refined keys go to a per-query pool in LDS.  A pool that fills up is cut back to its
 // k best (exact: it only compares final keys) and its k-th key then rejects later keys.
-// Output: up to k unsorted keys per pair.
+// Output: the surviving keys of each pair, unsorted, at most `pool` = next_pow2(k + 64) of them.
 // ---------------------------------------------------------------------------------
 constexpr int LIST_CAP = 512;
+
+#ifdef RQ_STATS  // development counters: survivors, refine rounds, compactions, flushes
+__device__ unsigned long long g_scan_stats[8];
+#define RQ_STAT(i, v) do { if (threadIdx.x == 0) atomicAdd(&g_scan_stats[i], (unsigned long long)(v)); } while (0)
+#else
+#define RQ_STAT(i, v) do { } while (0)
+#endif
 
 __device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   __syncthreads();
@@ -191,7 +198,10 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   // refine everything in the list (F > 0 only); wave-uniform control flow throughout
   auto flush = [&]() {
     __syncthreads();
+    RQ_STAT(0, list_cnt);
+    RQ_STAT(3, 1);
     for (int base = 0; base < list_cnt; base += NS) {
+      RQ_STAT(1, 1);
       const int idx = base + lane / G, t = lane % G;
       const bool valid = idx < list_cnt;
       const uint32_t e = valid ? list[idx] : 0u;
@@ -213,6 +223,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       for (int jj = 0; jj < QW; ++jj) {
         const int cj = pool_cnt[jj];
         if (cj + NS > a.pool) {
+          RQ_STAT(2, 1);
           uint64_t* pool = pools + (size_t)jj * a.pool;
           const int nc = pool_compact(pool, a.pool, cj, a.k);
           if (lane == 0) {
@@ -273,14 +284,14 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 #pragma unroll
     for (int j = 0; j < QW; ++j) cnt[j] = pool_cnt[j];
   }
+  // every key still in a pool goes out, unsorted; the per-query merge selects among them
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
-    uint64_t* pool = pools + (size_t)j * a.pool;
-    if (cnt[j] > a.k) cnt[j] = pool_compact(pool, a.pool, cnt[j], a.k);
+    const uint64_t* pool = pools + (size_t)j * a.pool;
     __syncthreads();
     if (lane == 0) a.cand_cnt[pj[j]] = cnt[j];
-    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.k + e] = pool[e];
+    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.pool + e] = pool[e];
   }
 }
 
@@ -357,5 +368,16 @@ bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, unsigned grid, bool dbg
     default: return false;
   }
 }
+
+#if defined(RQ_STATS) && RQ_PART == 0
+extern "C" int rabitq_debug_scan_stats(unsigned long long* out, int reset) {
+  if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_scan_stats), sizeof(g_scan_stats)) != hipSuccess) return -3;
+  if (reset) {
+    unsigned long long z[8] = {0};
+    if (hipMemcpyToSymbol(HIP_SYMBOL(g_scan_stats), z, sizeof(z)) != hipSuccess) return -3;
+  }
+  return 0;
+}
+#endif
 
 }  // namespace rq

@@ -219,22 +219,68 @@ int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nli
 
 // ---------------------------------------------------------------------------------
 // Section 3.3.5: merge the nprobe cluster-local lists of one query into its top-k.
+// The lists (cnt[j] keys at stride `cap`) are first packed into LDS; the selection then
+// runs on the packed keys.  A query with more candidates than the LDS buffer holds is
+// selected straight from global memory instead.
 // ---------------------------------------------------------------------------------
+constexpr int MERGE_LDS_KEYS = 3072;
+
 __global__ __launch_bounds__(256) void merge_kernel(const uint64_t* __restrict__ cand_keys,
-                                                   const int32_t* __restrict__ cand_cnt, int k, int kpad, int nprobe,
-                                                   int metric, int64_t* __restrict__ out_ids,
+                                                   const int32_t* __restrict__ cand_cnt, int k, int kpad, int cap,
+                                                   int nprobe, int metric, int64_t* __restrict__ out_ids,
                                                    float* __restrict__ out_dists) {
   extern __shared__ uint64_t sel_out[];  // [kpad]
+  __shared__ uint64_t buf[MERGE_LDS_KEYS];
+  __shared__ int offs[RABITQ_MAX_NPROBE + 1];
   __shared__ uint32_t sh[260];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t q = blockIdx.x;
-  const uint64_t* keys = cand_keys + q * nprobe * (int64_t)k;
+  const uint64_t* keys = cand_keys + q * nprobe * (int64_t)cap;
   const int32_t* cnt = cand_cnt + q * nprobe;
-  auto key_at = [&](int i) -> uint64_t {
-    const int j = i / k, e = i - j * k;
-    return (e < cnt[j]) ? keys[i] : KEY_NONE;
-  };
-  block_select_smallest(nprobe * k, k, kpad, key_at, sel_out, sh);
-  for (int r = threadIdx.x; r < k; r += blockDim.x) {
+  // exclusive scan of the list lengths (nprobe <= 1024: four per thread)
+  int loc[4], sum = 0;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = tid * 4 + i;
+    loc[i] = (j < nprobe) ? cnt[j] : 0;
+    sum += loc[i];
+  }
+  int incl = sum;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int o = __shfl_up(incl, d, 64);
+    if (lane >= d) incl += o;
+  }
+  __shared__ int wsum[4];
+  if (lane == 63) wsum[wave] = incl;
+  __syncthreads();
+  int base = incl - sum;
+  for (int w2 = 0; w2 < wave; ++w2) base += wsum[w2];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int j = tid * 4 + i;
+    if (j < nprobe) offs[j] = base;
+    base += loc[i];
+  }
+  if (tid == 255) offs[nprobe] = base;
+  __syncthreads();
+  const int total = offs[nprobe];
+  if (total <= MERGE_LDS_KEYS) {
+    for (int j = wave; j < nprobe; j += 4) {
+      const int n = offs[j + 1] - offs[j];
+      for (int e = lane; e < n; e += 64) buf[offs[j] + e] = keys[(int64_t)j * cap + e];
+    }
+    __syncthreads();
+    auto key_at = [&](int i) -> uint64_t { return buf[i]; };
+    block_select_smallest(total, k, kpad, key_at, sel_out, sh);
+  } else {
+    auto key_at = [&](int i) -> uint64_t {
+      const int j = i / cap, e = i - j * cap;
+      return (e < cnt[j]) ? keys[i] : KEY_NONE;
+    };
+    block_select_smallest(nprobe * cap, k, kpad, key_at, sel_out, sh);
+  }
+  for (int r = tid; r < k; r += blockDim.x) {
     const uint64_t key = sel_out[r];
     int64_t id = -1;
     float d = (metric == RABITQ_L2) ? INFINITY : -INFINITY;
@@ -252,8 +298,9 @@ int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq,
                  int64_t* out_ids, float* out_dists, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const int kpad = next_pow2(k);
+  const int cap = next_pow2(k + TILE);
   hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(256), kpad * sizeof(uint64_t), st, cand_keys, cand_cnt, k,
-                     kpad, nprobe, metric, out_ids, out_dists);
+                     kpad, cap, nprobe, metric, out_ids, out_dists);
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }

@@ -24,7 +24,7 @@ TILE = 64
 EXPORTS = [
     "rabitq_index_upload", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
     "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_coarse_probe",
-    "rabitq_probe_list_scratch_words", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
+    "rabitq_probe_list_scratch_words", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
 ]
 
@@ -67,12 +67,15 @@ def load_library() -> C.CDLL:
     lib.rabitq_coarse_probe.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.rabitq_probe_list_scratch_words.argtypes = [i32, i64]
     lib.rabitq_probe_list_scratch_words.restype = i64
+    lib.rabitq_cand_capacity.argtypes = [i32]
+    lib.rabitq_cand_capacity.restype = i32
     lib.rabitq_build_probe_lists.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.rabitq_seed_threshold.argtypes = [vp] + [vp] * 8 + [i64, i32, i32, vp, vp]
     lib.rabitq_scan.argtypes = [vp] + [vp] * 10 + [i64, i32, i32, vp, vp, vp, vp, vp]
     lib.rabitq_merge.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, vp]
     for name in EXPORTS:
-        if name not in ("rabitq_last_error", "rabitq_index_info", "rabitq_probe_list_scratch_words"):
+        if name not in ("rabitq_last_error", "rabitq_index_info", "rabitq_probe_list_scratch_words",
+                        "rabitq_cand_capacity"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -230,7 +233,10 @@ class Index:
     def scan(self, q_rot, prep, probes, pair_off, pair_ids, tau, k, dbg_off=None):
         nq, nprobe = probes["probe_G"].shape
         dev = q_rot.device
-        cand_keys = torch.empty((nq * nprobe, k), dtype=torch.int64, device=dev)
+        cap = load_library().rabitq_cand_capacity(k)
+        if cap < 0:
+            _check(cap)
+        cand_keys = torch.empty((nq * nprobe, cap), dtype=torch.int64, device=dev)
         cand_cnt = torch.empty(nq * nprobe, dtype=torch.int32, device=dev)
         dbg_ip = None
         if dbg_off is not None:
