@@ -35,34 +35,117 @@ __device__ inline void block_bitonic_sort(uint64_t* keys, int n) {
 // ---------------------------------------------------------------------------------
 // Workgroup-wide selection of the K smallest of n u64 keys produced by key_at(i),
 // written in ascending order to out[0..Kpad) (Kpad = power of two >= K, the tail is
-// KEY_NONE).  Keys are expected to be distinct (their low word is an index or id), so
-// the result is unique.  MSB-first radix select, 8 bits per pass, stops as soon as the
-// bucket that holds the K-th key is taken whole.
-// sh: LDS scratch of at least 260 u32.  blockDim.x must be a multiple of 64.
+// KEY_NONE).  key_at may return KEY_NONE for an absent entry.  Keys are distinct (their
+// low word is an index or id), so the result is unique.
+//
+// MSB-first radix select that (1) skips the bits all keys share (estimates of one query lie
+// in a narrow range, so their exponent bits are equal and would all hit one histogram bin),
+// (2) stops as soon as the bucket holding the K-th key is taken whole, and (3) finishes a
+// bucket of at most 64 keys inside one wavefront by ranking them against each other.
+// blockDim.x must be a multiple of 64, at most 1024.
 // ---------------------------------------------------------------------------------
+// Wavefront reductions on the VALU's data-parallel primitives (no LDS round trips).
+// After the four row steps every lane of a 16-lane row holds the row's result; the four
+// rows are then combined through scalar lane reads.
+template <typename Op>
+__device__ inline uint32_t wave_reduce_u32(uint32_t v, Op op) {
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0xB1, 0xF, 0xF, true));   // quad_perm [1,0,3,2]
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x4E, 0xF, 0xF, true));   // quad_perm [2,3,0,1]
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x141, 0xF, 0xF, true));  // row_half_mirror
+  v = op(v, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x140, 0xF, 0xF, true));  // row_mirror
+  const uint32_t a = __builtin_amdgcn_readlane((int)v, 0), b = __builtin_amdgcn_readlane((int)v, 16);
+  const uint32_t c = __builtin_amdgcn_readlane((int)v, 32), d = __builtin_amdgcn_readlane((int)v, 48);
+  return op(op(a, b), op(c, d));
+}
+
+template <typename Op>
+__device__ inline uint64_t wave_reduce_u64(uint64_t v, Op op) {
+  auto step = [&](int ctrl_id) {
+    int lo = (int)(uint32_t)v, hi = (int)(uint32_t)(v >> 32);
+    int olo, ohi;
+    switch (ctrl_id) {
+      case 0: olo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, true); ohi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, true); break;
+      case 1: olo = __builtin_amdgcn_update_dpp(0, lo, 0x4E, 0xF, 0xF, true); ohi = __builtin_amdgcn_update_dpp(0, hi, 0x4E, 0xF, 0xF, true); break;
+      case 2: olo = __builtin_amdgcn_update_dpp(0, lo, 0x141, 0xF, 0xF, true); ohi = __builtin_amdgcn_update_dpp(0, hi, 0x141, 0xF, 0xF, true); break;
+      default: olo = __builtin_amdgcn_update_dpp(0, lo, 0x140, 0xF, 0xF, true); ohi = __builtin_amdgcn_update_dpp(0, hi, 0x140, 0xF, 0xF, true); break;
+    }
+    v = op(v, ((uint64_t)(uint32_t)ohi << 32) | (uint32_t)olo);
+  };
+  step(0); step(1); step(2); step(3);
+  auto rd = [&](int l) {
+    return ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), l) << 32) |
+           (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, l);
+  };
+  return op(op(rd(0), rd(16)), op(rd(32), rd(48)));
+}
+
+struct SelectScratch {
+  uint64_t lo, hi, bound;
+  uint64_t small[64];
+  uint64_t wlo[16], whi[16];
+  uint32_t hist[256];
+  uint32_t wcnt[16];
+  uint32_t digit, need, bucket, cnt, nvalid;
+};
+
 template <typename KeyFn>
-__device__ inline void block_select_smallest(int n, int K, int Kpad, KeyFn key_at, uint64_t* out, uint32_t* sh) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  uint32_t* hist = sh;              // [256]
-  uint32_t* s_digit = sh + 256;     // [1]
-  uint32_t* s_need = sh + 257;      // [1]
-  uint32_t* s_take_all = sh + 258;  // [1]
-  uint32_t* s_cnt = sh + 259;       // [1]
-  uint64_t bound = KEY_NONE;        // select keys <= bound
-  if (n > K) {
-    uint64_t prefix = 0;
+__device__ inline void block_select_smallest(int n, int K, int Kpad, KeyFn key_at, uint64_t* out, SelectScratch* sh) {
+  const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wave = tid >> 6, nw = nt >> 6;
+  // range and count of the present keys
+  uint64_t lo = KEY_NONE, hi = 0ull;
+  uint32_t nv = 0;
+  for (int i = tid; i < n; i += nt) {
+    const uint64_t key = key_at(i);
+    if (key != KEY_NONE) {
+      lo = key < lo ? key : lo;
+      hi = key > hi ? key : hi;
+      ++nv;
+    }
+  }
+  lo = wave_reduce_u64(lo, [](uint64_t a, uint64_t b) { return a < b ? a : b; });
+  hi = wave_reduce_u64(hi, [](uint64_t a, uint64_t b) { return a > b ? a : b; });
+  nv = wave_reduce_u32(nv, [](uint32_t a, uint32_t b) { return a + b; });
+  if (lane == 0) {
+    sh->wlo[wave] = lo;
+    sh->whi[wave] = hi;
+    sh->wcnt[wave] = nv;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint64_t l = KEY_NONE, h = 0ull;
+    uint32_t c = 0;
+    for (int w = 0; w < nw; ++w) {
+      l = sh->wlo[w] < l ? sh->wlo[w] : l;
+      h = sh->whi[w] > h ? sh->whi[w] : h;
+      c += sh->wcnt[w];
+    }
+    sh->lo = l;
+    sh->hi = h;
+    sh->nvalid = c;
+  }
+  __syncthreads();
+  uint64_t bound = KEY_NONE;  // select present keys <= bound
+  if (sh->nvalid > (uint32_t)K && sh->lo != sh->hi) {
+    lo = sh->lo;
+    hi = sh->hi;
+    const int top = 63 - __clzll((long long)(lo ^ hi));  // highest bit in which two keys differ
+    int width = min(8, top + 1);
+    int shift = top + 1 - width;
+    uint64_t pmask = (top == 63) ? 0ull : (~0ull << (top + 1));
+    uint64_t prefix = lo & pmask;
     uint32_t need = (uint32_t)K;
-    for (int shift = 56; shift >= 0; shift -= 8) {
-      for (int i = tid; i < 256; i += nt) hist[i] = 0;
+    while (true) {
+      for (int i = tid; i < 256; i += nt) sh->hist[i] = 0;
       __syncthreads();
-      const uint64_t hi_mask = (shift == 56) ? 0ull : (~0ull << (shift + 8));
+      const uint32_t dmask = (1u << width) - 1u;
       for (int i = tid; i < n; i += nt) {
         const uint64_t key = key_at(i);
-        if ((key & hi_mask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & 255u], 1u);
+        if (key != KEY_NONE && (key & pmask) == prefix) atomicAdd(&sh->hist[(uint32_t)(key >> shift) & dmask], 1u);
       }
       __syncthreads();
       if (tid < 64) {
-        const uint32_t c0 = hist[4 * tid], c1 = hist[4 * tid + 1], c2 = hist[4 * tid + 2], c3 = hist[4 * tid + 3];
+        const uint32_t c0 = sh->hist[4 * tid], c1 = sh->hist[4 * tid + 1], c2 = sh->hist[4 * tid + 2],
+                       c3 = sh->hist[4 * tid + 3];
         const uint32_t s = c0 + c1 + c2 + c3;
         uint32_t incl = s;
 #pragma unroll
@@ -77,29 +160,50 @@ __device__ inline void block_select_smallest(int n, int K, int Kpad, KeyFn key_a
           else if (rem <= c0 + c1) { digit = 1; cnt = c1; rem -= c0; }
           else if (rem <= c0 + c1 + c2) { digit = 2; cnt = c2; rem -= c0 + c1; }
           else { digit = 3; cnt = c3; rem -= c0 + c1 + c2; }
-          *s_digit = 4 * tid + digit;
-          *s_need = rem;
-          *s_take_all = (cnt == rem) ? 1u : 0u;
+          sh->digit = 4 * tid + digit;
+          sh->need = rem;
+          sh->bucket = cnt;
+          sh->cnt = 0;
         }
       }
       __syncthreads();
-      prefix |= (uint64_t)(*s_digit) << shift;
-      need = *s_need;
-      const bool take_all = (*s_take_all) != 0u;
-      __syncthreads();
-      if (take_all || shift == 0) {
+      prefix |= (uint64_t)sh->digit << shift;
+      pmask |= (uint64_t)dmask << shift;
+      need = sh->need;
+      const uint32_t bucket = sh->bucket;
+      if (bucket == need || shift == 0) {  // the whole bucket is selected
         bound = prefix | (shift == 0 ? 0ull : ((1ull << shift) - 1ull));
         break;
       }
+      if (bucket <= 64u) {  // rank the bucket's keys against each other in one wavefront
+        for (int i = tid; i < n; i += nt) {
+          const uint64_t key = key_at(i);
+          if (key != KEY_NONE && (key & pmask) == prefix) sh->small[atomicAdd(&sh->cnt, 1u)] = key;
+        }
+        __syncthreads();
+        if (tid < (int)bucket) {
+          const uint64_t mine = sh->small[tid];
+          uint32_t rank = 0;
+          for (uint32_t m = 0; m < bucket; ++m) rank += (sh->small[m] < mine) ? 1u : 0u;
+          if (rank == need - 1u) sh->bound = mine;
+        }
+        __syncthreads();
+        bound = sh->bound;
+        break;
+      }
+      width = min(8, shift);
+      shift -= width;
+      __syncthreads();
     }
   }
-  if (tid == 0) *s_cnt = 0;
+  __syncthreads();
+  if (tid == 0) sh->cnt = 0;
   for (int i = tid; i < Kpad; i += nt) out[i] = KEY_NONE;
   __syncthreads();
   for (int i = tid; i < n; i += nt) {
     const uint64_t key = key_at(i);
     if (key <= bound && key != KEY_NONE) {
-      const uint32_t pos = atomicAdd(s_cnt, 1u);
+      const uint32_t pos = atomicAdd(&sh->cnt, 1u);
       if (pos < (uint32_t)Kpad) out[pos] = key;
     }
   }
@@ -136,7 +240,13 @@ __device__ inline int ip_bitplanes(const uint32_t (&cw)[W], const_u32_ptr pl) {
     p2 = bcnt_acc(cw[w] & pl[2 * W + w], p2);
     p3 = bcnt_acc(cw[w] & pl[3 * W + w], p3);
   }
-  return (int)(p0 + 2u * p1 + 4u * p2) - (int)(8u * p3);
+  // p0 + 2 p1 + 4 p2 - 8 p3 in three instructions
+  uint32_t t;
+  asm("v_lshl_add_u32 %0, %1, 1, %2" : "=v"(t) : "v"(p1), "v"(p0));
+  asm("v_lshl_add_u32 %0, %1, 2, %2" : "=v"(t) : "v"(p2), "v"(t));
+  int r;
+  asm("v_mad_i32_i24 %0, %1, -8, %2" : "=v"(r) : "v"(p3), "v"(t));
+  return r;
 }
 
 // ---------------------------------------------------------------------------------

@@ -35,7 +35,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   uint64_t* best = chunk + SEED_CHUNK_TILES * TILE;
   uint64_t* out = best + kpad;
   float* qf = reinterpret_cast<float*>(out + kpad);
-  __shared__ uint32_t sh[260];
+  __shared__ SelectScratch sh;
   __shared__ int s_rank;
   __shared__ uint32_t s_max;
 
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     __syncthreads();
     const int nc = nt * TILE;
     auto key_at = [&](int i) -> uint64_t { return i < nc ? chunk[i] : best[i - nc]; };
-    block_select_smallest(nc + kpad, a.k, kpad, key_at, out, sh);
+    block_select_smallest(nc + kpad, a.k, kpad, key_at, out, &sh);
     for (int i = tid; i < kpad; i += 256) best[i] = out[i];
     __syncthreads();
   }

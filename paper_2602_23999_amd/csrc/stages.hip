@@ -83,11 +83,11 @@ __global__ __launch_bounds__(256) void select_probes_kernel(const float* __restr
                                                            float* __restrict__ probe_G,
                                                            float* __restrict__ probe_E) {
   extern __shared__ uint64_t sel_out[];  // [npad]
-  __shared__ uint32_t sh[260];
+  __shared__ SelectScratch sh;
   const int64_t q = blockIdx.x;
   const float* row = scores + q * nlist;
   auto key_at = [&](int i) -> uint64_t { return make_key(row[i], (uint32_t)i); };
-  block_select_smallest(nlist, nprobe, npad, key_at, sel_out, sh);
+  block_select_smallest(nlist, nprobe, npad, key_at, sel_out, &sh);
   for (int r = threadIdx.x; r < nprobe; r += blockDim.x) {
     const uint64_t key = sel_out[r];
     const int c = (int)(uint32_t)key;
@@ -232,7 +232,7 @@ __global__ __launch_bounds__(256) void merge_kernel(const uint64_t* __restrict__
   extern __shared__ uint64_t sel_out[];  // [kpad]
   __shared__ uint64_t buf[MERGE_LDS_KEYS];
   __shared__ int offs[RABITQ_MAX_NPROBE + 1];
-  __shared__ uint32_t sh[260];
+  __shared__ SelectScratch sh;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int64_t q = blockIdx.x;
   const uint64_t* keys = cand_keys + q * nprobe * (int64_t)cap;
@@ -272,13 +272,13 @@ __global__ __launch_bounds__(256) void merge_kernel(const uint64_t* __restrict__
     }
     __syncthreads();
     auto key_at = [&](int i) -> uint64_t { return buf[i]; };
-    block_select_smallest(total, k, kpad, key_at, sel_out, sh);
+    block_select_smallest(total, k, kpad, key_at, sel_out, &sh);
   } else {
     auto key_at = [&](int i) -> uint64_t {
       const int j = i / cap, e = i - j * cap;
       return (e < cnt[j]) ? keys[i] : KEY_NONE;
     };
-    block_select_smallest(nprobe * cap, k, kpad, key_at, sel_out, sh);
+    block_select_smallest(nprobe * cap, k, kpad, key_at, sel_out, &sh);
   }
   for (int r = tid; r < k; r += blockDim.x) {
     const uint64_t key = sel_out[r];
