@@ -89,6 +89,36 @@ typedef struct {
  * offsets[nlist] != n), RABITQ_ENOMEM, RABITQ_EHIP.  *out is untouched on error. */
 int rabitq_index_upload(const rabitq_index_desc* desc, rabitq_index_t* out, void* stream);
 
+/*
+ * Index build on the device (Section 3.2): the vectors are rotated by P, k-means (plain
+ * Lloyd) runs in the rotated space on a training subset, every vector is assigned to its
+ * nearest centroid, normalised with respect to it, and quantised by the two-phase grid
+ * search over the rescaling factor (N_coarse = 64 samples over [0, m_B*2^(B-1)/max|o'|] with
+ * m_B = 6, 4.5, 2.5 for B = 2, 3, 4 and 1.5 above, then N_fine = 32 around the best); codes, factors and ids are written in the layout above.
+ * Deterministic: no order-dependent atomics anywhere.
+ *   data: device, [n*D] fp32 row-major raw vectors (not modified)
+ * The training subset is taken at a fixed stride through the data and the initial centroids
+ * at a fixed stride through the training subset (shuffle the data first if its order is not
+ * random).  Synchronises `stream`.  Errors as for rabitq_index_upload.
+ */
+typedef struct {
+  int32_t dim, nlist;
+  int64_t n;
+  int32_t total_bits, metric;
+  int32_t kmeans_iters;  /* Lloyd iterations, >= 0                                        */
+  int64_t train_size;    /* vectors used for k-means; <= 0 or > n: all of them            */
+  float epsilon0;        /* multiplier of the 1-bit error bound stored as f_err (e.g. 1.9) */
+  const float* rotation; /* host, [D*D] row-major orthogonal P                            */
+} rabitq_build_params;
+int rabitq_index_build(const rabitq_build_params* params, const float* data, rabitq_index_t* out, void* stream);
+
+/* Copies the arrays of an index back to HOST buffers laid out as in rabitq_index_desc (sizes
+ * from rabitq_index_info: n_tiles, n_slots, long_field_bits).  Any pointer may be NULL to
+ * skip that array.  Device-synchronising.  Errors: RABITQ_EINVAL, RABITQ_EHIP. */
+int rabitq_index_export(rabitq_index_t index, float* rotation, float* centroids, int64_t* offsets,
+                        uint32_t* short_codes, float* short_factors, uint32_t* long_codes, float* long_factors,
+                        int32_t* ids);
+
 /* Frees the handle and everything it owns (device-synchronising).  NULL is allowed. */
 int rabitq_index_free(rabitq_index_t index);
 
@@ -115,7 +145,7 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  * Errors: RABITQ_EINVAL for an unknown name or value. */
 int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
-/* Host-visible sizes of an uploaded index: name in {"n_tiles","n_slots","dim","nlist",
+/* Host-visible sizes of an uploaded index: name in {"n","n_tiles","n_slots","dim","nlist",
  * "total_bits","long_field_bits","metric"}.  Returns the value, or a negative status. */
 int64_t rabitq_index_info(rabitq_index_t index, const char* name);
 

@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librabitq_hip.so")
 # (source, extra defines, object name)
 UNITS = [("api.hip", [], "api.o"), ("gemm.hip", [], "gemm.o"), ("stages.hip", [], "stages.o"),
-         ("scan_dispatch.hip", [], "scan_dispatch.o"),
+         ("scan_dispatch.hip", [], "scan_dispatch.o"), ("build.hip", [], "build.o"),
          ("scan.hip", ["-DRQ_PART=0"], "scan0.o"), ("scan.hip", ["-DRQ_PART=1"], "scan1.o"),
          ("scan.hip", ["-DRQ_PART=2"], "scan2.o")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

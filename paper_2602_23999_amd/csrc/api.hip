@@ -190,6 +190,60 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
   return RABITQ_OK;
 }
 
+int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_index_t* out, void* stream) {
+  if (!p || !out) { set_error("build: null argument"); return RABITQ_EINVAL; }
+  if (p->dim < 32 || p->dim > 2048 || (p->dim % 32) != 0) { set_error("build: dim must be a multiple of 32 in 32..2048"); return RABITQ_EINVAL; }
+  if (p->nlist < 1 || p->n < 0 || p->n > 0x7fffffff) { set_error("build: bad nlist or n"); return RABITQ_EINVAL; }
+  if (p->total_bits < 1 || p->total_bits > 8) { set_error("build: total_bits must be 1..8"); return RABITQ_EINVAL; }
+  if (p->metric != RABITQ_L2 && p->metric != RABITQ_IP) { set_error("build: bad metric"); return RABITQ_EINVAL; }
+  if (p->kmeans_iters < 0 || !(p->epsilon0 >= 0.f)) { set_error("build: bad kmeans_iters or epsilon0"); return RABITQ_EINVAL; }
+  if (!p->rotation || (!data && p->n > 0)) { set_error("build: null array"); return RABITQ_EINVAL; }
+  rabitq_index* ix = new (std::nothrow) rabitq_index();
+  if (!ix) { set_error("build: out of host memory"); return RABITQ_ENOMEM; }
+  ix->dim = p->dim; ix->W = p->dim / 32; ix->nlist = p->nlist; ix->n = p->n; ix->total_bits = p->total_bits;
+  ix->metric = p->metric; ix->F = field_bits_of(p->total_bits); ix->LW = p->dim * ix->F / 32;
+  hipError_t he = hipGetDevice(&ix->device);
+  int rc = (he == hipSuccess) ? RABITQ_OK : hip_fail(he, "hipGetDevice");
+  if (rc == RABITQ_OK)
+    rc = build_index_device(ix, data, p->rotation, p->kmeans_iters, p->train_size, p->epsilon0, (hipStream_t)stream);
+  if (rc != RABITQ_OK) {
+    (void)hipDeviceSynchronize();
+    free_index(ix);
+    return rc;
+  }
+  *out = ix;
+  return RABITQ_OK;
+}
+
+int rabitq_index_export(rabitq_index_t ix, float* rotation, float* centroids, int64_t* offsets, uint32_t* short_codes,
+                        float* short_factors, uint32_t* long_codes, float* long_factors, int32_t* ids) {
+  if (!ix) { set_error("export: null index"); return RABITQ_EINVAL; }
+  RQ_HIP(hipDeviceSynchronize());
+  const int D = ix->dim, nlist = ix->nlist;
+  const int64_t slots = ix->n_slots, tiles = ix->n_tiles;
+  if (rotation) RQ_HIP(hipMemcpy(rotation, ix->rotation, (size_t)D * D * sizeof(float), hipMemcpyDeviceToHost));
+  if (centroids) {
+    std::vector<float> ct((size_t)D * nlist);
+    RQ_HIP(hipMemcpy(ct.data(), ix->centroids_t, ct.size() * sizeof(float), hipMemcpyDeviceToHost));
+    for (int c = 0; c < nlist; ++c)
+      for (int i = 0; i < D; ++i) centroids[(size_t)c * D + i] = ct[(size_t)i * nlist + c];
+  }
+  if (offsets) {
+    std::vector<int32_t> cs(nlist);
+    RQ_HIP(hipMemcpy(cs.data(), ix->cluster_size, (size_t)nlist * sizeof(int32_t), hipMemcpyDeviceToHost));
+    offsets[0] = 0;
+    for (int c = 0; c < nlist; ++c) offsets[c + 1] = offsets[c] + cs[c];
+  }
+  if (short_codes && tiles) RQ_HIP(hipMemcpy(short_codes, ix->short_codes, (size_t)tiles * ix->W * TILE * 4, hipMemcpyDeviceToHost));
+  if (short_factors && tiles) RQ_HIP(hipMemcpy(short_factors, ix->short_factors, (size_t)tiles * 3 * TILE * 4, hipMemcpyDeviceToHost));
+  if (ids && slots) RQ_HIP(hipMemcpy(ids, ix->ids, (size_t)slots * 4, hipMemcpyDeviceToHost));
+  if (ix->total_bits > 1) {
+    if (long_codes && slots) RQ_HIP(hipMemcpy(long_codes, ix->long_codes, (size_t)slots * ix->LW * 4, hipMemcpyDeviceToHost));
+    if (long_factors && slots) RQ_HIP(hipMemcpy(long_factors, ix->long_factors, (size_t)slots * 2 * 4, hipMemcpyDeviceToHost));
+  }
+  return RABITQ_OK;
+}
+
 int rabitq_index_free(rabitq_index_t ix) {
   if (!ix) return RABITQ_OK;
   (void)hipDeviceSynchronize();
@@ -219,6 +273,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
 
 int64_t rabitq_index_info(rabitq_index_t ix, const char* name) {
   if (!ix || !name) { set_error("index_info: null argument"); return RABITQ_EINVAL; }
+  if (!std::strcmp(name, "n")) return ix->n;
   if (!std::strcmp(name, "n_tiles")) return ix->n_tiles;
   if (!std::strcmp(name, "n_slots")) return ix->n_slots;
   if (!std::strcmp(name, "dim")) return ix->dim;

@@ -21,8 +21,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
   __shared__ float Bs[BK][BN];
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  const int64_t m0 = (int64_t)blockIdx.y * BM;
-  const int n0 = blockIdx.x * BN;
+  const int64_t m0 = (int64_t)blockIdx.x * BM;
+  const int n0 = blockIdx.y * BN;
   floatx16 acc0 = {0}, acc1 = {0};
 
   const int a_row = tid >> 1, a_half = tid & 1;        // A tile: 128 rows x 16 k, 8 floats per thread
@@ -77,6 +77,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
       float v = j == 0 ? acc0[r] : acc1[r];
       if (MODE == 1) v = rv + colv[n] - 2.0f * v;
       if (MODE == 2) v = -v;
+      if (MODE == 3) v = colv[n] - 2.0f * v;
       C[m * (int64_t)N + n] = v;
     }
   }
@@ -89,15 +90,16 @@ int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int 
     set_error("gemm: K must be a multiple of 16 and N positive");
     return RABITQ_EINVAL;
   }
-  dim3 grid((N + BN - 1) / BN, (unsigned)((M + BM - 1) / BM));
-  if (grid.y > 65535u * 16u) {
-    set_error("gemm: too many rows");
+  if ((M + BM - 1) / BM > 0x7fffffff || (N + BN - 1) / BN > 65535) {
+    set_error("gemm: matrix too large");
     return RABITQ_EINVAL;
   }
+  dim3 grid((unsigned)((M + BM - 1) / BM), (unsigned)((N + BN - 1) / BN));
   switch (mode) {
     case 0: hipLaunchKernelGGL(gemm_kernel<0>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     case 1: hipLaunchKernelGGL(gemm_kernel<1>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     case 2: hipLaunchKernelGGL(gemm_kernel<2>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
+    case 3: hipLaunchKernelGGL(gemm_kernel<3>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     default: set_error("gemm: bad mode"); return RABITQ_EINVAL;
   }
   RQ_HIP(hipGetLastError());

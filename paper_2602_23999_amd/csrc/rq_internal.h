@@ -90,7 +90,7 @@ __host__ __device__ inline float ord2f(uint32_t o) {
 
 // ---- launchers (each returns a rabitq_status) ----
 // C[M,N] = A[M,K] * B[K,N], row-major fp32.  mode 0: plain.  mode 1 (L2 coarse):
-// C = rowv[m] + colv[n] - 2*acc.  mode 2 (IP coarse): C = -acc.
+// C = rowv[m] + colv[n] - 2*acc.  mode 2 (IP coarse): C = -acc.  mode 3 (assignment): C = colv[n] - 2*acc.
 int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,
                 const float* colv, hipStream_t st);
 int launch_query_prep(const float* q_rot, int64_t nq, int D, uint32_t* planes, float* delta, int32_t* sum_qhat,
@@ -111,5 +111,7 @@ int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
 int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
                  int64_t* out_ids, float* out_dists, hipStream_t st);
 int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
+int build_index_device(rabitq_index* ix, const float* data, const float* rotation_host, int kmeans_iters,
+                       int64_t train_size, float eps0, hipStream_t st);
 
 }  // namespace rq

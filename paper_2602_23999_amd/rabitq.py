@@ -22,7 +22,7 @@ QUERY_BITS = 4
 TILE = 64
 
 EXPORTS = [
-    "rabitq_index_upload", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
+    "rabitq_index_upload", "rabitq_index_build", "rabitq_index_export", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
     "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_coarse_probe",
     "rabitq_probe_list_scratch_words", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
@@ -38,6 +38,12 @@ class _Desc(C.Structure):
                 ("metric", C.c_int32), ("rotation", C.c_void_p), ("centroids", C.c_void_p),
                 ("offsets", C.c_void_p), ("short_codes", C.c_void_p), ("short_factors", C.c_void_p),
                 ("long_codes", C.c_void_p), ("long_factors", C.c_void_p), ("ids", C.c_void_p)]
+
+
+class _BuildParams(C.Structure):
+    _fields_ = [("dim", C.c_int32), ("nlist", C.c_int32), ("n", C.c_int64), ("total_bits", C.c_int32),
+                ("metric", C.c_int32), ("kmeans_iters", C.c_int32), ("train_size", C.c_int64),
+                ("epsilon0", C.c_float), ("rotation", C.c_void_p)]
 
 
 _lib = None
@@ -56,6 +62,8 @@ def load_library() -> C.CDLL:
     lib.rabitq_last_error.restype = C.c_char_p
     lib.rabitq_last_error.argtypes = []
     lib.rabitq_index_upload.argtypes = [C.POINTER(_Desc), C.POINTER(vp), vp]
+    lib.rabitq_index_build.argtypes = [C.POINTER(_BuildParams), vp, C.POINTER(vp), vp]
+    lib.rabitq_index_export.argtypes = [vp] * 9
     lib.rabitq_index_free.argtypes = [vp]
     lib.rabitq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.rabitq_set_option.argtypes = [vp, C.c_char_p, i64]
@@ -135,6 +143,44 @@ class Index:
         self._keep = None
         self.dim, self.nlist, self.n, self.total_bits, self.metric = dim, nlist, n, total_bits, metric
         self.W = W
+
+    @classmethod
+    def build(cls, data: torch.Tensor, nlist: int, total_bits: int, rotation, metric: str = "l2",
+              kmeans_iters: int = 10, train_size: int = 0, epsilon0: float = 1.9) -> "Index":
+        """rabitq_index_build: builds the index on the device from raw vectors `data` [n, D]
+        (CUDA fp32) and a host rotation matrix [D, D]."""
+        lib = load_library()
+        n, dim = data.shape
+        rot = np.ascontiguousarray(rotation, dtype=np.float32)
+        if rot.shape != (dim, dim):
+            raise RabitqError("rotation must be [D, D]")
+        prm = _BuildParams(dim, nlist, n, total_bits, {"l2": 0, "ip": 1}[metric], kmeans_iters, train_size, epsilon0,
+                           rot.ctypes.data)
+        h = C.c_void_p()
+        _check(lib.rabitq_index_build(C.byref(prm), _dev(data, torch.float32), C.byref(h), _stream()))
+        self = cls.__new__(cls)
+        self._h, self._keep = h, None
+        self.dim, self.nlist, self.n, self.total_bits, self.metric, self.W = dim, nlist, n, total_bits, metric, dim // 32
+        return self
+
+    def export(self) -> dict:
+        """rabitq_index_export: host numpy arrays in the layout of rabitq_index_desc."""
+        lib = load_library()
+        D, nlist, W = self.dim, self.nlist, self.W
+        tiles, slots, F = self.index_info("n_tiles"), self.index_info("n_slots"), self.index_info("long_field_bits")
+        out = dict(dim=D, nlist=nlist, n=self.n, total_bits=self.total_bits, metric=self.metric,
+                   rotation=np.empty((D, D), np.float32), centroids=np.empty((nlist, D), np.float32),
+                   offsets=np.empty(nlist + 1, np.int64), short_codes=np.empty(tiles * W * TILE, np.uint32),
+                   short_factors=np.empty(tiles * 3 * TILE, np.float32), ids=np.empty(slots, np.int32),
+                   long_codes=None, long_factors=None)
+        if self.total_bits > 1:
+            out["long_codes"] = np.empty(slots * D * F // 32, np.uint32)
+            out["long_factors"] = np.empty(slots * 2, np.float32)
+        p = lambda a: None if a is None else a.ctypes.data
+        _check(lib.rabitq_index_export(self._h, p(out["rotation"]), p(out["centroids"]), p(out["offsets"]),
+                                       p(out["short_codes"]), p(out["short_factors"]), p(out["long_codes"]),
+                                       p(out["long_factors"]), p(out["ids"])))
+        return out
 
     def close(self):
         if getattr(self, "_h", None):
