@@ -100,6 +100,7 @@ def main():
     ap.add_argument("--workload", default="l2_128")
     ap.add_argument("--nprobe", type=int, default=0, help="fix the operating point instead of choosing it by recall")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
+    ap.add_argument("--scan-impl", type=int, default=0, help="0: popcount scan (default), 1: matrix-core scan")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
@@ -153,6 +154,7 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t) / steps
 
+    gi.set_option("scan_impl", args.scan_impl)
     sweep = []
     nprobes = [args.nprobe] if args.nprobe else [p for p in w.nprobes if p <= w.nlist]
     for p in nprobes:
@@ -193,7 +195,8 @@ def main():
                    "query_vector_evaluations": qv, "index_builder": "rabitq_index_build (HIP: k-means + two-phase grid search)",
                    "index_build_s": round(build_s, 4)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "kernel": "scan_kernel",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic if args.scan_impl == 0 else None,
+                     "kernel": "scan_kernel" if args.scan_impl == 0 else "scan_mfma_kernel",
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
     }
     if not args.no_cpu_baseline:

@@ -142,6 +142,10 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *   "prune"   1 (default): filter with the per-query seeded threshold (Section 3.3.4);
  *             0: refine every vector of every probed cluster (the unpruned definition).
  *   "profile" n: see rabitq_stage_ms.
+ *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per
+ *             wavefront; 1: the same integer inner products on the matrix cores (the sign
+ *             bits of a tile are expanded to int8 once and contracted against 16 queries'
+ *             qhat with v_mfma_i32_16x16x64_i8).  Results are identical; only speed differs.
  * Errors: RABITQ_EINVAL for an unknown name or value. */
 int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
@@ -167,12 +171,27 @@ int rabitq_stage_ms(rabitq_index_t index, float* out_ms, int32_t* out_calls);
 /* Section 3.3.1: q_rot [nq*D] = queries [nq*D] x P (fp32 MFMA). */
 int rabitq_rotate(rabitq_index_t index, const float* queries, int64_t nq, float* q_rot, void* stream);
 
-/* Section 3.3.3 / 3.4.1(2): per-query representation, computed once per query.
+/* Section 3.3.3 / 3.4.1(2): the per-query representation, computed once per query and
+ * reused by all of its cluster scans.  All members are DEVICE pointers supplied by the caller.
  *   planes   [nq][4][W] u32 two's-complement bit-planes of qhat (plane 3 weighs -8)
  *   delta    [nq] fp32  = max|q'|/7 (1 if q' == 0);  qhat = clamp(rint(q'/delta),-7,7)
- *   sum_qhat [nq] i32   = S;   sum_q [nq] fp32 = sum(q');   sq_norm [nq] fp32 = ||q'||^2 */
-int rabitq_query_prep(rabitq_index_t index, const float* q_rot, int64_t nq, uint32_t* planes, float* delta,
-                      int32_t* sum_qhat, float* sum_q, float* sq_norm, void* stream);
+ *   sum_qhat [nq] i32   = S;   sum_q [nq] fp32 = sum(q');   sq_norm [nq] fp32 = ||q'||^2
+ *   qhat8    [nq][rabitq_qhat_stride(D)] i8: qhat as bytes, zero padded to a multiple of 64
+ *            (the operand of the matrix-core variant of the scan)
+ *   q_stage  [nq][D] fp32: q' in the order the refinement reads it (within each long-code
+ *            word, dimension b*(8/F)+s of the word sits at position 4*s+b; identity if B == 1) */
+typedef struct {
+  uint32_t* planes;
+  float* delta;
+  int32_t* sum_qhat;
+  float* sum_q;
+  float* sq_norm;
+  int8_t* qhat8;
+  float* q_stage;
+} rabitq_query_repr;
+int32_t rabitq_qhat_stride(int32_t dim); /* = dim rounded up to a multiple of 64 */
+int rabitq_query_prep(rabitq_index_t index, const float* q_rot, int64_t nq, const rabitq_query_repr* out,
+                      void* stream);
 
 /* Section 3.3.2: coarse scores by one GEMM (s_q 1^T + 1 s_c^T - 2 Q'C^T for L2, -Q'C^T
  * for IP) and the nprobe best clusters per query, best first, ties to the lower id.
@@ -194,13 +213,12 @@ int rabitq_build_probe_lists(rabitq_index_t index, const int32_t* probe_ids, int
  * least k vectors, the k smallest 1-bit estimates (ties: lower position) are refined and
  * tau is the largest refined estimate (B == 1: the k-th smallest 1-bit estimate);
  * FLT_MAX when no probed cluster has k vectors. */
-int rabitq_seed_threshold(rabitq_index_t index, const float* q_rot, const uint32_t* planes, const float* delta,
-                          const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids,
+int rabitq_seed_threshold(rabitq_index_t index, const rabitq_query_repr* repr, const int32_t* probe_ids,
                           const float* probe_G, const float* probe_E, int64_t nq, int32_t k, int32_t nprobe,
                           float* tau, void* stream);
 
 /* Sections 3.3.4, 3.4.1(2), 3.4.2: the fused cluster-local search over all pairs.
- * For every pair: 1-bit estimate of every vector of the cluster by AND+popcount, filter
+ * For every pair: 1-bit estimate of every vector of the cluster (see option "scan_impl"), filter
  * (B > 1: lb1 <= tau, B == 1: est1 <= tau), refinement of survivors, cluster-local top-k.
  *   tau        [nq] fp32 (pass FLT_MAX everywhere to disable the filter)
  *   cand_keys  [nq*nprobe*cap] u64, cap = rabitq_cand_capacity(k): (order-preserving bits of
@@ -212,8 +230,7 @@ int rabitq_seed_threshold(rabitq_index_t index, const float* q_rot, const uint32
  *              raw integer <x_b, qhat> of every slot; dbg_off [nq*nprobe+1] i64 gives each
  *              pair's first entry (indexed by position in pair_ids).  For small inputs. */
 int32_t rabitq_cand_capacity(int32_t k); /* = smallest power of two >= k + 64; negative status if k is out of range */
-int rabitq_scan(rabitq_index_t index, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+int rabitq_scan(rabitq_index_t index, const rabitq_query_repr* repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int32_t k,
                 int32_t nprobe, uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off,
                 void* stream);

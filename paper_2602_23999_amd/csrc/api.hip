@@ -45,8 +45,8 @@ static void dev_free(T*& p) {
 }
 
 static void free_workspace(Workspace& w) {
-  dev_free(w.q_rot); dev_free(w.planes); dev_free(w.delta); dev_free(w.sum_qhat); dev_free(w.sum_q);
-  dev_free(w.sq_norm); dev_free(w.tau); dev_free(w.scores); dev_free(w.probe_ids); dev_free(w.probe_G);
+  dev_free(w.q_rot); dev_free(w.repr.planes); dev_free(w.repr.delta); dev_free(w.repr.sum_qhat);
+  dev_free(w.repr.sum_q); dev_free(w.repr.sq_norm); dev_free(w.repr.qhat8); dev_free(w.repr.q_stage); dev_free(w.tau); dev_free(w.scores); dev_free(w.probe_ids); dev_free(w.probe_G);
   dev_free(w.probe_E); dev_free(w.pair_off); dev_free(w.pair_ids); dev_free(w.list_scratch);
   dev_free(w.cand_keys); dev_free(w.cand_cnt);
   w.cap_nq = w.cap_pairs = w.cap_cand = w.cap_scratch = 0;
@@ -82,11 +82,13 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   int rc;
 #define RQ_A(ptr, cnt) if ((rc = dev_alloc(&(ptr), (cnt))) != RABITQ_OK) { free_workspace(w); return rc; }
   RQ_A(w.q_rot, c_nq * ix->dim);
-  RQ_A(w.planes, c_nq * 4 * ix->W);
-  RQ_A(w.delta, c_nq);
-  RQ_A(w.sum_qhat, c_nq);
-  RQ_A(w.sum_q, c_nq);
-  RQ_A(w.sq_norm, c_nq);
+  RQ_A(w.repr.planes, c_nq * 4 * ix->W);
+  RQ_A(w.repr.delta, c_nq);
+  RQ_A(w.repr.sum_qhat, c_nq);
+  RQ_A(w.repr.sum_q, c_nq);
+  RQ_A(w.repr.sq_norm, c_nq);
+  RQ_A(w.repr.qhat8, c_nq * qhat_stride(ix->dim));
+  RQ_A(w.repr.q_stage, c_nq * ix->dim);
   RQ_A(w.tau, c_nq);
   RQ_A(w.scores, c_nq * ix->nlist);
   RQ_A(w.probe_ids, c_pairs);
@@ -254,6 +256,7 @@ int rabitq_index_free(rabitq_index_t ix) {
 int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "scan_impl") && (value == 0 || value == 1)) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile") && value >= 0 && value <= 4096) {
     const size_t have = ix->prof_sets.size();
     if ((size_t)value > have) {
@@ -326,13 +329,18 @@ int rabitq_rotate(rabitq_index_t ix, const float* queries, int64_t nq, float* q_
   return launch_gemm(queries, ix->rotation, q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, (hipStream_t)stream);
 }
 
-int rabitq_query_prep(rabitq_index_t ix, const float* q_rot, int64_t nq, uint32_t* planes, float* delta,
-                      int32_t* sum_qhat, float* sum_q, float* sq_norm, void* stream) {
+static bool repr_ok(const rabitq_query_repr* r) {
+  return r && r->planes && r->delta && r->sum_qhat && r->sum_q && r->sq_norm && r->qhat8 && r->q_stage;
+}
+
+int32_t rabitq_qhat_stride(int32_t dim) { return dim < 1 ? RABITQ_EINVAL : qhat_stride(dim); }
+
+int rabitq_query_prep(rabitq_index_t ix, const float* q_rot, int64_t nq, const rabitq_query_repr* out, void* stream) {
   int rc = check_common(ix, nq, "query_prep");
   if (rc) return rc;
   if (nq == 0) return RABITQ_OK;
-  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !sq_norm) { set_error("query_prep: null pointer"); return RABITQ_EINVAL; }
-  return launch_query_prep(q_rot, nq, ix->dim, planes, delta, sum_qhat, sum_q, sq_norm, (hipStream_t)stream);
+  if (!q_rot || !repr_ok(out)) { set_error("query_prep: null pointer"); return RABITQ_EINVAL; }
+  return launch_query_prep(q_rot, nq, ix->dim, ix->F, *out, (hipStream_t)stream);
 }
 
 int rabitq_coarse_probe(rabitq_index_t ix, const float* q_rot, const float* sq_norm, int64_t nq, int32_t nprobe,
@@ -373,23 +381,18 @@ int rabitq_build_probe_lists(rabitq_index_t ix, const int32_t* probe_ids, int64_
   return launch_build_lists(probe_ids, nq, nprobe, ix->nlist, pair_off, pair_ids, scratch, (hipStream_t)stream);
 }
 
-int rabitq_seed_threshold(rabitq_index_t ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                          const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids,
+int rabitq_seed_threshold(rabitq_index_t ix, const rabitq_query_repr* repr, const int32_t* probe_ids,
                           const float* probe_G, const float* probe_E, int64_t nq, int32_t k, int32_t nprobe,
                           float* tau, void* stream) {
   int rc = check_common(ix, nq, "seed_threshold");
   if (rc) return rc;
   if ((rc = check_k_nprobe(ix, k, nprobe, "seed_threshold"))) return rc;
   if (nq == 0) return RABITQ_OK;
-  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !probe_ids || !probe_G || !probe_E || !tau) {
-    set_error("seed_threshold: null pointer"); return RABITQ_EINVAL;
-  }
-  return launch_seed(ix, q_rot, planes, delta, sum_qhat, sum_q, probe_ids, probe_G, probe_E, nq, k, nprobe, tau,
-                     (hipStream_t)stream);
+  if (!repr_ok(repr) || !probe_ids || !probe_G || !probe_E || !tau) { set_error("seed_threshold: null pointer"); return RABITQ_EINVAL; }
+  return launch_seed(ix, *repr, probe_ids, probe_G, probe_E, nq, k, nprobe, tau, (hipStream_t)stream);
 }
 
-int rabitq_scan(rabitq_index_t ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+int rabitq_scan(rabitq_index_t ix, const rabitq_query_repr* repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int32_t k,
                 int32_t nprobe, uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off,
                 void* stream) {
@@ -397,13 +400,13 @@ int rabitq_scan(rabitq_index_t ix, const float* q_rot, const uint32_t* planes, c
   if (rc) return rc;
   if ((rc = check_k_nprobe(ix, k, nprobe, "scan"))) return rc;
   if (nq == 0) return RABITQ_OK;
-  if (!q_rot || !planes || !delta || !sum_qhat || !sum_q || !probe_G || !probe_E || !pair_off || !pair_ids || !tau ||
-      !cand_keys || !cand_cnt || (dbg_ip && !dbg_off)) {
+  if (!repr_ok(repr) || !probe_G || !probe_E || !pair_off || !pair_ids || !tau || !cand_keys || !cand_cnt ||
+      (dbg_ip && !dbg_off)) {
     set_error("scan: null pointer"); return RABITQ_EINVAL;
   }
   if (nq * nprobe > 0x7fffffff) { set_error("scan: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
-  return launch_scan(ix, q_rot, planes, delta, sum_qhat, sum_q, probe_G, probe_E, pair_off, pair_ids, tau, nq, k,
-                     nprobe, cand_keys, cand_cnt, dbg_ip, dbg_off, (hipStream_t)stream);
+  return launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
+                     dbg_off, (hipStream_t)stream);
 }
 
 int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int32_t k,
@@ -435,24 +438,23 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   RQ_MARK();
   RQ_RUN(launch_gemm(queries, ix->rotation, w.q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, st));
   RQ_MARK();
-  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, w.planes, w.delta, w.sum_qhat, w.sum_q, w.sq_norm, st));
+  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, ix->F, w.repr, st));
   RQ_MARK();
   RQ_RUN(launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
-                     w.sq_norm, ix->centroid_sq, st));
+                     w.repr.sq_norm, ix->centroid_sq, st));
   RQ_MARK();
-  RQ_RUN(launch_select_probes(w.scores, w.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, w.probe_ids,
+  RQ_RUN(launch_select_probes(w.scores, w.repr.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, w.probe_ids,
                               w.probe_G, w.probe_E, st));
   RQ_MARK();
   RQ_RUN(launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, st));
   RQ_MARK();
   if (ix->prune) {
-    RQ_RUN(launch_seed(ix, w.q_rot, w.planes, w.delta, w.sum_qhat, w.sum_q, w.probe_ids, w.probe_G, w.probe_E, nq, k,
-                       nprobe, w.tau, st));
+    RQ_RUN(launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
   } else {
     RQ_RUN(launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));
   }
   RQ_MARK();
-  RQ_RUN(launch_scan(ix, w.q_rot, w.planes, w.delta, w.sum_qhat, w.sum_q, w.probe_G, w.probe_E, w.pair_off, w.pair_ids,
+  RQ_RUN(launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids,
                      w.tau, nq, k, nprobe, w.cand_keys, w.cand_cnt, nullptr, nullptr, st, ev ? ev[stage++] : nullptr));
   RQ_MARK();
   RQ_RUN(launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));

@@ -10,17 +10,14 @@
 namespace rq {
 
 constexpr int TILE = RABITQ_TILE;
-constexpr int QW = 4;        // queries handled by one scan wavefront
-constexpr int POOL = 256;    // per-(wave, query) candidate pool entries in LDS
+constexpr int QW = 4;        // queries handled by one wavefront of the popcount scan
+constexpr int QM = 16;       // queries handled by one wavefront of the matrix-core scan
+inline int qhat_stride(int D) { return (D + 63) / 64 * 64; }
 
 struct Workspace {
   // per query
   float* q_rot = nullptr;
-  uint32_t* planes = nullptr;
-  float* delta = nullptr;
-  int32_t* sum_qhat = nullptr;
-  float* sum_q = nullptr;
-  float* sq_norm = nullptr;
+  rabitq_query_repr repr = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   float* tau = nullptr;
   // coarse
   float* scores = nullptr;
@@ -60,6 +57,7 @@ struct rabitq_index {
   int32_t* ids = nullptr;
   // options
   int prune = 1;
+  int scan_impl = 0;
   static constexpr int N_STAGES = 9;
   struct EventSet { hipEvent_t ev[N_STAGES + 1]; };
   std::vector<EventSet> prof_sets;  // one per recorded search
@@ -93,18 +91,15 @@ __host__ __device__ inline float ord2f(uint32_t o) {
 // C = rowv[m] + colv[n] - 2*acc.  mode 2 (IP coarse): C = -acc.  mode 3 (assignment): C = colv[n] - 2*acc.
 int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,
                 const float* colv, hipStream_t st);
-int launch_query_prep(const float* q_rot, int64_t nq, int D, uint32_t* planes, float* delta, int32_t* sum_qhat,
-                      float* sum_q, float* sq_norm, hipStream_t st);
+int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st);
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st);
 int64_t probe_list_scratch_words(int32_t nlist, int64_t nq);
 int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,
                        int32_t* pair_ids, uint32_t* scratch, hipStream_t st);
-int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids, const float* probe_G,
+int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st);
-int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
                 uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
                 hipEvent_t after_setup = nullptr);

@@ -17,7 +17,9 @@ struct ScanArgs {
   int D, B, LW, nlist;
   float cB;  // (2^B - 1) / 2
   // per query
-  const float* q_rot;
+  const float* q_stage;   // [nq][D] rotated query in refinement order
+  const int8_t* qhat8;    // [nq][Dp] 4-bit query as bytes (matrix-core scan)
+  int Dp;
   const uint32_t* planes;
   const float* delta;
   const int32_t* sum_qhat;
@@ -30,7 +32,7 @@ struct ScanArgs {
   const int32_t* pair_off;
   const int32_t* pair_ids;
   const int32_t* item_off;
-  int nprobe, k, pool;
+  int nprobe, k, pool, cand_stride;
   // outputs
   uint64_t* cand_keys;
   int32_t* cand_cnt;
@@ -42,8 +44,9 @@ struct ScanArgs {
 bool seed_part0(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
 bool seed_part1(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
 bool seed_part2(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
-bool scan_part0(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
-bool scan_part1(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
-bool scan_part2(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st);
+// impl 0: popcount kernel (QW pairs per wavefront); impl 1: matrix-core kernel (QM pairs)
+bool scan_part0(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);
+bool scan_part1(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);
+bool scan_part2(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);
 
 }  // namespace rq

@@ -14,10 +14,9 @@ __device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float
   return G + fa + fr * (hd * (float)(2 * I - S));
 }
 
-// copy one rotated query into LDS in the order refine_lane reads it
-template <int F>
+// copy one rotated query (already in refinement order) into LDS
 __device__ inline void stage_query(float* dst, const float* __restrict__ src, int D, int tid, int nt) {
-  for (int i = tid; i < D; i += nt) dst[stage_index<(F > 0 ? F : 8)>(i)] = src[i];
+  for (int i = tid; i < D; i += nt) dst[i] = src[i];
 }
 
 // ---------------------------------------------------------------------------------
@@ -50,7 +49,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     s_max = 0u;
   }
   for (int i = tid; i < kpad; i += 256) best[i] = KEY_NONE;
-  if (F > 0) stage_query<F>(qf, a.q_rot + q * a.D, a.D, tid, 256);
+  if (F > 0) stage_query(qf, a.q_stage + q * a.D, a.D, tid, 256);
   __syncthreads();
   const int rank = s_rank;
   if (rank < 0) {
@@ -188,7 +187,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       qs[2 * j] = Gj[j];
       qs[2 * j + 1] = a.cB * a.sum_q[q];
     }
-    if (F > 0) stage_query<F>(qf + j * a.D, a.q_rot + q * a.D, a.D, lane, 64);
+    if (F > 0) stage_query(qf + j * a.D, a.q_stage + q * a.D, a.D, lane, 64);
   }
   __syncthreads();
 
@@ -291,7 +290,224 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     const uint64_t* pool = pools + (size_t)j * a.pool;
     __syncthreads();
     if (lane == 0) a.cand_cnt[pj[j]] = cnt[j];
-    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.pool + e] = pool[e];
+    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.cand_stride + e] = pool[e];
+  }
+}
+
+// ---------------------------------------------------------------------------------
+// Matrix-core variant of the fused cluster-local search.  The integer inner product
+// <x_b, qhat> of Section 3.4.1(2) is a dense contraction once the batch is grouped by
+// cluster: (queries probing the cluster) x (vectors of the cluster) over D.  One wavefront
+// takes QM = 16 pairs of one cluster; per 64-vector tile it expands the sign bits to int8
+// once (nibble * 0x204081 & 0x01010101 spreads 4 bits over 4 bytes) and issues
+// v_mfma_i32_16x16x64_i8 with the 16 queries' qhat bytes held in registers.  Accumulator
+// r of lane l is query 4*(l/16)+r, vector 16*cb + l%16 of the tile, so a lane keeps the
+// factors of its four vectors and the scalars of its four queries.  Everything after the
+// inner product (filter, survivor list, refinement, pools, output) is shared in form with
+// the popcount kernel; integer results are identical.
+// ---------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+constexpr int MWAVES = 4;                          // wavefronts per work item (they split its tiles)
+constexpr int MLIST_CAP = 512 + MWAVES * QM * TILE;  // a round of tiles adds at most MWAVES*1024 survivors
+
+__device__ inline v4i expand16(uint32_t bits16) {  // 16 sign bits -> 16 bytes of 0/1
+  v4i v;
+  v.x = (int)(__umul24(bits16 & 15u, 0x204081u) & 0x01010101u);
+  v.y = (int)(__umul24((bits16 >> 4) & 15u, 0x204081u) & 0x01010101u);
+  v.z = (int)(__umul24((bits16 >> 8) & 15u, 0x204081u) & 0x01010101u);
+  v.w = (int)(__umul24((bits16 >> 12) & 15u, 0x204081u) & 0x01010101u);
+  return v;
+}
+
+__device__ inline int block_pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
+  __syncthreads();
+  for (int i = cnt + (int)threadIdx.x; i < pool_n; i += (int)blockDim.x) pool[i] = KEY_NONE;
+  block_bitonic_sort(pool, pool_n);
+  return min(cnt, k);
+}
+
+template <int W, int F, bool DBG>
+__global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
+  constexpr int FF = (F > 0 ? F : 8), LW = W * FF, KC = (W + 1) / 2;
+  constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
+  extern __shared__ unsigned char smem_raw[];
+  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);          // [QM][pool]
+  uint64_t* pool_kth = pools + (size_t)QM * a.pool;                 // [QM]
+  float* qs = reinterpret_cast<float*>(pool_kth + QM);              // [QM][2]: G, cB*sum(q')
+  int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QM);              // [QM]
+  int* qidx = pool_cnt + QM;                                        // [QM] query of each pair
+  int* s_list_cnt = qidx + QM;                                      // [4]
+  uint32_t* list = reinterpret_cast<uint32_t*>(s_list_cnt + 4);     // [MLIST_CAP] (F > 0)
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lj = lane & 15, g = lane >> 4;
+
+  const int nb = gridDim.x;
+  const int per = (nb + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if (item >= a.item_off[a.nlist]) return;
+  int lo = 0, hi = a.nlist;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (a.item_off[mid] <= item) lo = mid; else hi = mid;
+  }
+  const int c = lo;
+  const int pbeg = a.pair_off[c] + (item - a.item_off[c]) * QM;
+  const int np = min(QM, a.pair_off[c + 1] - pbeg);
+
+  // query operand: lane (row lj, k-group g) holds qhat[16g .. 16g+15] of every 64-dim chunk
+  v4i qa[KC];
+  {
+    const int pp = a.pair_ids[pbeg + min(lj, np - 1)];
+    const int64_t q = pp / a.nprobe;
+    const int8_t* src = a.qhat8 + q * a.Dp + 16 * g;
+#pragma unroll
+    for (int kc = 0; kc < KC; ++kc) {
+      qa[kc] = *reinterpret_cast<const v4i*>(src + 64 * kc);
+      if (lj >= np) qa[kc] = v4i{0, 0, 0, 0};
+    }
+    if (tid < QM) {  // one thread per pair fills the shared per-pair state
+      qidx[lj] = (int)q;
+      qs[2 * lj] = a.probe_G[pp];
+      qs[2 * lj + 1] = a.cB * a.sum_q[q];
+      pool_kth[lj] = KEY_NONE;
+      pool_cnt[lj] = 0;
+    }
+    if (tid == 0) s_list_cnt[0] = 0;
+  }
+  // scalars of this lane's four queries (rows 4g .. 4g+3)
+  float al[4], be[4], Gr[4], Er[4], tr[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int qi = 4 * g + r;
+    const int pp = a.pair_ids[pbeg + min(qi, np - 1)];
+    const int64_t q = pp / a.nprobe;
+    const float dl = a.delta[q];
+    al[r] = dl;
+    be[r] = 0.5f * dl * (float)a.sum_qhat[q];
+    Gr[r] = a.probe_G[pp];
+    Er[r] = a.probe_E[pp];
+    tr[r] = (qi < np) ? a.tau[q] : -3.402823466e+38f;
+  }
+  __syncthreads();
+
+  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+
+  auto compact_if_full = [&](int room) {  // afterwards every pool has `room` free slots
+#pragma unroll 1
+    for (int jj = 0; jj < QM; ++jj) {
+      const int cj = pool_cnt[jj];
+      if (cj + room > a.pool) {  // workgroup-uniform: pool_cnt is read after a barrier
+        uint64_t* pool = pools + (size_t)jj * a.pool;
+        const int nc = block_pool_compact(pool, a.pool, cj, a.k);
+        if (tid == 0) {
+          pool_cnt[jj] = nc;
+          if (nc >= a.k) pool_kth[jj] = pool[a.k - 1];
+        }
+        __syncthreads();
+      }
+    }
+  };
+
+  auto flush = [&]() {  // refine everything in the survivor list (F > 0); each wavefront takes NS entries per round
+    __syncthreads();
+    const int list_cnt = s_list_cnt[0];
+    for (int base = 0; base < list_cnt; base += MWAVES * NS) {
+      const int idx = base + wave * NS + lane / G, t = lane % G;
+      const bool valid = idx < list_cnt;
+      const uint32_t e = valid ? list[idx] : 0u;
+      const int j = (int)(e >> 28);
+      const int64_t slot = (int64_t)t0 * TILE + (e & 0x0fffffffu);
+      float part = 0.f;
+      if (valid) part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + (int64_t)qidx[j] * a.D, t);
+      const float ip = group_sum<G>(part);
+      if (valid && t == 0) {
+        const float eB = qs[2 * j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - qs[2 * j + 1]);
+        const uint64_t key = make_key(eB, (uint32_t)a.ids[slot]);
+        if (key <= pool_kth[j]) {
+          const int pos = atomicAdd(&pool_cnt[j], 1);
+          pools[(size_t)j * a.pool + pos] = key;
+        }
+      }
+      __syncthreads();
+      compact_if_full(MWAVES * NS);
+    }
+    __syncthreads();
+    if (tid == 0) s_list_cnt[0] = 0;
+    __syncthreads();
+  };
+
+  for (int tb = t0; tb < t1; tb += MWAVES) {
+    if (F > 0) {
+      if (s_list_cnt[0] > 512) flush();
+    } else {
+      compact_if_full(MWAVES * TILE);
+    }
+    const int tile = tb + wave;
+    if (tile < t1) {
+      // inner products: 4 column blocks of 16 vectors x 16 queries
+      v4i acc[4];
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        acc[cb] = v4i{0, 0, 0, 0};
+#pragma unroll
+        for (int kc = 0; kc < KC; ++kc) {
+          const int w = 2 * kc + (g >> 1);
+          uint32_t word = 0u;
+          if (w < W) word = a.short_codes[((int64_t)tile * W + w) * TILE + 16 * cb + lj];
+          const v4i xb = expand16((word >> (16 * (g & 1))) & 0xffffu);
+          acc[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa[kc], xb, acc[cb], 0, 0, 0);
+        }
+      }
+      uint32_t my[4] = {0u, 0u, 0u, 0u};  // survivor bits per column block (bit r = query 4g+r)
+      int n_mine = 0;
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const int v = 16 * cb + lj;
+        const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + v];
+        const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + v];
+        const float fe = a.short_factors[((int64_t)tile * 3 + 2) * TILE + v];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int I = acc[cb][r];
+          if (DBG) {
+            if (4 * g + r < np) a.dbg_ip[a.dbg_off[pbeg + 4 * g + r] + (int64_t)(tile - t0) * TILE + v] = I;
+          }
+          const float x = fmaf(al[r], (float)I, -be[r]);  // delta * (I - S/2)
+          const float e1 = fmaf(fr, x, fa + Gr[r]);
+          const float filt = (F > 0) ? fmaf(-fe, Er[r], e1) : e1;
+          if (filt <= tr[r]) {
+            if (F == 0) {  // B == 1: the 1-bit estimate is the final key
+              const int j = 4 * g + r;
+              const uint64_t key = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + v]);
+              if (key <= pool_kth[j]) pools[(size_t)j * a.pool + atomicAdd(&pool_cnt[j], 1)] = key;
+            } else {
+              my[cb] |= 1u << r;
+              ++n_mine;
+            }
+          }
+        }
+      }
+      if (F > 0 && n_mine > 0) {
+        int pos = atomicAdd(&s_list_cnt[0], n_mine);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (my[cb] & (1u << r))
+              list[pos++] = ((uint32_t)(4 * g + r) << 28) | (uint32_t)((tile - t0) * TILE + 16 * cb + lj);
+      }
+    }
+    __syncthreads();
+  }
+  if (F > 0) flush();
+  __syncthreads();
+  compact_if_full(a.pool - a.cand_stride);  // a pool larger than the output region is cut to its k best
+#pragma unroll 1
+  for (int j = 0; j < np; ++j) {
+    const uint64_t* pool = pools + (size_t)j * a.pool;
+    const int cj = pool_cnt[j];
+    const int pp = a.pair_ids[pbeg + j];
+    if (tid == 0) a.cand_cnt[pp] = cj;
+    for (int e = tid; e < cj; e += 64 * MWAVES) a.cand_keys[(int64_t)pp * a.cand_stride + e] = pool[e];
   }
 }
 
@@ -321,6 +537,17 @@ static void launch_seed_wf(const ScanArgs& a, int64_t nq, hipStream_t st) {
 }
 
 template <int W, int F>
+static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
+  const size_t smem = (size_t)QM * a.pool * sizeof(uint64_t) +
+                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + 4 * sizeof(int) +
+                      (F > 0 ? MLIST_CAP * sizeof(uint32_t) : 0);
+  if (dbg)
+    hipLaunchKernelGGL((scan_mfma_kernel<W, F, true>), dim3(grid), dim3(64 * MWAVES), smem, st, a);
+  else
+    hipLaunchKernelGGL((scan_mfma_kernel<W, F, false>), dim3(grid), dim3(64 * MWAVES), smem, st, a);
+}
+
+template <int W, int F>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
                       (F > 0 ? LIST_CAP * sizeof(uint32_t) + (size_t)QW * a.D * sizeof(float) : 0);
@@ -341,7 +568,16 @@ static void seed_by_f(const ScanArgs& a, int F, int64_t nq, hipStream_t st) {
 }
 
 template <int W>
-static void scan_by_f(const ScanArgs& a, int F, unsigned grid, bool dbg, hipStream_t st) {
+static void scan_by_f(const ScanArgs& a, int F, int impl, unsigned grid, bool dbg, hipStream_t st) {
+  if (impl == 1) {
+    switch (F) {
+      case 0: launch_scan_mfma_wf<W, 0>(a, grid, dbg, st); break;
+      case 2: launch_scan_mfma_wf<W, 2>(a, grid, dbg, st); break;
+      case 4: launch_scan_mfma_wf<W, 4>(a, grid, dbg, st); break;
+      default: launch_scan_mfma_wf<W, 8>(a, grid, dbg, st); break;
+    }
+    return;
+  }
   switch (F) {
     case 0: launch_scan_wf<W, 0>(a, grid, dbg, st); break;
     case 2: launch_scan_wf<W, 2>(a, grid, dbg, st); break;
@@ -360,9 +596,9 @@ bool RQ_PART_NAME(seed)(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t
   }
 }
 
-bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, unsigned grid, bool dbg, hipStream_t st) {
+bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st) {
   switch (W) {
-#define RQ_X(W_) case W_: scan_by_f<W_>(a, F, grid, dbg, st); return true;
+#define RQ_X(W_) case W_: scan_by_f<W_>(a, F, impl, grid, dbg, st); return true;
     RQ_W_LIST(RQ_X)
 #undef RQ_X
     default: return false;

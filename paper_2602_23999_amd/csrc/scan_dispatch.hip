@@ -6,17 +6,17 @@
 namespace rq {
 
 // ---------------------------------------------------------------------------------
-// item_off[c] = first work item of cluster c; a work item is QW consecutive pairs of
+// item_off[c] = first work item of cluster c; a work item is qw consecutive pairs of
 // one cluster.  (One workgroup.)
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off, int n,
+__global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off, int n, int qw,
                                                           int32_t* __restrict__ item_off) {
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;
   const int per = (n + 255) / 256;
   const int s = tid * per, e = min(n, s + per);
   uint32_t sum = 0;
-  for (int i = s; i < e; ++i) sum += (uint32_t)(pair_off[i + 1] - pair_off[i] + QW - 1) / QW;
+  for (int i = s; i < e; ++i) sum += (uint32_t)(pair_off[i + 1] - pair_off[i] + qw - 1) / qw;
   part[tid] = sum;
   __syncthreads();
   for (int d = 1; d < 256; d <<= 1) {
@@ -28,7 +28,7 @@ __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __rest
   uint32_t run = part[tid] - sum;
   for (int i = s; i < e; ++i) {
     item_off[i] = (int32_t)run;
-    run += (uint32_t)(pair_off[i + 1] - pair_off[i] + QW - 1) / QW;
+    run += (uint32_t)(pair_off[i + 1] - pair_off[i] + qw - 1) / qw;
   }
   if (tid == 255) item_off[n] = (int32_t)part[255];
 }
@@ -69,12 +69,16 @@ static int bad_width() {
   return RABITQ_EINVAL;
 }
 
-int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const int32_t* probe_ids, const float* probe_G,
+static void set_repr(ScanArgs& a, const rabitq_index* ix, const rabitq_query_repr& r) {
+  a.q_stage = r.q_stage; a.qhat8 = r.qhat8; a.Dp = qhat_stride(ix->dim);
+  a.planes = r.planes; a.delta = r.delta; a.sum_qhat = r.sum_qhat; a.sum_q = r.sum_q;
+}
+
+int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   ScanArgs a = base_args(ix);
-  a.q_rot = q_rot; a.planes = planes; a.delta = delta; a.sum_qhat = sum_qhat; a.sum_q = sum_q;
+  set_repr(a, ix, repr);
   a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
   a.nprobe = nprobe; a.k = k; a.tau_out = tau;
   const int W = ix->W, F = field_bits(ix->total_bits);
@@ -83,25 +87,32 @@ int launch_seed(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
   return RABITQ_OK;
 }
 
-int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* planes, const float* delta,
-                const int32_t* sum_qhat, const float* sum_q, const float* probe_G, const float* probe_E,
+int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
                 uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
                 hipEvent_t after_setup) {
   if (nq <= 0) return RABITQ_OK;
   ScanArgs a = base_args(ix);
-  a.q_rot = q_rot; a.planes = planes; a.delta = delta; a.sum_qhat = sum_qhat; a.sum_q = sum_q;
+  set_repr(a, ix, repr);
+  const int impl = ix->scan_impl;
+  const int qw = impl == 1 ? QM : QW;
   a.probe_G = probe_G; a.probe_E = probe_E; a.pair_off = pair_off; a.pair_ids = pair_ids; a.tau = tau;
-  a.nprobe = nprobe; a.k = k; a.pool = next_pow2_host(k + TILE);
+  a.nprobe = nprobe; a.k = k;
+  a.cand_stride = next_pow2_host(k + TILE);
+  // LDS pool entries per pair: the popcount kernel may append a whole tile at once
+  // (the matrix-core kernel's four wavefronts may together append 4 x 16 refined keys per round, or four whole
+  // tiles when there is no long code)
+  a.pool = next_pow2_host(k + TILE);
+  if (impl == 1 && ix->total_bits == 1) a.pool = next_pow2_host(k + 4 * TILE);
   a.cand_keys = cand_keys; a.cand_cnt = cand_cnt; a.dbg_ip = dbg_ip; a.dbg_off = dbg_off;
   // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
   a.item_off = item_off;
-  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->nlist, item_off);
+  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->nlist, qw, item_off);
   if (after_setup) RQ_HIP(hipEventRecord(after_setup, st));
-  // at most ceil(pairs/QW) + nlist work items; the kernel drops the excess
+  // at most ceil(pairs/qw) + nlist work items; the kernel drops the excess
   const int64_t npairs = nq * nprobe;
-  int64_t max_items = (npairs + QW - 1) / QW + ix->nlist;
+  int64_t max_items = (npairs + qw - 1) / qw + ix->nlist;
   max_items = ((max_items + 7) / 8) * 8;
   if (max_items > 0x7fffffff) {
     set_error("scan: too many work items");
@@ -110,7 +121,8 @@ int launch_scan(const rabitq_index* ix, const float* q_rot, const uint32_t* plan
   const unsigned grid = (unsigned)max_items;
   const bool dbg = dbg_ip != nullptr;
   const int W = ix->W, F = field_bits(ix->total_bits);
-  if (!(scan_part0(a, W, F, grid, dbg, st) || scan_part1(a, W, F, grid, dbg, st) || scan_part2(a, W, F, grid, dbg, st)))
+  if (!(scan_part0(a, W, F, impl, grid, dbg, st) || scan_part1(a, W, F, impl, grid, dbg, st) ||
+        scan_part2(a, W, F, impl, grid, dbg, st)))
     return bad_width();
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;

@@ -9,21 +9,22 @@ namespace rq {
 // per query.  One wavefront per query.  delta = max|q'|/7 and q'/delta use IEEE fp32
 // division and round-half-even, because they decide integers.
 // ---------------------------------------------------------------------------------
+template <int F>
 __global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict__ q_rot, int64_t nq, int D,
-                                                        uint32_t* __restrict__ planes, float* __restrict__ delta,
-                                                        int32_t* __restrict__ sum_qhat, float* __restrict__ sum_q,
-                                                        float* __restrict__ sq_norm) {
+                                                        rabitq_query_repr o) {
   const int lane = threadIdx.x & 63;
   const int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (q >= nq) return;
   const float* x = q_rot + q * D;
   const int W = D >> 5;
+  const int Dp = (D + 63) / 64 * 64;
   float amax = 0.f, s1 = 0.f, s2 = 0.f;
   for (int i = lane; i < D; i += 64) {
     const float v = x[i];
     amax = fmaxf(amax, fabsf(v));
     s1 += v;
     s2 += v * v;
+    o.q_stage[q * D + (F == 0 ? i : stage_index<(F == 0 ? 8 : F)>(i))] = v;
   }
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) {
@@ -33,8 +34,8 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict
   }
   const float dl = (amax == 0.f) ? 1.0f : __fdiv_rn(amax, 7.0f);
   int S = 0;
-  uint32_t* pl = planes + q * 4 * W;
-  for (int base = 0; base < D; base += 64) {
+  uint32_t* pl = o.planes + q * 4 * W;
+  for (int base = 0; base < Dp; base += 64) {
     const int i = base + lane;
     int qh = 0;
     if (i < D && amax != 0.f) {
@@ -42,31 +43,35 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict
       qh = (int)fminf(fmaxf(t, -7.f), 7.f);
     }
     S += qh;
+    o.qhat8[q * Dp + i] = (int8_t)qh;
     const uint32_t tc = (uint32_t)qh & 15u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const uint64_t m = __ballot((tc >> j) & 1u);
       const int w = base >> 5;
-      if (lane == 0) pl[j * W + w] = (uint32_t)m;
+      if (lane == 0 && w < W) pl[j * W + w] = (uint32_t)m;
       if (lane == 0 && w + 1 < W) pl[j * W + w + 1] = (uint32_t)(m >> 32);
     }
   }
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) S += __shfl_xor(S, d, 64);
   if (lane == 0) {
-    delta[q] = dl;
-    sum_qhat[q] = S;
-    sum_q[q] = s1;
-    sq_norm[q] = s2;
+    o.delta[q] = dl;
+    o.sum_qhat[q] = S;
+    o.sum_q[q] = s1;
+    o.sq_norm[q] = s2;
   }
 }
 
-int launch_query_prep(const float* q_rot, int64_t nq, int D, uint32_t* planes, float* delta, int32_t* sum_qhat,
-                      float* sum_q, float* sq_norm, hipStream_t st) {
+int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const unsigned grid = (unsigned)((nq + 3) / 4);
-  hipLaunchKernelGGL(query_prep_kernel, dim3(grid), dim3(256), 0, st, q_rot, nq, D, planes, delta, sum_qhat, sum_q,
-                     sq_norm);
+  switch (F) {
+    case 0: hipLaunchKernelGGL(query_prep_kernel<0>, dim3(grid), dim3(256), 0, st, q_rot, nq, D, out); break;
+    case 2: hipLaunchKernelGGL(query_prep_kernel<2>, dim3(grid), dim3(256), 0, st, q_rot, nq, D, out); break;
+    case 4: hipLaunchKernelGGL(query_prep_kernel<4>, dim3(grid), dim3(256), 0, st, q_rot, nq, D, out); break;
+    default: hipLaunchKernelGGL(query_prep_kernel<8>, dim3(grid), dim3(256), 0, st, q_rot, nq, D, out); break;
+  }
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }

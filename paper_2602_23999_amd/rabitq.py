@@ -23,7 +23,7 @@ TILE = 64
 
 EXPORTS = [
     "rabitq_index_upload", "rabitq_index_build", "rabitq_index_export", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
-    "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_coarse_probe",
+    "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_qhat_stride", "rabitq_coarse_probe",
     "rabitq_probe_list_scratch_words", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
 ]
@@ -38,6 +38,11 @@ class _Desc(C.Structure):
                 ("metric", C.c_int32), ("rotation", C.c_void_p), ("centroids", C.c_void_p),
                 ("offsets", C.c_void_p), ("short_codes", C.c_void_p), ("short_factors", C.c_void_p),
                 ("long_codes", C.c_void_p), ("long_factors", C.c_void_p), ("ids", C.c_void_p)]
+
+
+class _QueryRepr(C.Structure):
+    _fields_ = [("planes", C.c_void_p), ("delta", C.c_void_p), ("sum_qhat", C.c_void_p), ("sum_q", C.c_void_p),
+                ("sq_norm", C.c_void_p), ("qhat8", C.c_void_p), ("q_stage", C.c_void_p)]
 
 
 class _BuildParams(C.Structure):
@@ -71,19 +76,21 @@ def load_library() -> C.CDLL:
     lib.rabitq_index_info.restype = i64
     lib.rabitq_stage_ms.argtypes = [vp, C.POINTER(C.c_float), C.POINTER(C.c_int32)]
     lib.rabitq_rotate.argtypes = [vp, vp, i64, vp, vp]
-    lib.rabitq_query_prep.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
+    lib.rabitq_query_prep.argtypes = [vp, vp, i64, C.POINTER(_QueryRepr), vp]
+    lib.rabitq_qhat_stride.argtypes = [i32]
+    lib.rabitq_qhat_stride.restype = i32
     lib.rabitq_coarse_probe.argtypes = [vp, vp, vp, i64, i32, vp, vp, vp, vp, vp]
     lib.rabitq_probe_list_scratch_words.argtypes = [i32, i64]
     lib.rabitq_probe_list_scratch_words.restype = i64
     lib.rabitq_cand_capacity.argtypes = [i32]
     lib.rabitq_cand_capacity.restype = i32
     lib.rabitq_build_probe_lists.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
-    lib.rabitq_seed_threshold.argtypes = [vp] + [vp] * 8 + [i64, i32, i32, vp, vp]
-    lib.rabitq_scan.argtypes = [vp] + [vp] * 10 + [i64, i32, i32, vp, vp, vp, vp, vp]
+    lib.rabitq_seed_threshold.argtypes = [vp, C.POINTER(_QueryRepr), vp, vp, vp, i64, i32, i32, vp, vp]
+    lib.rabitq_scan.argtypes = [vp, C.POINTER(_QueryRepr), vp, vp, vp, vp, vp, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.rabitq_merge.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("rabitq_last_error", "rabitq_index_info", "rabitq_probe_list_scratch_words",
-                        "rabitq_cand_capacity"):
+                        "rabitq_cand_capacity", "rabitq_qhat_stride"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -231,17 +238,27 @@ class Index:
                                             _dev(out, torch.float32), _stream()))
         return out
 
+    @staticmethod
+    def _repr_struct(prep: dict) -> "_QueryRepr":
+        return _QueryRepr(_dev(prep["planes"], torch.int32), _dev(prep["delta"], torch.float32),
+                          _dev(prep["sum_qhat"], torch.int32), _dev(prep["sum_q"], torch.float32),
+                          _dev(prep["sq_norm"], torch.float32), _dev(prep["qhat8"], torch.int8),
+                          _dev(prep["q_stage"], torch.float32))
+
     def query_prep(self, q_rot):
+        """rabitq_query_prep: the per-query representation as a dict of device tensors."""
         nq, dev = q_rot.shape[0], q_rot.device
-        planes = torch.empty((nq, QUERY_BITS, self.W), dtype=torch.int32, device=dev)
-        delta = torch.empty(nq, dtype=torch.float32, device=dev)
-        sum_qhat = torch.empty(nq, dtype=torch.int32, device=dev)
-        sum_q = torch.empty(nq, dtype=torch.float32, device=dev)
-        sq_norm = torch.empty(nq, dtype=torch.float32, device=dev)
-        _check(load_library().rabitq_query_prep(self._h, _dev(q_rot, torch.float32), nq, planes.data_ptr(),
-                                                delta.data_ptr(), sum_qhat.data_ptr(), sum_q.data_ptr(),
-                                                sq_norm.data_ptr(), _stream()))
-        return dict(planes=planes, delta=delta, sum_qhat=sum_qhat, sum_q=sum_q, sq_norm=sq_norm)
+        stride = load_library().rabitq_qhat_stride(self.dim)
+        prep = dict(planes=torch.empty((nq, QUERY_BITS, self.W), dtype=torch.int32, device=dev),
+                    delta=torch.empty(nq, dtype=torch.float32, device=dev),
+                    sum_qhat=torch.empty(nq, dtype=torch.int32, device=dev),
+                    sum_q=torch.empty(nq, dtype=torch.float32, device=dev),
+                    sq_norm=torch.empty(nq, dtype=torch.float32, device=dev),
+                    qhat8=torch.empty((nq, stride), dtype=torch.int8, device=dev),
+                    q_stage=torch.empty((nq, self.dim), dtype=torch.float32, device=dev))
+        r = self._repr_struct(prep)
+        _check(load_library().rabitq_query_prep(self._h, _dev(q_rot, torch.float32), nq, C.byref(r), _stream()))
+        return prep
 
     def coarse_probe(self, q_rot, sq_norm, nprobe):
         nq, dev = q_rot.shape[0], q_rot.device
@@ -266,19 +283,18 @@ class Index:
                                                        _stream()))
         return pair_off, pair_ids
 
-    def seed_threshold(self, q_rot, prep, probes, k):
+    def seed_threshold(self, prep, probes, k):
         nq, nprobe = probes["probe_ids"].shape
-        tau = torch.empty(nq, dtype=torch.float32, device=q_rot.device)
+        tau = torch.empty(nq, dtype=torch.float32, device=probes["probe_ids"].device)
+        r = self._repr_struct(prep)
         _check(load_library().rabitq_seed_threshold(
-            self._h, _dev(q_rot, torch.float32), _dev(prep["planes"], torch.int32), _dev(prep["delta"], torch.float32),
-            _dev(prep["sum_qhat"], torch.int32), _dev(prep["sum_q"], torch.float32),
-            _dev(probes["probe_ids"], torch.int32), _dev(probes["probe_G"], torch.float32),
+            self._h, C.byref(r), _dev(probes["probe_ids"], torch.int32), _dev(probes["probe_G"], torch.float32),
             _dev(probes["probe_E"], torch.float32), nq, k, nprobe, tau.data_ptr(), _stream()))
         return tau
 
-    def scan(self, q_rot, prep, probes, pair_off, pair_ids, tau, k, dbg_off=None):
+    def scan(self, prep, probes, pair_off, pair_ids, tau, k, dbg_off=None):
         nq, nprobe = probes["probe_G"].shape
-        dev = q_rot.device
+        dev = tau.device
         cap = load_library().rabitq_cand_capacity(k)
         if cap < 0:
             _check(cap)
@@ -287,10 +303,9 @@ class Index:
         dbg_ip = None
         if dbg_off is not None:
             dbg_ip = torch.zeros(int(dbg_off[-1].item()), dtype=torch.int32, device=dev)
+        r = self._repr_struct(prep)
         _check(load_library().rabitq_scan(
-            self._h, _dev(q_rot, torch.float32), _dev(prep["planes"], torch.int32), _dev(prep["delta"], torch.float32),
-            _dev(prep["sum_qhat"], torch.int32), _dev(prep["sum_q"], torch.float32),
-            _dev(probes["probe_G"], torch.float32), _dev(probes["probe_E"], torch.float32),
+            self._h, C.byref(r), _dev(probes["probe_G"], torch.float32), _dev(probes["probe_E"], torch.float32),
             _dev(pair_off, torch.int32), _dev(pair_ids, torch.int32), _dev(tau, torch.float32), nq, k, nprobe,
             cand_keys.data_ptr(), cand_cnt.data_ptr(), None if dbg_ip is None else dbg_ip.data_ptr(),
             None if dbg_off is None else _dev(dbg_off, torch.int64), _stream()))

@@ -54,6 +54,8 @@ def test_query_prep_bit_exact(name):
     assert np.array_equal(out["planes"].cpu().numpy().view(np.uint32), st["planes"])
     assert np.array_equal(out["delta"].cpu().numpy(), st["delta"])
     assert np.array_equal(out["sum_qhat"].cpu().numpy(), st["S"])
+    assert np.array_equal(out["qhat8"].cpu().numpy(), st["qhat"])
+    assert np.array_equal(out["q_stage"].cpu().numpy(), st["q_stage"])
     assert np.allclose(out["sq_norm"].cpu().numpy(), st["sq_norm"], rtol=1e-5)
     scale = np.abs(st["Qr"]).sum(1)
     assert np.all(np.abs(out["sum_q"].cpu().numpy() - st["sum_q"]) <= 1e-6 * scale)
@@ -84,17 +86,20 @@ def test_probe_lists_bit_exact(name):
     assert np.array_equal(ids.cpu().numpy(), st["pair_ids"])
 
 
+@pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name", ALL)
-def test_scan_integer_inner_products_bit_exact(name):
+def test_scan_integer_inner_products_bit_exact(name, impl):
     c = case(name)
+    c["gi"].set_option("scan_impl", impl)
     st, d, ix, s = c["st"], c["dev"], c["ix"], c["s"]
     nprobe, k = c["nprobe"], c["k"]
     tiles = (np.diff(ix["offsets"]) + 63) // 64
     pair_cluster = st["probes"].reshape(-1)[st["pair_ids"]]
     dbg_off = np.zeros(len(pair_cluster) + 1, np.int64)
     dbg_off[1:] = np.cumsum(tiles[pair_cluster] * 64)
-    cand_keys, cand_cnt, dbg = c["gi"].scan(d["q_rot"], d["prep"], d["probes"], d["pair_off"], d["pair_ids"],
+    cand_keys, cand_cnt, dbg = c["gi"].scan(d["prep"], d["probes"], d["pair_off"], d["pair_ids"],
                                             d["tau"], k, dbg_off=torch.from_numpy(dbg_off).cuda())
+    c["gi"].set_option("scan_impl", 0)
     dbg = dbg.cpu().numpy()
     rng = np.random.default_rng(0)
     for pos in rng.choice(len(pair_cluster), size=min(300, len(pair_cluster)), replace=False):
@@ -109,7 +114,7 @@ def test_scan_integer_inner_products_bit_exact(name):
 def test_seed_threshold(name):
     c = case(name)
     st, d = c["st"], c["dev"]
-    tau = c["gi"].seed_threshold(d["q_rot"], d["prep"], d["probes"], c["k"]).cpu().numpy().astype(np.float64)
+    tau = c["gi"].seed_threshold(d["prep"], d["probes"], c["k"]).cpu().numpy().astype(np.float64)
     want = np.minimum(st["tau"], rabitq.FLT_MAX)
     scale = st["G"].max(axis=1) + 1e-6
     bad = np.abs(tau - want) > 1e-4 * (np.abs(want) + scale)
@@ -117,10 +122,12 @@ def test_seed_threshold(name):
     assert bad.mean() <= 0.02, (tau[bad], want[bad])
 
 
+@pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name", ALL)
 @pytest.mark.parametrize("prune", [True, False])
-def test_scan_and_merge_with_injected_threshold(name, prune):
+def test_scan_and_merge_with_injected_threshold(name, prune, impl):
     c = case(name)
+    c["gi"].set_option("scan_impl", impl)
     st, d, s = c["st"], c["dev"], c["s"]
     nq, k, nprobe = len(c["Q"]), c["k"], c["nprobe"]
     # The injected threshold is the oracle's, moved up by a hair (as an fp32 value that both
@@ -131,7 +138,8 @@ def test_scan_and_merge_with_injected_threshold(name, prune):
     if not prune:
         tau_np[:] = rabitq.FLT_MAX
     tau = torch.from_numpy(tau_np).cuda()
-    keys, cnt, _ = c["gi"].scan(d["q_rot"], d["prep"], d["probes"], d["pair_off"], d["pair_ids"], tau, k)
+    keys, cnt, _ = c["gi"].scan(d["prep"], d["probes"], d["pair_off"], d["pair_ids"], tau, k)
+    c["gi"].set_option("scan_impl", 0)
     ids, dist = c["gi"].merge(keys, cnt, nq, k, nprobe)
     o_ids, o_d, info = s.search(c["Q"], k, nprobe, prune=prune, Qr=st["Qr"], tau=tau_np.astype(np.float64))
     atol = 1e-4 * (st["G"].max(axis=1) + 1e-6)
@@ -140,11 +148,14 @@ def test_scan_and_merge_with_injected_threshold(name, prune):
     assert int(cnt.max()) <= keys.shape[1]
 
 
+@pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name", ALL)
-def test_search_end_to_end(name):
+def test_search_end_to_end(name, impl):
     c = case(name)
     s, k, nprobe = c["s"], c["k"], c["nprobe"]
+    c["gi"].set_option("scan_impl", impl)
     ids, dist = c["gi"].search(torch.from_numpy(c["Q"]).cuda(), k, nprobe)
+    c["gi"].set_option("scan_impl", 0)
     ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
     o_ids, o_d, info = s.search(c["Q"], k, nprobe)
     gt, _ = exact.exact_knn(c["X"], c["Q"], k, c["ix"]["metric"])
