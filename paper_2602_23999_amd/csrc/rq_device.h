@@ -210,6 +210,73 @@ __device__ inline void block_select_smallest(int n, int K, int Kpad, KeyFn key_a
   block_bitonic_sort(out, Kpad);
 }
 
+// ---------------------------------------------------------------------------------
+// Wavefront-wide selection with the keys in registers: every lane holds R keys (KEY_NONE =
+// absent).  Returns a bound such that exactly min(K, #present) present keys are <= bound.
+// MSB-first bisection: one bit per step, counting the keys of the current bucket whose
+// next bit is 0; the bits all keys share are skipped and the search stops as soon as the
+// bucket holding the K-th key is taken whole.  No LDS, no barriers.
+// ---------------------------------------------------------------------------------
+template <int R>
+__device__ inline uint64_t wave_kth_bound(const uint64_t (&key)[R], int K) {
+  uint64_t lo = KEY_NONE, hi = 0ull;
+  uint32_t nv = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    if (key[r] != KEY_NONE) {
+      lo = key[r] < lo ? key[r] : lo;
+      hi = key[r] > hi ? key[r] : hi;
+      ++nv;
+    }
+  }
+  lo = wave_reduce_u64(lo, [](uint64_t a, uint64_t b) { return a < b ? a : b; });
+  hi = wave_reduce_u64(hi, [](uint64_t a, uint64_t b) { return a > b ? a : b; });
+  nv = wave_reduce_u32(nv, [](uint32_t a, uint32_t b) { return a + b; });
+  if (nv <= (uint32_t)K) return KEY_NONE - 1ull;
+  if (lo == hi) return hi;
+  const int top = 63 - __clzll((long long)(lo ^ hi));
+  uint64_t prefix = (top == 63) ? 0ull : (hi & (~0ull << (top + 1)));
+  uint32_t need = (uint32_t)K, cmatch = nv;
+  for (int b = top; b >= 0; --b) {
+    const uint64_t mask_hi = ~0ull << b;
+    uint32_t c0 = 0;
+#pragma unroll
+    for (int r = 0; r < R; ++r) c0 += ((key[r] & mask_hi) == prefix) ? 1u : 0u;
+    c0 = wave_reduce_u32(c0, [](uint32_t a, uint32_t x) { return a + x; });
+    if (need <= c0) {
+      cmatch = c0;
+    } else {
+      need -= c0;
+      cmatch -= c0;
+      prefix |= 1ull << b;
+    }
+    if (cmatch == need) return prefix | ((b == 0) ? 0ull : ((1ull << b) - 1ull));
+  }
+  return prefix;
+}
+
+// Packs the keys <= bound of every lane into out[0..) in LDS (any order) and pads the rest
+// of out[0..Kpad) with KEY_NONE.  For a single-wavefront workgroup.  Returns the count.
+template <int R>
+__device__ inline int wave_gather_selected(const uint64_t (&key)[R], uint64_t bound, uint64_t* out, int Kpad) {
+  const int lane = threadIdx.x & 63;
+  for (int i = lane; i < Kpad; i += 64) out[i] = KEY_NONE;
+  __syncthreads();
+  int base = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const bool sel = key[r] <= bound && key[r] != KEY_NONE;
+    const uint64_t m = __ballot(sel);
+    if (sel) {
+      const int pos = base + __popcll(m & ((1ull << lane) - 1ull));
+      if (pos < Kpad) out[pos] = key[r];
+    }
+    base += __popcll(m);
+  }
+  __syncthreads();
+  return base;
+}
+
 __host__ __device__ inline int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;

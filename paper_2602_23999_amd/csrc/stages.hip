@@ -104,12 +104,57 @@ __global__ __launch_bounds__(256) void select_probes_kernel(const float* __restr
   }
 }
 
+// The same selection with one wavefront per query and the whole score row in registers
+// (nlist <= 64*R): no LDS histogram, no workgroup barriers.
+template <int R>
+__global__ __launch_bounds__(64) void select_probes_wave_kernel(const float* __restrict__ scores,
+                                                               const float* __restrict__ sq_norm,
+                                                               const float* __restrict__ centroid_sq, int nlist,
+                                                               int nprobe, int npad, int metric,
+                                                               int32_t* __restrict__ probe_ids,
+                                                               float* __restrict__ probe_G,
+                                                               float* __restrict__ probe_E) {
+  extern __shared__ uint64_t sel_out[];  // [npad]
+  const int lane = threadIdx.x;
+  const int64_t q = blockIdx.x;
+  const float* row = scores + q * nlist;
+  uint64_t key[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int i = r * 64 + lane;
+    key[r] = (i < nlist) ? make_key(row[i], (uint32_t)i) : KEY_NONE;
+  }
+  const uint64_t bound = wave_kth_bound<R>(key, nprobe);
+  wave_gather_selected<R>(key, bound, sel_out, npad);
+  block_bitonic_sort(sel_out, npad);
+  for (int r = lane; r < nprobe; r += 64) {
+    const uint64_t k2 = sel_out[r];
+    const int c = (int)(uint32_t)k2;
+    const float s = ord2f((uint32_t)(k2 >> 32));
+    probe_ids[q * nprobe + r] = c;
+    probe_G[q * nprobe + r] = s;
+    const float d2 = (metric == RABITQ_L2) ? s : (sq_norm[q] + centroid_sq[c] + 2.0f * s);
+    probe_E[q * nprobe + r] = sqrtf(fmaxf(d2, 0.f));
+  }
+}
+
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const int npad = next_pow2(nprobe);
-  hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)nq), dim3(256), npad * sizeof(uint64_t), st, scores, sq_norm,
-                     centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  const size_t smem = npad * sizeof(uint64_t);
+  if (nlist <= 64 * 8)
+    hipLaunchKernelGGL(select_probes_wave_kernel<8>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm, centroid_sq,
+                       nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  else if (nlist <= 64 * 16)
+    hipLaunchKernelGGL(select_probes_wave_kernel<16>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
+                       centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  else if (nlist <= 64 * 32)
+    hipLaunchKernelGGL(select_probes_wave_kernel<32>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
+                       centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  else
+    hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)nq), dim3(256), smem, st, scores, sq_norm, centroid_sq,
+                       nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }
