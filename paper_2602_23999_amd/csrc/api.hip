@@ -142,6 +142,8 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
   ix->F = field_bits_of(d->total_bits);
   ix->LW = D * ix->F / 32;
   ix->n_tiles = tiles; ix->n_slots = tiles * TILE;
+  ix->host_tiles.resize(nlist);
+  for (int c = 0; c < nlist; ++c) ix->host_tiles[c] = tile_off[c + 1] - tile_off[c];
   hipStream_t st = static_cast<hipStream_t>(stream);
   int rc = RABITQ_OK;
   hipError_t he = hipGetDevice(&ix->device);

@@ -360,6 +360,8 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
     tiles += (h_off[c + 1] - h_off[c] + TILE - 1) / TILE;
   }
   h_tile[nlist] = (int32_t)tiles;
+  ix->host_tiles.resize(nlist);
+  for (int c = 0; c < nlist; ++c) ix->host_tiles[c] = h_tile[c + 1] - h_tile[c];
   if (tiles > (0x7fffffff / TILE)) { set_error("index build: too many slots"); return RABITQ_EINVAL; }
   ix->n_tiles = tiles;
   ix->n_slots = tiles * TILE;

@@ -55,6 +55,7 @@ struct rabitq_index {
   uint32_t* long_codes = nullptr;
   float* long_factors = nullptr;
   int32_t* ids = nullptr;
+  std::vector<int32_t> host_tiles;  // tiles per cluster (host copy, sizes the scan grid)
   // options
   int prune = 1;
   int scan_impl = 0;

@@ -33,6 +33,7 @@ struct ScanArgs {
   const int32_t* pair_ids;
   const int32_t* item_off;
   int nprobe, k, pool, cand_stride;
+  int tseg, segmax;  // a cluster of more than tseg tiles is scanned in up to segmax segments (separate work items)
   // outputs
   uint64_t* cand_keys;
   int32_t* cand_cnt;
@@ -40,6 +41,12 @@ struct ScanArgs {
   int32_t* dbg_ip;
   const int64_t* dbg_off;
 };
+
+// number of segments a cluster of `tiles` tiles is split into
+__host__ __device__ inline int seg_count(int tiles, int tseg, int segmax) {
+  const int n = (tiles + tseg - 1) / tseg;
+  return n < 1 ? 1 : (n > segmax ? segmax : n);
+}
 
 bool seed_part0(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
 bool seed_part1(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);

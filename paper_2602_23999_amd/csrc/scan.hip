@@ -163,7 +163,14 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     if (a.item_off[mid] <= item) lo = mid; else hi = mid;
   }
   const int c = lo;
-  const int pbeg = a.pair_off[c] + (item - a.item_off[c]) * QW;
+  // a long cluster is scanned in nseg segments by separate work items
+  const int t0 = a.tile_off[c], tc1 = a.tile_off[c + 1];
+  const int nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
+  const int local = item - a.item_off[c];
+  const int grp = local / nseg, sidx = local - grp * nseg;
+  const int seglen = (tc1 - t0 + nseg - 1) / nseg;
+  const int ts = t0 + sidx * seglen, te = min(tc1, ts + seglen);
+  const int pbeg = a.pair_off[c] + grp * QW;
   const int np = min(QW, a.pair_off[c + 1] - pbeg);
 
   int pj[QW], Sj[QW], cnt[QW];
@@ -191,7 +198,6 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   }
   __syncthreads();
 
-  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
   int list_cnt = 0;
 
   // refine everything in the list (F > 0 only); wave-uniform control flow throughout
@@ -236,7 +242,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     list_cnt = 0;
   };
 
-  for (int tile = t0; tile < t1; ++tile) {
+  for (int tile = ts; tile < te; ++tile) {
     uint32_t cw[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) cw[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
@@ -283,14 +289,19 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 #pragma unroll
     for (int j = 0; j < QW; ++j) cnt[j] = pool_cnt[j];
   }
-  // every key still in a pool goes out, unsorted; the per-query merge selects among them
+  // every key still in a pool goes out, unsorted; the per-query merge selects among them.
+  // The segments of a split cluster share the pair's region (cand_cnt starts at 0 and is
+  // advanced atomically), each contributing at most k keys so that the region cannot overflow.
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
-    const uint64_t* pool = pools + (size_t)j * a.pool;
+    uint64_t* pool = pools + (size_t)j * a.pool;
+    if (nseg > 1 && cnt[j] > a.k) cnt[j] = pool_compact(pool, a.pool, cnt[j], a.k);
     __syncthreads();
-    if (lane == 0) a.cand_cnt[pj[j]] = cnt[j];
-    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.cand_stride + e] = pool[e];
+    int base = 0;
+    if (lane == 0 && cnt[j] > 0) base = atomicAdd(&a.cand_cnt[pj[j]], cnt[j]);
+    base = __builtin_amdgcn_readfirstlane(base);
+    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.cand_stride + base + e] = pool[e];
   }
 }
 
@@ -307,8 +318,9 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 // the popcount kernel; integer results are identical.
 // ---------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
-constexpr int MWAVES = 4;                          // wavefronts per work item (they split its tiles)
-constexpr int MLIST_CAP = 512 + MWAVES * QM * TILE;  // a round of tiles adds at most MWAVES*1024 survivors
+constexpr int MWAVES = 4;                     // wavefronts per work item (they split its tiles)
+constexpr int MLIST_FLUSH = 128;              // an owner list longer than this is refined before the next tiles
+constexpr int MLIST_CAP = MLIST_FLUSH + MWAVES * TILE * (QM / MWAVES);  // + what one round of tiles can add
 
 __device__ inline v4i expand16(uint32_t bits16) {  // 16 sign bits -> 16 bytes of 0/1
   v4i v;
@@ -319,6 +331,39 @@ __device__ inline v4i expand16(uint32_t bits16) {  // 16 sign bits -> 16 bytes o
   return v;
 }
 
+__device__ inline void wave_sync() {  // orders LDS traffic among the lanes of one wavefront
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// bitonic sort of n = 2^m keys in LDS by ONE wavefront of a larger workgroup (no workgroup barrier)
+__device__ inline void wave_bitonic_sort(uint64_t* keys, int n, int lane) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      wave_sync();
+      for (int t = lane; t < (n >> 1); t += 64) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const uint64_t x = keys[i], y = keys[l];
+        const bool up = (i & k) == 0;
+        if ((x > y) == up) {
+          keys[i] = y;
+          keys[l] = x;
+        }
+      }
+    }
+  }
+  wave_sync();
+}
+
+__device__ inline int wave_pool_compact(uint64_t* pool, int pool_n, int cnt, int k, int lane) {
+  wave_sync();
+  for (int i = cnt + lane; i < pool_n; i += 64) pool[i] = KEY_NONE;
+  wave_bitonic_sort(pool, pool_n, lane);
+  return min(cnt, k);
+}
+
 __device__ inline int block_pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   __syncthreads();
   for (int i = cnt + (int)threadIdx.x; i < pool_n; i += (int)blockDim.x) pool[i] = KEY_NONE;
@@ -326,6 +371,10 @@ __device__ inline int block_pool_compact(uint64_t* pool, int pool_n, int cnt, in
   return min(cnt, k);
 }
 
+// Work split inside the workgroup: every wavefront scans a quarter of the tiles for all 16
+// queries, but survivors are filed by OWNER: query j belongs to wavefront j % 4, which alone
+// refines them and keeps that query's pool.  Refinement therefore needs no workgroup
+// barrier; the wavefronts only meet once per round of tiles.
 template <int W, int F, bool DBG>
 __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF, KC = (W + 1) / 2;
@@ -336,8 +385,9 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   float* qs = reinterpret_cast<float*>(pool_kth + QM);              // [QM][2]: G, cB*sum(q')
   int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QM);              // [QM]
   int* qidx = pool_cnt + QM;                                        // [QM] query of each pair
-  int* s_list_cnt = qidx + QM;                                      // [4]
-  uint32_t* list = reinterpret_cast<uint32_t*>(s_list_cnt + 4);     // [MLIST_CAP] (F > 0)
+  int* s_list_cnt = qidx + QM;                                      // [MWAVES] entries in each owner list
+  int* s_misc = s_list_cnt + MWAVES;                                // [4]
+  uint32_t* lists = reinterpret_cast<uint32_t*>(s_misc + 4);        // [MWAVES][MLIST_CAP] (F > 0)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lj = lane & 15, g = lane >> 4;
 
   const int nb = gridDim.x;
@@ -350,7 +400,13 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
     if (a.item_off[mid] <= item) lo = mid; else hi = mid;
   }
   const int c = lo;
-  const int pbeg = a.pair_off[c] + (item - a.item_off[c]) * QM;
+  const int t0 = a.tile_off[c], tc1 = a.tile_off[c + 1];
+  const int nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
+  const int local = item - a.item_off[c];
+  const int grp = local / nseg, sidx = local - grp * nseg;
+  const int seglen = (tc1 - t0 + nseg - 1) / nseg;
+  const int ts = t0 + sidx * seglen, t1 = min(tc1, ts + seglen);
+  const int pbeg = a.pair_off[c] + grp * QM;
   const int np = min(QM, a.pair_off[c + 1] - pbeg);
 
   // query operand: lane (row lj, k-group g) holds qhat[16g .. 16g+15] of every 64-dim chunk
@@ -371,9 +427,9 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
       pool_kth[lj] = KEY_NONE;
       pool_cnt[lj] = 0;
     }
-    if (tid == 0) s_list_cnt[0] = 0;
+    if (tid < MWAVES) s_list_cnt[tid] = 0;
   }
-  // scalars of this lane's four queries (rows 4g .. 4g+3)
+  // scalars of this lane's four queries (rows 4g .. 4g+3; query 4g+r is owned by wavefront r)
   float al[4], be[4], Gr[4], Er[4], tr[4];
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
@@ -389,9 +445,8 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   }
   __syncthreads();
 
-  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
-
-  auto compact_if_full = [&](int room) {  // afterwards every pool has `room` free slots
+  // F == 0 only: the pools are filled by all wavefronts straight from the tiles
+  auto block_compact_if_full = [&](int room) {
 #pragma unroll 1
     for (int jj = 0; jj < QM; ++jj) {
       const int cj = pool_cnt[jj];
@@ -407,11 +462,12 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
     }
   };
 
-  auto flush = [&]() {  // refine everything in the survivor list (F > 0); each wavefront takes NS entries per round
-    __syncthreads();
-    const int list_cnt = s_list_cnt[0];
-    for (int base = 0; base < list_cnt; base += MWAVES * NS) {
-      const int idx = base + wave * NS + lane / G, t = lane % G;
+  // F > 0: this wavefront refines its own list (queries j with j % 4 == wave) into its own pools
+  auto flush_own = [&]() {
+    uint32_t* list = lists + (size_t)wave * MLIST_CAP;
+    const int list_cnt = s_list_cnt[wave];
+    for (int base = 0; base < list_cnt; base += NS) {
+      const int idx = base + lane / G, t = lane % G;
       const bool valid = idx < list_cnt;
       const uint32_t e = valid ? list[idx] : 0u;
       const int j = (int)(e >> 28);
@@ -427,19 +483,36 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
           pools[(size_t)j * a.pool + pos] = key;
         }
       }
-      __syncthreads();
-      compact_if_full(MWAVES * NS);
+      wave_sync();
+#pragma unroll
+      for (int rr = 0; rr < QM / MWAVES; ++rr) {  // the four pools this wavefront owns
+        const int jj = MWAVES * rr + wave;
+        const int cj = pool_cnt[jj];
+        if (cj + NS > a.pool) {
+          uint64_t* pool = pools + (size_t)jj * a.pool;
+          const int nc = wave_pool_compact(pool, a.pool, cj, a.k, lane);
+          if (lane == 0) {
+            pool_cnt[jj] = nc;
+            if (nc >= a.k) pool_kth[jj] = pool[a.k - 1];
+          }
+          wave_sync();
+        }
+      }
     }
-    __syncthreads();
-    if (tid == 0) s_list_cnt[0] = 0;
-    __syncthreads();
+    wave_sync();
+    if (lane == 0) s_list_cnt[wave] = 0;
   };
 
-  for (int tb = t0; tb < t1; tb += MWAVES) {
+  for (int tb = ts; tb < t1; tb += MWAVES) {
     if (F > 0) {
-      if (s_list_cnt[0] > 512) flush();
+      // workgroup-uniform decision (the counts were last written before the barrier below)
+      const int longest = max(max(s_list_cnt[0], s_list_cnt[1]), max(s_list_cnt[2], s_list_cnt[3]));
+      if (longest > MLIST_FLUSH) {
+        flush_own();
+        __syncthreads();
+      }
     } else {
-      compact_if_full(MWAVES * TILE);
+      block_compact_if_full(MWAVES * TILE);
     }
     const int tile = tb + wave;
     if (tile < t1) {
@@ -457,8 +530,6 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
           acc[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa[kc], xb, acc[cb], 0, 0, 0);
         }
       }
-      uint32_t my[4] = {0u, 0u, 0u, 0u};  // survivor bits per column block (bit r = query 4g+r)
-      int n_mine = 0;
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb) {
         const int v = 16 * cb + lj;
@@ -475,39 +546,36 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
           const float e1 = fmaf(fr, x, fa + Gr[r]);
           const float filt = (F > 0) ? fmaf(-fe, Er[r], e1) : e1;
           if (filt <= tr[r]) {
+            const int j = 4 * g + r;
             if (F == 0) {  // B == 1: the 1-bit estimate is the final key
-              const int j = 4 * g + r;
               const uint64_t key = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + v]);
               if (key <= pool_kth[j]) pools[(size_t)j * a.pool + atomicAdd(&pool_cnt[j], 1)] = key;
-            } else {
-              my[cb] |= 1u << r;
-              ++n_mine;
+            } else {       // file the survivor with the owner of query j (= wavefront r)
+              const int pos = atomicAdd(&s_list_cnt[r], 1);
+              lists[(size_t)r * MLIST_CAP + pos] = ((uint32_t)j << 28) | (uint32_t)((tile - t0) * TILE + v);
             }
           }
         }
       }
-      if (F > 0 && n_mine > 0) {
-        int pos = atomicAdd(&s_list_cnt[0], n_mine);
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (my[cb] & (1u << r))
-              list[pos++] = ((uint32_t)(4 * g + r) << 28) | (uint32_t)((tile - t0) * TILE + 16 * cb + lj);
-      }
     }
     __syncthreads();
   }
-  if (F > 0) flush();
-  __syncthreads();
-  compact_if_full(a.pool - a.cand_stride);  // a pool larger than the output region is cut to its k best
+  if (F > 0) {
+    flush_own();
+    __syncthreads();
+  }
+  // a pool larger than the output region, or any pool of a split cluster, is cut to its k best
+  block_compact_if_full(nseg > 1 ? a.pool - a.k : a.pool - a.cand_stride);
 #pragma unroll 1
   for (int j = 0; j < np; ++j) {
     const uint64_t* pool = pools + (size_t)j * a.pool;
     const int cj = pool_cnt[j];
     const int pp = a.pair_ids[pbeg + j];
-    if (tid == 0) a.cand_cnt[pp] = cj;
-    for (int e = tid; e < cj; e += 64 * MWAVES) a.cand_keys[(int64_t)pp * a.cand_stride + e] = pool[e];
+    if (tid == 0) s_misc[0] = cj > 0 ? atomicAdd(&a.cand_cnt[pp], cj) : 0;
+    __syncthreads();
+    const int base = s_misc[0];
+    for (int e = tid; e < cj; e += 64 * MWAVES) a.cand_keys[(int64_t)pp * a.cand_stride + base + e] = pool[e];
+    __syncthreads();
   }
 }
 
@@ -539,8 +607,8 @@ static void launch_seed_wf(const ScanArgs& a, int64_t nq, hipStream_t st) {
 template <int W, int F>
 static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   const size_t smem = (size_t)QM * a.pool * sizeof(uint64_t) +
-                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + 4 * sizeof(int) +
-                      (F > 0 ? MLIST_CAP * sizeof(uint32_t) : 0);
+                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + 4) * sizeof(int) +
+                      (F > 0 ? (size_t)MWAVES * MLIST_CAP * sizeof(uint32_t) : 0);
   if (dbg)
     hipLaunchKernelGGL((scan_mfma_kernel<W, F, true>), dim3(grid), dim3(64 * MWAVES), smem, st, a);
   else
@@ -605,8 +673,9 @@ bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, int impl, unsigned grid
   }
 }
 
-#if defined(RQ_STATS) && RQ_PART == 0
-extern "C" int rabitq_debug_scan_stats(unsigned long long* out, int reset) {
+#if defined(RQ_STATS)
+// development only: one counter block per translation unit (part), summed by the caller
+extern "C" int RQ_PART_NAME(rabitq_debug_scan_stats)(unsigned long long* out, int reset) {
   if (hipMemcpyFromSymbol(out, HIP_SYMBOL(g_scan_stats), sizeof(g_scan_stats)) != hipSuccess) return -3;
   if (reset) {
     unsigned long long z[8] = {0};

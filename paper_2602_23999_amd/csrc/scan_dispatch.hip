@@ -1,5 +1,7 @@
 // Host-side launchers of the seeding and scan kernels: argument block, work-item
 // offsets, and routing to the translation unit that holds the kernels for W = dim/32.
+#include <algorithm>
+
 #include "rq_internal.h"
 #include "rq_scan_args.h"
 
@@ -7,16 +9,25 @@ namespace rq {
 
 // ---------------------------------------------------------------------------------
 // item_off[c] = first work item of cluster c; a work item is qw consecutive pairs of
-// one cluster.  (One workgroup.)
+// one cluster times one segment of its tiles.  (One workgroup.)
 // ---------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off, int n, int qw,
-                                                          int32_t* __restrict__ item_off) {
+__global__ void zero_i32_kernel(int32_t* p, int64_t n) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
+}
+
+__global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off,
+                                                          const int32_t* __restrict__ tile_off, int n, int qw, int tseg,
+                                                          int segmax, int32_t* __restrict__ item_off) {
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;
   const int per = (n + 255) / 256;
   const int s = tid * per, e = min(n, s + per);
   uint32_t sum = 0;
-  for (int i = s; i < e; ++i) sum += (uint32_t)(pair_off[i + 1] - pair_off[i] + qw - 1) / qw;
+  auto items = [&](int i) -> uint32_t {
+    return (uint32_t)((pair_off[i + 1] - pair_off[i] + qw - 1) / qw) *
+           (uint32_t)seg_count(tile_off[i + 1] - tile_off[i], tseg, segmax);
+  };
+  for (int i = s; i < e; ++i) sum += items(i);
   part[tid] = sum;
   __syncthreads();
   for (int d = 1; d < 256; d <<= 1) {
@@ -28,7 +39,7 @@ __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __rest
   uint32_t run = part[tid] - sum;
   for (int i = s; i < e; ++i) {
     item_off[i] = (int32_t)run;
-    run += (uint32_t)(pair_off[i + 1] - pair_off[i] + qw - 1) / qw;
+    run += items(i);
   }
   if (tid == 255) item_off[n] = (int32_t)part[255];
 }
@@ -108,11 +119,24 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
   a.item_off = item_off;
-  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->nlist, qw, item_off);
+  // long clusters are scanned in segments of about tseg tiles by separate work items; each segment of a split
+  // cluster contributes at most k keys to the pair's region of cand_stride keys (cand_cnt is advanced atomically)
+  a.tseg = 32;
+  a.segmax = std::max(1, a.cand_stride / k);
+  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
+                     a.segmax, item_off);
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nq * nprobe + 255) / 256, 4096)), dim3(256), 0, st,
+                     cand_cnt, nq * nprobe);
   if (after_setup) RQ_HIP(hipEventRecord(after_setup, st));
   // at most ceil(pairs/qw) + nlist work items; the kernel drops the excess
   const int64_t npairs = nq * nprobe;
+  // grid bound: a cluster has at most cnt_c/qw + 1 groups of pairs; one split into nseg segments has nseg times
+  // as many work items, and cnt_c <= nq
   int64_t max_items = (npairs + qw - 1) / qw + ix->nlist;
+  for (int32_t t : ix->host_tiles) {
+    const int ns = seg_count(t, a.tseg, a.segmax);
+    if (ns > 1) max_items += (int64_t)(ns - 1) * ((std::min<int64_t>(nq, npairs) + qw - 1) / qw + 1);
+  }
   max_items = ((max_items + 7) / 8) * 8;
   if (max_items > 0x7fffffff) {
     set_error("scan: too many work items");
