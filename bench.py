@@ -92,6 +92,81 @@ def cpu_baseline(w, nprobe, sample_n=100_000, sample_q=200):
                        f"index build {t_build:.1f}s not included")
 
 
+def stream_scan(args):
+    """Streaming regime of the code scan: an index whose 1-bit codes and factors (28 B per
+    vector at D = 128) are several times larger than the 256 MB last-level cache, searched
+    with nprobe = 1 by one query per inverted list, so every byte the scan needs comes from
+    HBM exactly once.  The whole search path runs; the line reports the scan kernel."""
+    import torch
+    from paper_2602_23999_amd import rabitq
+    rabitq.load_library()
+    n, dim, nlist, bits, k = args.stream_n, 128, args.stream_n // args.stream_list, args.stream_bits, 10
+    gen = torch.Generator(device="cuda").manual_seed(1234)
+    centres = torch.randn((nlist, dim), generator=gen, device="cuda") * 4.0
+    X = torch.empty((n, dim), dtype=torch.float32, device="cuda")
+    own = torch.randint(0, nlist, (n,), generator=gen, device="cuda")
+    for s0 in range(0, n, 1 << 20):
+        e0 = min(n, s0 + (1 << 20))
+        X[s0:e0] = centres[own[s0:e0]] + torch.randn((e0 - s0, dim), generator=gen, device="cuda")
+    g = np.random.Generator(np.random.PCG64(7)).standard_normal((dim, dim))
+    qm, rm = np.linalg.qr(g)
+    P = (qm * np.sign(np.diag(rm))[None, :]).astype(np.float32)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    gi = rabitq.Index.build(X, nlist, bits, P, metric="l2", kmeans_iters=4, train_size=n // 10)
+    torch.cuda.synchronize()
+    log(f"[bench] stream-scan index N={n} nlist={nlist} B={bits}: {time.perf_counter() - t0:.2f}s")
+    offsets = np.empty(nlist + 1, np.int64)
+    rabitq._check(rabitq.load_library().rabitq_index_export(gi._h, None, None, offsets.ctypes.data, None, None, None,
+                                                           None, None))
+    cluster_sizes = np.diff(offsets).astype(np.int64)
+    # one query per generating centre: a fresh draw around it
+    Qd = centres + torch.randn((nlist, dim), generator=gen, device="cuda")
+    del X, own
+    # keep one query per distinct nearest list, so that no two pairs share a list
+    first = gi.coarse_probe(gi.rotate(Qd), gi.query_prep(gi.rotate(Qd))["sq_norm"], 1)["probe_ids"].view(-1).long()
+    pick = torch.full((nlist,), Qd.shape[0], dtype=torch.int64, device="cuda")
+    pick.scatter_reduce_(0, first, torch.arange(Qd.shape[0], device="cuda"), reduce="amin")
+    Qd = Qd[pick[pick < Qd.shape[0]]].contiguous()
+    nq = Qd.shape[0]
+    out_ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
+    out_d = torch.empty((nq, k), dtype=torch.float32, device="cuda")
+    gi.set_option("scan_impl", args.scan_impl)
+    for _ in range(args.warmup):
+        gi.search(Qd, k, 1, out_ids, out_d)
+    gi.set_option("profile", args.steps)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(args.steps):
+        gi.search(Qd, k, 1, out_ids, out_d)
+    torch.cuda.synchronize()
+    sec = (time.perf_counter() - t) / args.steps
+    stage_ms, calls = gi.stage_ms()
+    gi.set_option("profile", 0)
+    alg_bytes, qv = scan_algorithmic_bytes(gi, Qd, 1, cluster_sizes, dim)
+    probes = gi.coarse_probe(gi.rotate(Qd), gi.query_prep(gi.rotate(Qd))["sq_norm"], 1)["probe_ids"]
+    distinct = int(torch.unique(probes).numel())
+    scan_ms = stage_ms["scan"]
+    achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    res = {
+        "metric": "code-scan HBM GB/s vs peak, streaming regime (1 GPU)", "value": achieved, "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u32 popcount + f32", "data": "synthetic",
+        "config": {"workload": f"stream_scan: N={n} D={dim} nlist={nlist} B={bits} nq={nq} k={k} nprobe=1 "
+                               f"(one query per list; {distinct} distinct lists probed)",
+                   "index_short_bytes": int(cluster_sizes.sum()) * (dim // 8 + 12),
+                   "list_size_median_max": [int(np.median(cluster_sizes)), int(cluster_sizes.max())],
+                   "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "stage_ms_calls": calls,
+                   "query_vector_evaluations": qv},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "scan_kernel" if args.scan_impl == 0 else "scan_mfma_kernel",
+                     "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
+    }
+    print(json.dumps(res), flush=True)
+    gi.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -105,6 +180,12 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--stream-scan", action="store_true",
+                    help="measure the code scan in the streaming regime instead (index far larger than the caches, "
+                         "one query per list); prints its own JSON line")
+    ap.add_argument("--stream-n", type=int, default=32 * 1024 * 1024)
+    ap.add_argument("--stream-bits", type=int, default=1)
+    ap.add_argument("--stream-list", type=int, default=1024, help="mean inverted-list length of the streaming index")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures the one-GPU path only: this build has no multi-GPU sharding (run with --gpus 1)")
@@ -114,6 +195,8 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a HIP device")
     rabitq.load_library()
+    if args.stream_scan:
+        return stream_scan(args)
     w = synth.WORKLOADS[args.workload]
     if args.n:
         w = w.scaled(n=args.n, nlist=max(64, int(round(w.nlist * args.n / w.n))))

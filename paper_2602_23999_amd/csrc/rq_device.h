@@ -277,6 +277,24 @@ __device__ inline int wave_gather_selected(const uint64_t (&key)[R], uint64_t bo
   return base;
 }
 
+// Largest c in [0, n) with off[c] <= v, for a non-decreasing array off[0..n] with off[0] <= v < off[n]
+// (any v >= off[n] gives n - 1).  One wavefront, 64-ary: every level is a single coalesced load and a ballot,
+// so the chain of dependent loads is ceil(log64(n + 1)) long.  Every index read is within [0, n].
+__device__ inline int wave_upper_cluster(const int32_t* __restrict__ off, int n, int v, int lane) {
+  int stride = 1;
+  while ((int64_t)stride * 64 < (int64_t)n + 1) stride *= 64;
+  int base = 0;
+  for (; stride >= 1; stride >>= 6) {
+    const int64_t idx = (int64_t)base + (int64_t)lane * stride;
+    const bool in = idx < n;
+    const int val = off[in ? idx : n];
+    const uint64_t m = __ballot(in && val <= v);
+    const int cnt = __popcll(m);
+    base += (cnt > 0 ? cnt - 1 : 0) * stride;
+  }
+  return base;
+}
+
 __host__ __device__ inline int next_pow2(int v) {
   int p = 1;
   while (p < v) p <<= 1;

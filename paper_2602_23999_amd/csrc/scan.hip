@@ -151,18 +151,13 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 
   // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
   // contiguous range of work items; items of one cluster then share one L2.
-  const int nb = gridDim.x;
-  const int per = (nb + 7) >> 3;
-  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  // (the grid is an upper bound of the number of work items; the ranges are cut from the true count)
   const int n_items = a.item_off[a.nlist];
-  if (item >= n_items) return;
+  const int per = (n_items + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per || item >= n_items) return;
   // cluster of this item: largest c with item_off[c] <= item
-  int lo = 0, hi = a.nlist;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.item_off[mid] <= item) lo = mid; else hi = mid;
-  }
-  const int c = lo;
+  const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
   // a long cluster is scanned in nseg segments by separate work items
   const int t0 = a.tile_off[c], tc1 = a.tile_off[c + 1];
   const int nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
@@ -390,16 +385,11 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   uint32_t* lists = reinterpret_cast<uint32_t*>(s_misc + 4);        // [MWAVES][MLIST_CAP] (F > 0)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lj = lane & 15, g = lane >> 4;
 
-  const int nb = gridDim.x;
-  const int per = (nb + 7) >> 3;
+  const int n_items = a.item_off[a.nlist];
+  const int per = (n_items + 7) >> 3;
   const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if (item >= a.item_off[a.nlist]) return;
-  int lo = 0, hi = a.nlist;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if (a.item_off[mid] <= item) lo = mid; else hi = mid;
-  }
-  const int c = lo;
+  if ((int)(blockIdx.x >> 3) >= per || item >= n_items) return;
+  const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
   const int t0 = a.tile_off[c], tc1 = a.tile_off[c + 1];
   const int nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
   const int local = item - a.item_off[c];

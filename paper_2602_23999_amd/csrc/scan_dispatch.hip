@@ -1,6 +1,7 @@
 // Host-side launchers of the seeding and scan kernels: argument block, work-item
 // offsets, and routing to the translation unit that holds the kernels for W = dim/32.
 #include <algorithm>
+#include <functional>
 
 #include "rq_internal.h"
 #include "rq_scan_args.h"
@@ -128,15 +129,23 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nq * nprobe + 255) / 256, 4096)), dim3(256), 0, st,
                      cand_cnt, nq * nprobe);
   if (after_setup) RQ_HIP(hipEventRecord(after_setup, st));
-  // at most ceil(pairs/qw) + nlist work items; the kernel drops the excess
+  // Grid bound.  Cluster c with cnt_c pairs and nseg_c segments has ceil(cnt_c / qw) * nseg_c work items, at most
+  // (cnt_c / qw + 1) * nseg_c.  Every query probes nprobe distinct clusters, so cnt_c <= nq and sum cnt_c = nq * nprobe:
+  // the sum is largest when the nprobe clusters with the most segments are probed by every query.  The kernel
+  // drops the blocks beyond the true count.
   const int64_t npairs = nq * nprobe;
-  // grid bound: a cluster has at most cnt_c/qw + 1 groups of pairs; one split into nseg segments has nseg times
-  // as many work items, and cnt_c <= nq
-  int64_t max_items = (npairs + qw - 1) / qw + ix->nlist;
-  for (int32_t t : ix->host_tiles) {
-    const int ns = seg_count(t, a.tseg, a.segmax);
-    if (ns > 1) max_items += (int64_t)(ns - 1) * ((std::min<int64_t>(nq, npairs) + qw - 1) / qw + 1);
+  std::vector<int>& nseg = ix->seg_sorted;
+  if (ix->seg_sorted_max != a.segmax) {
+    nseg.resize(ix->host_tiles.size());
+    for (size_t c = 0; c < nseg.size(); ++c) nseg[c] = seg_count(ix->host_tiles[c], a.tseg, a.segmax);
+    std::sort(nseg.begin(), nseg.end(), std::greater<int>());
+    ix->seg_sorted_max = a.segmax;
+    ix->seg_total = 0;
+    for (int v : nseg) ix->seg_total += v;
   }
+  int64_t top = 0;
+  for (int i = 0; i < nprobe && i < (int)nseg.size(); ++i) top += nseg[i];
+  int64_t max_items = ix->seg_total + (nq * top + qw - 1) / qw;
   max_items = ((max_items + 7) / 8) * 8;
   if (max_items > 0x7fffffff) {
     set_error("scan: too many work items");
