@@ -122,7 +122,14 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   a.item_off = item_off;
   // long clusters are scanned in segments of about tseg tiles by separate work items; each segment of a split
   // cluster contributes at most k keys to the pair's region of cand_stride keys (cand_cnt is advanced atomically)
-  a.tseg = 32;
+  // The segment length adapts to the batch: a large batch has more work items than the chip has wavefront slots and
+  // keeps long segments (32 tiles); a small batch is cut finer, down to 2 tiles, so that about 4096 items exist.
+  {
+    const int64_t np_all = nq * nprobe;
+    const int64_t est_items = std::min<int64_t>(np_all, (np_all + qw - 1) / qw + ix->nlist);
+    const int64_t avg_tiles = std::max<int64_t>(1, ix->n_tiles / std::max(1, ix->nlist));
+    a.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
+  }
   a.segmax = std::max(1, a.cand_stride / k);
   hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
                      a.segmax, item_off);
@@ -135,11 +142,12 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // drops the blocks beyond the true count.
   const int64_t npairs = nq * nprobe;
   std::vector<int>& nseg = ix->seg_sorted;
-  if (ix->seg_sorted_max != a.segmax) {
+  if (ix->seg_sorted_max != a.segmax || ix->seg_sorted_tseg != a.tseg) {
     nseg.resize(ix->host_tiles.size());
     for (size_t c = 0; c < nseg.size(); ++c) nseg[c] = seg_count(ix->host_tiles[c], a.tseg, a.segmax);
     std::sort(nseg.begin(), nseg.end(), std::greater<int>());
     ix->seg_sorted_max = a.segmax;
+    ix->seg_sorted_tseg = a.tseg;
     ix->seg_total = 0;
     for (int v : nseg) ix->seg_total += v;
   }
