@@ -12,6 +12,13 @@ Readings taken where the paper is silent
   ``delta = max|q'| / 7``, ``qhat = clamp(rint(q'/delta), -7, 7)`` (round half to
   even), both evaluated in fp32 because they decide integers; 4 two's-complement
   bit-planes, plane 3 weighted -8.
+* Lookup-table variant (Section 3.4.1(1), U = 4; the paper fixes neither the
+  stored type nor the summation): ``L_j(b)`` is the fp32 sum, in ascending
+  dimension order, of the ``q'[4j+i]`` whose bit ``b_i`` is set (bit i of the
+  table index is dimension 4j+i), stored as binary16 (the paper's FP16
+  example); ``<x_b, q'>`` is the fp32 sum of the looked-up entries in ascending
+  block order.  Both are precision decisions of the variant, so they are part of
+  its definition here.  The query is not quantised in this variant.
 * Refinement uses the unquantised fp32 ``q'`` (Section 3.4.2 says only "the
   query").
 * Threshold (Section 3.3.4 "current K-th best distance"): the running value is
@@ -31,6 +38,12 @@ rotate_queries, coarse_probe  pinned: direct ||q'-c'||^2 loop, full argsort.
 quantize_query, bitplanes     pinned: |delta*qhat - q'| <= delta/2, planes
                               reassemble to qhat, storage size of Section 3.4.1.
 ip_bitplane                   pinned: exhaustive identity of Section 3.4.1(2).
+lut_tables / ip_lut           pinned: every entry against the fp64 dot product of
+                              its block within binary16 rounding, the table
+                              size of Section 3.4.1(1), the blockwise sum against
+                              the fp64 <x_b, q'> within the rounding bound, and
+                              exactness on queries whose partial sums are
+                              representable.
 estimate_1bit / _refined      pinned via build.vector_factors pins; refined
                               estimate error shrinking with B is a trend only
                               ("parity unpinned" for its exact values).
@@ -114,6 +127,49 @@ def ip_bitplane(xb_words: np.ndarray, planes: np.ndarray) -> np.ndarray:
     return out
 
 
+# ---- 3.4.1(1) ----------------------------------------------------------------
+LUT_U = 4  # dimensions per lookup block
+
+
+def lut_tables(qr: np.ndarray) -> np.ndarray:
+    """Lookup tables of one rotated query: ``[D/4, 16]`` binary16 with
+    ``L_j(b) = sum_i q'[4j+i] b_i`` (bit i of b is dimension 4j+i), the sum taken in
+    fp32 in ascending i and then rounded to binary16."""
+    qr = np.asarray(qr, dtype=np.float32)
+    m = qr.shape[0] // LUT_U
+    t = np.zeros((m, 1 << LUT_U), dtype=np.float32)
+    for b in range(1 << LUT_U):
+        acc = np.zeros(m, dtype=np.float32)
+        for i in range(LUT_U):
+            if (b >> i) & 1:
+                acc = (acc + qr[i::LUT_U][:m]).astype(np.float32)
+        t[:, b] = acc
+    return t.astype(np.float16)
+
+
+def ip_lut(xb_words: np.ndarray, tables: np.ndarray) -> np.ndarray:
+    """``<x_b, q'>`` for packed 1-bit codes [n, W] by one table lookup per block of
+    4 dimensions, summed in fp32 in ascending block order.  Returns fp32 [n]."""
+    n = xb_words.shape[0]
+    m = tables.shape[0]
+    acc = np.zeros(n, dtype=np.float32)
+    per_word = 32 // LUT_U
+    for j in range(m):
+        nib = (xb_words[:, j // per_word] >> np.uint32(LUT_U * (j % per_word))) & np.uint32(15)
+        acc = (acc + tables[j][nib].astype(np.float32)).astype(np.float32)
+    return acc
+
+
+def estimate_1bit_lut(G, E, short_factors, ip, sum_q):
+    """1-bit estimate and lower bound from ``ip = <x_b, q'>``:
+    ``<x_bar, q'> = ip - sum(q')/2`` with ``x_bar = u_b - 1/2``."""
+    f = short_factors.astype(np.float64)
+    ipq = ip.astype(np.float64) - 0.5 * float(sum_q)
+    est = G + f[:, 0] + f[:, 1] * ipq
+    lb = est - f[:, 2] * E
+    return est, lb
+
+
 def estimate_1bit(G, E, short_factors, delta, I, S):
     """1-bit estimate and its lower bound for one (query, cluster) pair.
     ``<x_bar, q'> ~= delta * (I - S/2)`` with ``x_bar = u_b - 1/2``."""
@@ -142,7 +198,11 @@ def topk_pairs(keys: np.ndarray, ids: np.ndarray, k: int):
 class Searcher:
     """Holds an index (oracle.build.build_index output) and answers batches."""
 
-    def __init__(self, index: dict):
+    def __init__(self, index: dict, ip_method: str = "bitwise"):
+        """``ip_method``: "bitwise" (Section 3.4.1(2), the default) or "lut"
+        (Section 3.4.1(1)) for the 1-bit inner product."""
+        assert ip_method in ("bitwise", "lut")
+        self.ip_method = ip_method
         self.ix = index
         self.words = short_words(index)  # [N, W] packed 1-bit codes
         self.B = index["total_bits"]
@@ -152,6 +212,10 @@ class Searcher:
     def pair(self, c, G, E, qr, delta, planes, S):
         ix = self.ix
         s, e = int(ix["offsets"][c]), int(ix["offsets"][c + 1])
+        if self.ip_method == "lut":
+            I = ip_lut(self.words[s:e], lut_tables(qr))
+            est1, lb1 = estimate_1bit_lut(G, E, ix["short_factors"][s:e], I, np.asarray(qr, np.float64).sum())
+            return s, e, I, est1, lb1
         I = ip_bitplane(self.words[s:e], planes)
         est1, lb1 = estimate_1bit(G, E, ix["short_factors"][s:e], delta, I, S)
         return s, e, I, est1, lb1
