@@ -160,7 +160,7 @@ def stream_scan(args):
                    "query_vector_evaluations": qv},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": "scan_kernel" if args.scan_impl == 0 else "scan_mfma_kernel",
+                     "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[args.scan_impl],
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
     }
     print(json.dumps(res), flush=True)
@@ -175,7 +175,8 @@ def main():
     ap.add_argument("--workload", default="l2_128")
     ap.add_argument("--nprobe", type=int, default=0, help="fix the operating point instead of choosing it by recall")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
-    ap.add_argument("--scan-impl", type=int, default=0, help="0: popcount scan (default), 1: matrix-core scan")
+    ap.add_argument("--scan-impl", type=int, default=0,
+                    help="0: popcount scan (default), 1: matrix-core scan, 2: lookup-table scan")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
@@ -270,7 +271,7 @@ def main():
         "metric": "queries/sec at recall@10~0.95 (1 GPU); code-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "u32 popcount + f32", "data": "synthetic",
+        "dtype": ("u32 popcount + f32", "i8 matrix cores + f32", "f16 tables + f32")[args.scan_impl], "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n} D={w.dim} nlist={w.nlist} B={w.total_bits} "
                                f"nq={w.nq} k={w.k} nprobe={nprobe}",
                    "recall_at_k": round(r_op, 4), "recall_target": 0.95, "nprobe_sweep": sweep,
@@ -279,7 +280,7 @@ def main():
                    "index_build_s": round(build_s, 4)},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic if args.scan_impl == 0 else None,
-                     "kernel": "scan_kernel" if args.scan_impl == 0 else "scan_mfma_kernel",
+                     "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[args.scan_impl],
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
     }
     if not args.no_cpu_baseline:

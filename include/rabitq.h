@@ -145,7 +145,12 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per
  *             wavefront; 1: the same integer inner products on the matrix cores (the sign
  *             bits of a tile are expanded to int8 once and contracted against 16 queries'
- *             qhat with v_mfma_i32_16x16x64_i8).  Results are identical; only speed differs.
+ *             qhat with v_mfma_i32_16x16x64_i8).  Results of 0 and 1 are identical; only speed differs.
+ *             2: the lookup-table scheme of Section 3.4.1(1) instead of the quantised query:
+ *             <x_b, q'> is the fp32 sum, in ascending block order, of one binary16 table entry per
+ *             4 dimensions (tables in LDS, 4 queries per wavefront).  Used by the threshold
+ *             seeding and the scan; its estimates differ from those of 0/1 by the query
+ *             quantisation error.
  * Errors: RABITQ_EINVAL for an unknown name or value. */
 int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
@@ -179,7 +184,11 @@ int rabitq_rotate(rabitq_index_t index, const float* queries, int64_t nq, float*
  *   qhat8    [nq][rabitq_qhat_stride(D)] i8: qhat as bytes, zero padded to a multiple of 64
  *            (the operand of the matrix-core variant of the scan)
  *   q_stage  [nq][D] fp32: q' in the order the refinement reads it (within each long-code
- *            word, dimension b*(8/F)+s of the word sits at position 4*s+b; identity if B == 1) */
+ *            word, dimension b*(8/F)+s of the word sits at position 4*s+b; identity if B == 1)
+ *   lut      [nq][D/4][16] binary16 bit patterns, or NULL (then not written; required by
+ *            "scan_impl" 2): the lookup tables of Section 3.4.1(1) with U = 4,
+ *            L_j(b) = sum of the q'[4j+i] whose bit i of b is set, summed in fp32 in ascending
+ *            i and rounded to binary16 */
 typedef struct {
   uint32_t* planes;
   float* delta;
@@ -188,6 +197,7 @@ typedef struct {
   float* sq_norm;
   int8_t* qhat8;
   float* q_stage;
+  uint16_t* lut;
 } rabitq_query_repr;
 int32_t rabitq_qhat_stride(int32_t dim); /* = dim rounded up to a multiple of 64 */
 int rabitq_query_prep(rabitq_index_t index, const float* q_rot, int64_t nq, const rabitq_query_repr* out,
@@ -227,7 +237,8 @@ int rabitq_seed_threshold(rabitq_index_t index, const rabitq_query_repr* repr, c
  *              holds every surviving key of the pair unless more than cap-16 survived, in
  *              which case it holds at least the k best of them.
  *   dbg_ip     optional (may be NULL) [sum over pairs, in pair_ids order, of 64*tiles(c)] i32:
- *              raw integer <x_b, qhat> of every slot; dbg_off [nq*nprobe+1] i64 gives each
+ *              raw integer <x_b, qhat> of every slot (scan_impl 2: the bits of the fp32 table sum
+ *              <x_b, q'>); dbg_off [nq*nprobe+1] i64 gives each
  *              pair's first entry (indexed by position in pair_ids).  For small inputs. */
 int32_t rabitq_cand_capacity(int32_t k); /* = smallest power of two >= k + 64; negative status if k is out of range */
 int rabitq_scan(rabitq_index_t index, const rabitq_query_repr* repr, const float* probe_G, const float* probe_E,

@@ -46,10 +46,10 @@ static void dev_free(T*& p) {
 
 static void free_workspace(Workspace& w) {
   dev_free(w.q_rot); dev_free(w.repr.planes); dev_free(w.repr.delta); dev_free(w.repr.sum_qhat);
-  dev_free(w.repr.sum_q); dev_free(w.repr.sq_norm); dev_free(w.repr.qhat8); dev_free(w.repr.q_stage); dev_free(w.tau); dev_free(w.scores); dev_free(w.probe_ids); dev_free(w.probe_G);
+  dev_free(w.repr.sum_q); dev_free(w.repr.sq_norm); dev_free(w.repr.qhat8); dev_free(w.repr.q_stage); dev_free(w.repr.lut); dev_free(w.tau); dev_free(w.scores); dev_free(w.probe_ids); dev_free(w.probe_G);
   dev_free(w.probe_E); dev_free(w.pair_off); dev_free(w.pair_ids); dev_free(w.list_scratch);
   dev_free(w.cand_keys); dev_free(w.cand_cnt);
-  w.cap_nq = w.cap_pairs = w.cap_cand = w.cap_scratch = 0;
+  w.cap_nq = w.cap_pairs = w.cap_cand = w.cap_scratch = w.cap_lut = 0;
 }
 
 static void free_index(rabitq_index* ix) {
@@ -73,7 +73,10 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   while (cap < k + TILE) cap <<= 1;
   const int64_t cand = pairs * cap;
   const int64_t scratch = probe_list_scratch_words(ix->nlist, nq);
-  if (nq <= w.cap_nq && pairs <= w.cap_pairs && cand <= w.cap_cand && scratch <= w.cap_scratch) return RABITQ_OK;
+  const bool want_lut = ix->scan_impl == 2;  // lookup tables only exist once the lookup-table scan is selected
+  if (nq <= w.cap_nq && pairs <= w.cap_pairs && cand <= w.cap_cand && scratch <= w.cap_scratch &&
+      (!want_lut || nq <= w.cap_lut))
+    return RABITQ_OK;
   hipError_t e = hipDeviceSynchronize();
   if (e != hipSuccess) return hip_fail(e, "hipDeviceSynchronize");
   const int64_t c_nq = std::max(nq, w.cap_nq), c_pairs = std::max(pairs, w.cap_pairs);
@@ -89,6 +92,7 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   RQ_A(w.repr.sq_norm, c_nq);
   RQ_A(w.repr.qhat8, c_nq * qhat_stride(ix->dim));
   RQ_A(w.repr.q_stage, c_nq * ix->dim);
+  if (want_lut) RQ_A(w.repr.lut, c_nq * ix->dim * 4);
   RQ_A(w.tau, c_nq);
   RQ_A(w.scores, c_nq * ix->nlist);
   RQ_A(w.probe_ids, c_pairs);
@@ -101,6 +105,7 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   RQ_A(w.cand_cnt, c_pairs);
 #undef RQ_A
   w.cap_nq = c_nq; w.cap_pairs = c_pairs; w.cap_cand = c_cand; w.cap_scratch = c_scr;
+  w.cap_lut = want_lut ? c_nq : 0;
   return RABITQ_OK;
 }
 
@@ -258,7 +263,7 @@ int rabitq_index_free(rabitq_index_t ix) {
 int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
-  if (!std::strcmp(name, "scan_impl") && (value == 0 || value == 1)) { ix->scan_impl = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 2) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile") && value >= 0 && value <= 4096) {
     const size_t have = ix->prof_sets.size();
     if ((size_t)value > have) {
@@ -440,7 +445,9 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   RQ_MARK();
   RQ_RUN(launch_gemm(queries, ix->rotation, w.q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, st));
   RQ_MARK();
-  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, ix->F, w.repr, st));
+  rabitq_query_repr repr = w.repr;
+  if (ix->scan_impl != 2) repr.lut = nullptr;  // tables are only built for the scan that reads them
+  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, ix->F, repr, st));
   RQ_MARK();
   RQ_RUN(launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
                      w.repr.sq_norm, ix->centroid_sq, st));

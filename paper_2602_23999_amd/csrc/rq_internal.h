@@ -17,7 +17,8 @@ inline int qhat_stride(int D) { return (D + 63) / 64 * 64; }
 struct Workspace {
   // per query
   float* q_rot = nullptr;
-  rabitq_query_repr repr = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  rabitq_query_repr repr = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  int64_t cap_lut = 0;  // queries the lookup tables were sized for (allocated on first use of scan_impl 2)
   float* tau = nullptr;
   // coarse
   float* scores = nullptr;

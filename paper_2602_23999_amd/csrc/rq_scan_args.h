@@ -21,6 +21,7 @@ struct ScanArgs {
   const int8_t* qhat8;    // [nq][Dp] 4-bit query as bytes (matrix-core scan)
   int Dp;
   const uint32_t* planes;
+  const uint16_t* lut;    // [nq][D/4][16] binary16 lookup tables (lookup-table scan only)
   const float* delta;
   const int32_t* sum_qhat;
   const float* sum_q;
@@ -48,10 +49,11 @@ __host__ __device__ inline int seg_count(int tiles, int tseg, int segmax) {
   return n < 1 ? 1 : (n > segmax ? segmax : n);
 }
 
-bool seed_part0(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
-bool seed_part1(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
-bool seed_part2(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st);
-// impl 0: popcount kernel (QW pairs per wavefront); impl 1: matrix-core kernel (QM pairs)
+// impl 0: popcount kernel (QW pairs per wavefront); impl 1: matrix-core kernel (QM pairs; seeds by popcount);
+// impl 2: lookup-table kernel (QW pairs)
+bool seed_part0(const ScanArgs& a, int W, int F, int impl, int64_t nq, hipStream_t st);
+bool seed_part1(const ScanArgs& a, int W, int F, int impl, int64_t nq, hipStream_t st);
+bool seed_part2(const ScanArgs& a, int W, int F, int impl, int64_t nq, hipStream_t st);
 bool scan_part0(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);
 bool scan_part1(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);
 bool scan_part2(const ScanArgs& a, int W, int F, int impl, unsigned grid, bool dbg, hipStream_t st);

@@ -14,6 +14,30 @@ __device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float
   return G + fa + fr * (hd * (float)(2 * I - S));
 }
 
+// Lookup-table variant (Section 3.4.1(1), U = 4): <x_b, q'> as the fp32 sum, in ascending
+// block order, of one binary16 entry per 4 dimensions; `lut` points at the query's tables
+// [8W][16] in LDS.  The order and the types are part of the variant's definition.
+template <int W>
+__device__ inline float ip_lut_of(const uint32_t (&cw)[W], const _Float16* lut) {
+  float acc = 0.f;
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t nib = (cw[w] >> (4 * i)) & 15u;
+      acc += (float)lut[(w * 8 + i) * 16 + nib];
+    }
+  }
+  return acc;
+}
+
+// copy one query's tables (W * 64 words) into LDS
+__device__ inline void stage_lut(_Float16* dst, const uint16_t* __restrict__ src, int W, int tid, int nt) {
+  const uint32_t* s32 = reinterpret_cast<const uint32_t*>(src);
+  uint32_t* d32 = reinterpret_cast<uint32_t*>(dst);
+  for (int i = tid; i < W * 64; i += nt) d32[i] = s32[i];
+}
+
 // copy one rotated query (already in refinement order) into LDS
 __device__ inline void stage_query(float* dst, const float* __restrict__ src, int D, int tid, int nt) {
   for (int i = tid; i < D; i += nt) dst[i] = src[i];
@@ -25,15 +49,16 @@ __device__ inline void stage_query(float* dst, const float* __restrict__ src, in
 // ---------------------------------------------------------------------------------
 constexpr int SEED_CHUNK_TILES = 32;  // 2048 keys per selection round
 
-template <int W, int F>
+template <int W, int F, int M>  // M = 1: lookup-table inner product
 __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   extern __shared__ unsigned char smem_raw[];
-  // layout: chunk keys [2048] u64 | best [kpad] u64 | out [kpad] u64 | qf [D] f32
+  // layout: chunk keys [2048] u64 | best [kpad] u64 | out [kpad] u64 | qf [D] f32 | tables [8W][16] f16 (M = 1)
   const int kpad = next_pow2(a.k);
   uint64_t* chunk = reinterpret_cast<uint64_t*>(smem_raw);
   uint64_t* best = chunk + SEED_CHUNK_TILES * TILE;
   uint64_t* out = best + kpad;
   float* qf = reinterpret_cast<float*>(out + kpad);
+  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + a.D);
   __shared__ SelectScratch sh;
   __shared__ int s_rank;
   __shared__ uint32_t s_max;
@@ -50,6 +75,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   }
   for (int i = tid; i < kpad; i += 256) best[i] = KEY_NONE;
   if (F > 0) stage_query(qf, a.q_stage + q * a.D, a.D, tid, 256);
+  if (M == 1) stage_lut(lut_s, a.lut + q * (int64_t)W * 128, W, tid, 256);
   __syncthreads();
   const int rank = s_rank;
   if (rank < 0) {
@@ -61,6 +87,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   const float G = a.probe_G[p];
   const float hd = 0.5f * a.delta[q];
   const int S = a.sum_qhat[q];
+  const float hsq = 0.5f * a.sum_q[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
   const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
 
@@ -74,7 +101,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
       const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
       const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
       int I;
-      const float e1 = est1_of<W>(cw, pl, fa, fr, G, hd, S, &I);
+      const float e1 = (M == 1) ? G + fa + fr * (ip_lut_of<W>(cw, lut_s) - hsq) : est1_of<W>(cw, pl, fa, fr, G, hd, S, &I);
       const bool real = a.ids[(int64_t)tile * TILE + lane] >= 0;
       chunk[tl * TILE + lane] = real ? make_key(e1, (uint32_t)((tile - t0) * TILE + lane)) : KEY_NONE;
     }
@@ -136,7 +163,7 @@ __device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   return min(cnt, k);
 }
 
-template <int W, int F, bool DBG>
+template <int W, int F, bool DBG, int M>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
 __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF;
   constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
@@ -147,6 +174,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QW);                 // [QW]
   uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QW);         // [LIST_CAP] (F > 0)
   float* qf = reinterpret_cast<float*>(list + (F > 0 ? LIST_CAP : 0)); // [QW][D] (F > 0)
+  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + (F > 0 ? QW * a.D : 0));  // [QW][8W][16] (M = 1)
   const int lane = threadIdx.x;
 
   // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
@@ -169,7 +197,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int np = min(QW, a.pair_off[c + 1] - pbeg);
 
   int pj[QW], Sj[QW], cnt[QW];
-  float Gj[QW], Ej[QW], hdj[QW], tauj[QW];
+  float Gj[QW], Ej[QW], hdj[QW], tauj[QW], hsqj[QW];
   int64_t qj[QW];
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
@@ -181,6 +209,8 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     Ej[j] = a.probe_E[pp];
     hdj[j] = 0.5f * a.delta[q];
     Sj[j] = a.sum_qhat[q];
+    hsqj[j] = 0.5f * a.sum_q[q];
+    if (M == 1) stage_lut(lut_s + j * W * 128, a.lut + q * (int64_t)W * 128, W, lane, 64);
     tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
     cnt[j] = 0;
     if (lane == 0) {
@@ -252,7 +282,14 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     for (int j = 0; j < QW; ++j) {
       const_u32_ptr pl = (const_u32_ptr)(a.planes + qj[j] * 4 * W + opaque0);
       int I;
-      const float e1 = est1_of<W>(cw, pl, fa, fr, Gj[j], hdj[j], Sj[j], &I);
+      float e1;
+      if (M == 1) {
+        const float ipf = ip_lut_of<W>(cw, lut_s + j * W * 128);
+        I = __float_as_int(ipf);
+        e1 = Gj[j] + fa + fr * (ipf - hsqj[j]);
+      } else {
+        e1 = est1_of<W>(cw, pl, fa, fr, Gj[j], hdj[j], Sj[j], &I);
+      }
       if (DBG) {
         if (j < np) a.dbg_ip[a.dbg_off[pbeg + j] + (int64_t)(tile - t0) * TILE + lane] = I;
       }
@@ -588,10 +625,13 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
 #endif
 
 template <int W, int F>
-static void launch_seed_wf(const ScanArgs& a, int64_t nq, hipStream_t st) {
+static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t st) {
   const int kpad = next_pow2(a.k);
   const size_t smem = (size_t)(SEED_CHUNK_TILES * TILE + 2 * kpad) * sizeof(uint64_t) + (size_t)a.D * sizeof(float);
-  hipLaunchKernelGGL((seed_kernel<W, F>), dim3((unsigned)nq), dim3(256), smem, st, a);
+  if (impl == 2)
+    hipLaunchKernelGGL((seed_kernel<W, F, 1>), dim3((unsigned)nq), dim3(256), smem + (size_t)W * 256, st, a);
+  else
+    hipLaunchKernelGGL((seed_kernel<W, F, 0>), dim3((unsigned)nq), dim3(256), smem, st, a);
 }
 
 template <int W, int F>
@@ -605,23 +645,24 @@ static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipS
     hipLaunchKernelGGL((scan_mfma_kernel<W, F, false>), dim3(grid), dim3(64 * MWAVES), smem, st, a);
 }
 
-template <int W, int F>
+template <int W, int F, int M>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
-                      (F > 0 ? LIST_CAP * sizeof(uint32_t) + (size_t)QW * a.D * sizeof(float) : 0);
+                      (F > 0 ? LIST_CAP * sizeof(uint32_t) + (size_t)QW * a.D * sizeof(float) : 0) +
+                      (M == 1 ? (size_t)QW * W * 256 : 0);
   if (dbg)
-    hipLaunchKernelGGL((scan_kernel<W, F, true>), dim3(grid), dim3(64), smem, st, a);
+    hipLaunchKernelGGL((scan_kernel<W, F, true, M>), dim3(grid), dim3(64), smem, st, a);
   else
-    hipLaunchKernelGGL((scan_kernel<W, F, false>), dim3(grid), dim3(64), smem, st, a);
+    hipLaunchKernelGGL((scan_kernel<W, F, false, M>), dim3(grid), dim3(64), smem, st, a);
 }
 
 template <int W>
-static void seed_by_f(const ScanArgs& a, int F, int64_t nq, hipStream_t st) {
+static void seed_by_f(const ScanArgs& a, int F, int impl, int64_t nq, hipStream_t st) {
   switch (F) {
-    case 0: launch_seed_wf<W, 0>(a, nq, st); break;
-    case 2: launch_seed_wf<W, 2>(a, nq, st); break;
-    case 4: launch_seed_wf<W, 4>(a, nq, st); break;
-    default: launch_seed_wf<W, 8>(a, nq, st); break;
+    case 0: launch_seed_wf<W, 0>(a, impl, nq, st); break;
+    case 2: launch_seed_wf<W, 2>(a, impl, nq, st); break;
+    case 4: launch_seed_wf<W, 4>(a, impl, nq, st); break;
+    default: launch_seed_wf<W, 8>(a, impl, nq, st); break;
   }
 }
 
@@ -636,18 +677,27 @@ static void scan_by_f(const ScanArgs& a, int F, int impl, unsigned grid, bool db
     }
     return;
   }
+  if (impl == 2) {
+    switch (F) {
+      case 0: launch_scan_wf<W, 0, 1>(a, grid, dbg, st); break;
+      case 2: launch_scan_wf<W, 2, 1>(a, grid, dbg, st); break;
+      case 4: launch_scan_wf<W, 4, 1>(a, grid, dbg, st); break;
+      default: launch_scan_wf<W, 8, 1>(a, grid, dbg, st); break;
+    }
+    return;
+  }
   switch (F) {
-    case 0: launch_scan_wf<W, 0>(a, grid, dbg, st); break;
-    case 2: launch_scan_wf<W, 2>(a, grid, dbg, st); break;
-    case 4: launch_scan_wf<W, 4>(a, grid, dbg, st); break;
-    default: launch_scan_wf<W, 8>(a, grid, dbg, st); break;
+    case 0: launch_scan_wf<W, 0, 0>(a, grid, dbg, st); break;
+    case 2: launch_scan_wf<W, 2, 0>(a, grid, dbg, st); break;
+    case 4: launch_scan_wf<W, 4, 0>(a, grid, dbg, st); break;
+    default: launch_scan_wf<W, 8, 0>(a, grid, dbg, st); break;
   }
 }
 
 // Return false when W is not one of this part's widths.
-bool RQ_PART_NAME(seed)(const ScanArgs& a, int W, int F, int64_t nq, hipStream_t st) {
+bool RQ_PART_NAME(seed)(const ScanArgs& a, int W, int F, int impl, int64_t nq, hipStream_t st) {
   switch (W) {
-#define RQ_X(W_) case W_: seed_by_f<W_>(a, F, nq, st); return true;
+#define RQ_X(W_) case W_: seed_by_f<W_>(a, F, impl, nq, st); return true;
     RQ_W_LIST(RQ_X)
 #undef RQ_X
     default: return false;

@@ -83,18 +83,29 @@ static int bad_width() {
 
 static void set_repr(ScanArgs& a, const rabitq_index* ix, const rabitq_query_repr& r) {
   a.q_stage = r.q_stage; a.qhat8 = r.qhat8; a.Dp = qhat_stride(ix->dim);
-  a.planes = r.planes; a.delta = r.delta; a.sum_qhat = r.sum_qhat; a.sum_q = r.sum_q;
+  a.planes = r.planes; a.delta = r.delta; a.sum_qhat = r.sum_qhat; a.sum_q = r.sum_q; a.lut = r.lut;
+}
+
+static int need_lut(const rabitq_index* ix, const rabitq_query_repr& r) {
+  if (ix->scan_impl == 2 && r.lut == nullptr) {
+    set_error("scan_impl 2 needs the lookup tables (rabitq_query_repr.lut)");
+    return RABITQ_EINVAL;
+  }
+  return RABITQ_OK;
 }
 
 int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
+  if (int rc = need_lut(ix, repr)) return rc;
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
   a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
   a.nprobe = nprobe; a.k = k; a.tau_out = tau;
   const int W = ix->W, F = field_bits(ix->total_bits);
-  if (!(seed_part0(a, W, F, nq, st) || seed_part1(a, W, F, nq, st) || seed_part2(a, W, F, nq, st))) return bad_width();
+  const int impl = ix->scan_impl;
+  if (!(seed_part0(a, W, F, impl, nq, st) || seed_part1(a, W, F, impl, nq, st) || seed_part2(a, W, F, impl, nq, st)))
+    return bad_width();
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }
@@ -104,6 +115,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
                 uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
                 hipEvent_t after_setup) {
   if (nq <= 0) return RABITQ_OK;
+  if (int rc = need_lut(ix, repr)) return rc;
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
   const int impl = ix->scan_impl;

@@ -55,6 +55,19 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict
   }
 #pragma unroll
   for (int d = 32; d > 0; d >>= 1) S += __shfl_xor(S, d, 64);
+  // Section 3.4.1(1): lookup tables, one entry per (block of 4 dimensions, 4-bit pattern); the sum runs in
+  // fp32 over the set bits in ascending dimension order and is rounded to binary16
+  if (o.lut != nullptr) {
+    _Float16* lut = reinterpret_cast<_Float16*>(o.lut) + q * (int64_t)D * 4;
+    for (int e = lane; e < D * 4; e += 64) {
+      const int j = e >> 4, b = e & 15;
+      float acc = 0.f;
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        if ((b >> i) & 1) acc += x[4 * j + i];
+      lut[e] = (_Float16)acc;
+    }
+  }
   if (lane == 0) {
     o.delta[q] = dl;
     o.sum_qhat[q] = S;

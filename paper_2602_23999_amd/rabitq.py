@@ -42,7 +42,7 @@ class _Desc(C.Structure):
 
 class _QueryRepr(C.Structure):
     _fields_ = [("planes", C.c_void_p), ("delta", C.c_void_p), ("sum_qhat", C.c_void_p), ("sum_q", C.c_void_p),
-                ("sq_norm", C.c_void_p), ("qhat8", C.c_void_p), ("q_stage", C.c_void_p)]
+                ("sq_norm", C.c_void_p), ("qhat8", C.c_void_p), ("q_stage", C.c_void_p), ("lut", C.c_void_p)]
 
 
 class _BuildParams(C.Structure):
@@ -243,7 +243,8 @@ class Index:
         return _QueryRepr(_dev(prep["planes"], torch.int32), _dev(prep["delta"], torch.float32),
                           _dev(prep["sum_qhat"], torch.int32), _dev(prep["sum_q"], torch.float32),
                           _dev(prep["sq_norm"], torch.float32), _dev(prep["qhat8"], torch.int8),
-                          _dev(prep["q_stage"], torch.float32))
+                          _dev(prep["q_stage"], torch.float32),
+                          _dev(prep["lut"], torch.float16) if prep.get("lut") is not None else None)
 
     def query_prep(self, q_rot):
         """rabitq_query_prep: the per-query representation as a dict of device tensors."""
@@ -255,7 +256,8 @@ class Index:
                     sum_q=torch.empty(nq, dtype=torch.float32, device=dev),
                     sq_norm=torch.empty(nq, dtype=torch.float32, device=dev),
                     qhat8=torch.empty((nq, stride), dtype=torch.int8, device=dev),
-                    q_stage=torch.empty((nq, self.dim), dtype=torch.float32, device=dev))
+                    q_stage=torch.empty((nq, self.dim), dtype=torch.float32, device=dev),
+                    lut=torch.empty((nq, self.dim // 4, 16), dtype=torch.float16, device=dev))
         r = self._repr_struct(prep)
         _check(load_library().rabitq_query_prep(self._h, _dev(q_rot, torch.float32), nq, C.byref(r), _stream()))
         return prep

@@ -39,7 +39,8 @@ def oracle_stages(s: search.Searcher, Q: np.ndarray, k: int, nprobe: int) -> dic
     for i in range(nq):
         qhat[i, :D] = search.quantize_query(Qr[i])[1]
     F = 0 if ix["total_bits"] == 1 else build.long_field_bits(ix["total_bits"])
-    return dict(Qr=Qr, qhat=qhat, q_stage=stage_order(Qr, F), planes=planes, delta=delta, S=S, sum_q=Qr64.sum(1),
+    lut = np.stack([search.lut_tables(Qr[i]) for i in range(nq)])
+    return dict(lut=lut, Qr=Qr, qhat=qhat, q_stage=stage_order(Qr, F), planes=planes, delta=delta, S=S, sum_q=Qr64.sum(1),
                 sq_norm=(Qr64 ** 2).sum(1),
                 probes=probes, G=G, E=E, pair_off=pair_off, pair_ids=order, tau=tau)
 
@@ -63,7 +64,7 @@ def to_dev(st: dict, dev="cuda") -> dict:
     t = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a.astype(dt))).to(dev)
     prep = dict(planes=t(st["planes"].view(np.int32), np.int32), delta=t(st["delta"], np.float32),
                 sum_qhat=t(st["S"], np.int32), sum_q=t(st["sum_q"], np.float32), sq_norm=t(st["sq_norm"], np.float32),
-                qhat8=t(st["qhat"], np.int8), q_stage=t(st["q_stage"], np.float32))
+                qhat8=t(st["qhat"], np.int8), q_stage=t(st["q_stage"], np.float32), lut=t(st["lut"], np.float16))
     probes = dict(probe_ids=t(st["probes"], np.int32), probe_G=t(st["G"], np.float32), probe_E=t(st["E"], np.float32))
     return dict(q_rot=t(st["Qr"], np.float32), prep=prep, probes=probes, pair_off=t(st["pair_off"], np.int32),
                 pair_ids=t(st["pair_ids"], np.int32),

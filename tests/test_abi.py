@@ -53,3 +53,30 @@ def test_host_side_argument_errors_need_no_device():
     assert lib.rabitq_search(None, None, 1, 1, 1, None, None, None) == -1
     assert lib.rabitq_probe_list_scratch_words(1024, 10000) == 2 * 1024 * 313 + 1024
     assert lib.rabitq_index_free(None) == 0
+
+
+def _header_structs():
+    """name -> member names, for every `typedef struct { ... } name;` of the headers."""
+    out = {}
+    for fn in os.listdir(os.path.join(ROOT, "include")):
+        if fn.endswith(".h"):
+            text = open(os.path.join(ROOT, "include", fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            for body, name in re.findall(r"typedef\s+struct\s*\{(.*?)\}\s*(\w+)\s*;", text, flags=re.S):
+                members = []
+                for decl in body.split(";"):
+                    decl = decl.strip()
+                    if decl:  # "type a, b" declares two members
+                        members += [re.findall(r"(\w+)\s*$", part.strip())[0] for part in decl.split(",")]
+                out[name] = members
+    return out
+
+
+def test_binding_structures_match_the_header_member_for_member():
+    # a binding structure shorter than the header's makes the library read past its end
+    from paper_2602_23999_amd import rabitq
+    structs = _header_structs()
+    for cname, ctype in (("rabitq_query_repr", rabitq._QueryRepr), ("rabitq_index_desc", rabitq._Desc),
+                         ("rabitq_build_params", rabitq._BuildParams)):
+        assert [f[0] for f in ctype._fields_] == structs[cname], cname
+    assert ctypes.sizeof(rabitq._QueryRepr) == 8 * len(structs["rabitq_query_repr"])
