@@ -277,6 +277,63 @@ __device__ inline int wave_gather_selected(const uint64_t (&key)[R], uint64_t bo
   return base;
 }
 
+// ---------------------------------------------------------------------------------
+// Streaming selection of the K <= 64 smallest 64-bit keys by one wavefront, entirely in
+// registers: lane l holds the l-th smallest key seen so far.  The first 64 keys are sorted
+// across the lanes (bitonic network); afterwards a tile of 64 keys is compared with the
+// current K-th key and only the few that beat it are inserted, one at a time.  Keys are
+// unique (their low word is an index), so the result does not depend on the order of
+// arrival.  All control flow is wave-uniform.
+// ---------------------------------------------------------------------------------
+__device__ inline uint64_t shfl_u64(uint64_t v, int src) {
+  const uint32_t lo = (uint32_t)__shfl((int)(uint32_t)v, src, 64);
+  const uint32_t hi = (uint32_t)__shfl((int)(uint32_t)(v >> 32), src, 64);
+  return ((uint64_t)hi << 32) | lo;
+}
+__device__ inline uint64_t readlane_u64(uint64_t v, int src) {  // src must be wave-uniform
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, src);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)(v >> 32), src);
+  return ((uint64_t)hi << 32) | lo;
+}
+
+struct WaveTopK {
+  uint64_t v;  // lane l: l-th smallest key so far (KEY_NONE where there is none yet)
+
+  // the first tile: ascending bitonic sort of one key per lane
+  __device__ inline void init_sorted(uint64_t key, int lane) {
+#pragma unroll
+    for (int k = 2; k <= 64; k <<= 1) {
+#pragma unroll
+      for (int j = k >> 1; j > 0; j >>= 1) {
+        const uint64_t other = shfl_u64(key, lane ^ j);
+        const bool asc = (lane & k) == 0;
+        const bool low = (lane & j) == 0;
+        const bool take_min = (asc == low);
+        const uint64_t mn = key < other ? key : other, mx = key < other ? other : key;
+        key = take_min ? mn : mx;
+      }
+    }
+    v = key;
+  }
+
+  // a further tile: one key per lane
+  __device__ inline void push_tile(uint64_t key, int K, int lane) {
+    uint64_t kth = readlane_u64(v, K - 1);
+    uint64_t m = __ballot(key < kth);
+    while (m != 0ull) {
+      const int src = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)m) - 1);
+      m &= m - 1ull;
+      const uint64_t x = readlane_u64(key, src);
+      if (x < kth) {  // the K-th key may have dropped since the ballot
+        const int p = __popcll(__ballot(v < x));  // keys below x; x goes to position p (< K)
+        const uint64_t up = shfl_u64(v, lane > 0 ? lane - 1 : 0);
+        v = lane < p ? v : (lane == p ? x : up);
+        kth = readlane_u64(v, K - 1);
+      }
+    }
+  }
+};
+
 // Largest c in [0, n) with off[c] <= v, for a non-decreasing array off[0..n] with off[0] <= v < off[n]
 // (any v >= off[n] gives n - 1).  One wavefront, 64-ary: every level is a single coalesced load and a ballot,
 // so the chain of dependent loads is ceil(log64(n + 1)) long.  Every index read is within [0, n].

@@ -138,6 +138,88 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 }
 
 // ---------------------------------------------------------------------------------
+// Seeding with one wavefront per query (k <= 64, popcount inner products): the same
+// selection and refinement as seed_kernel, but the k smallest (est1, position) keys are
+// kept in registers while the cluster streams by, so there is no LDS and no barrier.
+// ---------------------------------------------------------------------------------
+template <int W, int F>
+__global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (q >= nq) return;
+  int rank = -1;
+  for (int b = 0; b < a.nprobe && rank < 0; b += 64) {
+    const int j = b + lane;
+    const bool ok = j < a.nprobe && a.cluster_size[a.probe_ids[q * a.nprobe + j]] >= a.k;
+    const uint64_t m = __ballot(ok);
+    if (m != 0ull) rank = b + __ffsll((unsigned long long)m) - 1;
+  }
+  if (rank < 0) {
+    if (lane == 0) a.tau_out[q] = 3.402823466e+38f;
+    return;
+  }
+  const int64_t p = q * a.nprobe + rank;
+  const int c = a.probe_ids[p];
+  const float G = a.probe_G[p];
+  const float hd = 0.5f * a.delta[q];
+  const int S = a.sum_qhat[q];
+  const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
+  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  WaveTopK top;
+  // U tiles are requested together so that their load latencies overlap (tiles past the end
+  // re-read the last tile and contribute no key)
+  constexpr int U = (W <= 4) ? 4 : (W <= 8 ? 2 : 1);
+  for (int tb = t0; tb < t1; tb += U) {
+    uint32_t cw[U][W];
+    float fa[U], fr[U];
+    bool real[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int tile = min(tb + u, t1 - 1);
+#pragma unroll
+      for (int w = 0; w < W; ++w) cw[u][w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
+      fa[u] = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
+      fr[u] = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
+      real[u] = tb + u < t1 && a.ids[(int64_t)tile * TILE + lane] >= 0;
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      int I;
+      const float e1 = est1_of<W>(cw[u], pl, fa[u], fr[u], G, hd, S, &I);
+      const uint64_t key = real[u] ? make_key(e1, (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
+      if (tb + u == t0) top.init_sorted(key, lane); else top.push_tile(key, a.k, lane);
+    }
+  }
+  if (F == 0) {
+    const uint64_t kth = readlane_u64(top.v, a.k - 1);
+    if (lane == 0) a.tau_out[q] = ord2f((uint32_t)(kth >> 32));
+    return;
+  }
+  // refine the k seeds, GL lanes per seed
+  constexpr int FF = (F > 0 ? F : 8), LW = W * FF, GL = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
+  const int grp = lane / GL, t = lane % GL;
+  const float csq = a.cB * a.sum_q[q];
+  uint32_t best = 0u;
+  for (int base = 0; base < a.k; base += NS) {
+    const int sidx = base + grp;
+    const uint32_t pos = (uint32_t)__shfl((int)(uint32_t)top.v, min(sidx, 63), 64);
+    float part = 0.f;
+    int64_t slot = 0;
+    if (sidx < a.k) {
+      slot = (int64_t)t0 * TILE + pos;
+      part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + q * a.D, t);
+    }
+    const float ip = group_sum<GL>(part);
+    if (sidx < a.k && t == 0) {
+      const float eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq);
+      best = max(best, f2ord(eB));
+    }
+  }
+  best = wave_reduce_u32(best, [](uint32_t x, uint32_t y) { return x > y ? x : y; });
+  if (lane == 0) a.tau_out[q] = fminf(ord2f(best), 3.402823466e+38f);
+}
+
+// ---------------------------------------------------------------------------------
 // Fused cluster-local search.  One wavefront (= one 64-thread workgroup) per work item:
 // QW pairs of the same cluster.  Lane l owns vector l of the current 64-vector tile; its
 // code words stay in registers while the plane words of the QW queries come through the
@@ -630,6 +712,8 @@ static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t 
   const size_t smem = (size_t)(SEED_CHUNK_TILES * TILE + 2 * kpad) * sizeof(uint64_t) + (size_t)a.D * sizeof(float);
   if (impl == 2)
     hipLaunchKernelGGL((seed_kernel<W, F, 1>), dim3((unsigned)nq), dim3(256), smem + (size_t)W * 256, st, a);
+  else if (a.k <= 64)
+    hipLaunchKernelGGL((seed_wave_kernel<W, F>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, a, nq);
   else
     hipLaunchKernelGGL((seed_kernel<W, F, 0>), dim3((unsigned)nq), dim3(256), smem, st, a);
 }

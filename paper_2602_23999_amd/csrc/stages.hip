@@ -151,12 +151,55 @@ __global__ __launch_bounds__(64) void select_probes_wave_kernel(const float* __r
   }
 }
 
+// The selection for nprobe <= 64 and any nlist, one wavefront per query: the score row is read
+// once, four 64-score tiles in flight, through a register-resident sorted list of the best.
+__global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* __restrict__ scores,
+                                                                  const float* __restrict__ sq_norm,
+                                                                  const float* __restrict__ centroid_sq, int64_t nq,
+                                                                  int nlist, int nprobe, int metric,
+                                                                  int32_t* __restrict__ probe_ids,
+                                                                  float* __restrict__ probe_G,
+                                                                  float* __restrict__ probe_E) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (q >= nq) return;
+  const float* row = scores + q * nlist;
+  WaveTopK top;
+  top.v = KEY_NONE;
+  for (int tb = 0; tb < nlist; tb += 256) {
+    uint64_t kk[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int i = tb + u * 64 + lane;
+      kk[u] = (i < nlist) ? make_key(row[i], (uint32_t)i) : KEY_NONE;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (tb + u * 64 < nlist) {
+        if (tb + u == 0) top.init_sorted(kk[u], lane); else top.push_tile(kk[u], nprobe, lane);
+      }
+    }
+  }
+  if (lane < nprobe) {
+    const uint64_t key = top.v;
+    const int c = (int)(uint32_t)key;
+    const float s = ord2f((uint32_t)(key >> 32));
+    probe_ids[q * nprobe + lane] = c;
+    probe_G[q * nprobe + lane] = s;
+    const float d2 = (metric == RABITQ_L2) ? s : (sq_norm[q] + centroid_sq[c] + 2.0f * s);
+    probe_E[q * nprobe + lane] = sqrtf(fmaxf(d2, 0.f));
+  }
+}
+
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const int npad = next_pow2(nprobe);
   const size_t smem = npad * sizeof(uint64_t);
-  if (nlist <= 64 * 8)
+  if (nprobe <= 64 && nlist > 64 * 32)  // rows too long for the register-resident kernels below
+    hipLaunchKernelGGL(select_probes_stream_kernel, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, scores, sq_norm,
+                       centroid_sq, nq, nlist, nprobe, metric, probe_ids, probe_G, probe_E);
+  else if (nlist <= 64 * 8)
     hipLaunchKernelGGL(select_probes_wave_kernel<8>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm, centroid_sq,
                        nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
   else if (nlist <= 64 * 16)
@@ -357,13 +400,69 @@ __global__ __launch_bounds__(256) void merge_kernel(const uint64_t* __restrict__
   }
 }
 
+// The same merge with one wavefront per query (k <= 64): the candidate lists stream through
+// a register-resident sorted list, G lanes per list, four entries per lane in flight.
+__global__ __launch_bounds__(256) void merge_wave_kernel(const uint64_t* __restrict__ cand_keys,
+                                                        const int32_t* __restrict__ cand_cnt, int64_t nq, int k,
+                                                        int cap, int nprobe, int metric,
+                                                        int64_t* __restrict__ out_ids, float* __restrict__ out_dists) {
+  const int lane = threadIdx.x & 63;
+  const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (q >= nq) return;
+  const uint64_t* keys = cand_keys + q * nprobe * (int64_t)cap;
+  const int32_t* cnt = cand_cnt + q * nprobe;
+  int G = 1;  // lanes per list: the largest power of two with G * nprobe <= 64
+  while (2 * G * nprobe <= 64) G <<= 1;
+  const int ppc = 64 / G, g = lane % G;
+  WaveTopK top;
+  top.v = KEY_NONE;
+  bool first = true;
+  for (int jb = 0; jb < nprobe; jb += ppc) {
+    const int j = jb + lane / G;
+    const int n = (j < nprobe) ? min(cnt[j], cap) : 0;
+    const int nmax = (int)wave_reduce_u32((uint32_t)n, [](uint32_t a, uint32_t b) { return a > b ? a : b; });
+    const uint64_t* row = keys + (int64_t)min(j, nprobe - 1) * cap;
+    for (int e0 = 0; e0 < nmax; e0 += 4 * G) {
+      uint64_t kk[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * G + g;
+        kk[u] = (e < n) ? row[e] : KEY_NONE;
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (e0 + u * G < nmax) {
+          if (first) top.init_sorted(kk[u], lane); else top.push_tile(kk[u], k, lane);
+          first = false;
+        }
+      }
+    }
+  }
+  if (lane < k) {
+    const uint64_t key = top.v;
+    int64_t id = -1;
+    float d = (metric == RABITQ_L2) ? INFINITY : -INFINITY;
+    if (key != KEY_NONE) {
+      id = (int64_t)(int32_t)(uint32_t)key;
+      d = ord2f((uint32_t)(key >> 32));
+      if (metric == RABITQ_IP) d = -d;
+    }
+    out_ids[q * k + lane] = id;
+    out_dists[q * k + lane] = d;
+  }
+}
+
 int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
                  int64_t* out_ids, float* out_dists, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const int kpad = next_pow2(k);
   const int cap = next_pow2(k + TILE);
-  hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(256), kpad * sizeof(uint64_t), st, cand_keys, cand_cnt, k,
-                     kpad, cap, nprobe, metric, out_ids, out_dists);
+  if (k <= 64)
+    hipLaunchKernelGGL(merge_wave_kernel, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, cand_keys, cand_cnt, nq, k,
+                       cap, nprobe, metric, out_ids, out_dists);
+  else
+    hipLaunchKernelGGL(merge_kernel, dim3((unsigned)nq), dim3(256), kpad * sizeof(uint64_t), st, cand_keys, cand_cnt, k,
+                       kpad, cap, nprobe, metric, out_ids, out_dists);
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }
