@@ -23,12 +23,15 @@ Readings taken where the paper is silent
   query").
 * Threshold (Section 3.3.4 "current K-th best distance"): the running value is
   order dependent on a parallel machine, so it is fixed per query before the
-  scan.  In the query's nearest probed cluster holding at least K vectors, the K
-  vectors with the smallest 1-bit estimates are refined and ``tau`` is the largest
-  of their refined estimates (for B = 1: the K-th smallest 1-bit estimate).
-  Every probed cluster is then filtered with that one ``tau``: a vector survives
-  when its 1-bit lower bound (B = 1: its 1-bit estimate) is <= tau.  ``tau`` is
-  always >= the final K-th best key of the unpruned search.
+  scan, as the K-th best distance after a first look at the nearest cluster.  In
+  the query's nearest probed cluster holding at least K vectors, the
+  ``M = max(K, SEED_M)`` vectors with the smallest 1-bit estimates (all of them if
+  the cluster is smaller; ties to the lower position) are refined and ``tau`` is
+  the K-th smallest of their refined estimates (for B = 1: the K-th smallest
+  1-bit estimate).  Every probed cluster is then filtered with that one ``tau``:
+  a vector survives when its 1-bit lower bound (B = 1: its 1-bit estimate) is
+  <= tau.  ``tau`` is always >= the final K-th best key of the unpruned search,
+  because K scanned vectors have keys <= tau.
 * Result: the K smallest (key, id) among survivors; L2 keys are estimated squared
   distances, IP keys are negated estimated inner products.
 
@@ -59,6 +62,7 @@ from .build import short_words
 
 FLT_MAX = float(np.finfo(np.float32).max)
 BQ = 4  # query bits (Section 3.4.1(2) example)
+SEED_M = 32  # 1-bit candidates refined to seed the threshold (at least K are taken)
 
 
 # ---- 3.3.1 -----------------------------------------------------------------
@@ -198,11 +202,13 @@ def topk_pairs(keys: np.ndarray, ids: np.ndarray, k: int):
 class Searcher:
     """Holds an index (oracle.build.build_index output) and answers batches."""
 
-    def __init__(self, index: dict, ip_method: str = "bitwise"):
+    def __init__(self, index: dict, ip_method: str = "bitwise", seed_m: int = SEED_M):
         """``ip_method``: "bitwise" (Section 3.4.1(2), the default) or "lut"
-        (Section 3.4.1(1)) for the 1-bit inner product."""
+        (Section 3.4.1(1)) for the 1-bit inner product.  ``seed_m``: number of 1-bit
+        candidates refined when the threshold is seeded (see the module header)."""
         assert ip_method in ("bitwise", "lut")
         self.ip_method = ip_method
+        self.seed_m = seed_m
         self.ix = index
         self.words = short_words(index)  # [N, W] packed 1-bit codes
         self.B = index["total_bits"]
@@ -233,11 +239,11 @@ class Searcher:
             if e - s < k:
                 continue
             _, _, _, est1, _ = self.pair(c, G, E, qr, delta, planes, S)
-            ids = ix["ids"][s:e].astype(np.int64)
-            sel = np.lexsort((ids, est1))[:k]
+            order = np.lexsort((np.arange(e - s), est1))  # by (1-bit estimate, position in the cluster)
             if self.B == 1:
-                return float(est1[sel[-1]])
-            return float(np.max(self.refined(s, e, G, qr, sel)))
+                return float(est1[order[k - 1]])
+            sel = order[:max(k, self.seed_m)]
+            return float(np.sort(self.refined(s, e, G, qr, sel))[k - 1])
         return FLT_MAX
 
     def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False, tau=None):

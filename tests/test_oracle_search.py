@@ -121,3 +121,80 @@ def test_ip_metric_search_orders_by_inner_product():
     assert exact.recall_at_k(ids, gt) >= 0.95
     assert np.all(np.diff(d, axis=1) <= 0)
     assert np.abs(d[:, 0] - gs[:, 0]).max() < 0.02
+
+
+def _seed_inputs(s, Q, nprobe):
+    ix = s.ix
+    Qr = search.rotate_queries(Q, ix["P"])
+    probes, G, E = search.coarse_probe(Qr, ix["centroids_rot"], nprobe, s.metric)
+    prep = []
+    for qr in Qr:
+        delta, qhat, S = search.quantize_query(qr)
+        prep.append((delta, search.query_bitplanes(qhat), S))
+    return Qr, probes, G, E, prep
+
+
+@pytest.mark.parametrize("B", [3, 8])
+def test_seeded_threshold_definition(B):
+    # Section 3.3.4 reading: tau = K-th smallest refined estimate among the M best 1-bit candidates
+    # of the nearest cluster.  Pins: M = K is the largest of the K refined seeds; M >= cluster size is
+    # the K-th key of the unpruned one-cluster search; tau never grows with M; tau bounds the final
+    # K-th key of the full search.
+    K = 10
+    X, Q, ix = _tiny(n=3000, nq=30, B=B)
+    Qr, probes, G, E, prep = _seed_inputs(search.Searcher(ix), Q, 4)
+    taus = {}
+    for M in (K, 16, search.SEED_M, 10 ** 6):
+        s = search.Searcher(ix, seed_m=M)
+        taus[M] = np.array([s.seed_threshold(probes[i], G[i], E[i], Qr[i], *prep[i], K) for i in range(len(Q))])
+    s = search.Searcher(ix)
+    assert s.seed_m == search.SEED_M == 32
+    sizes = np.diff(ix["offsets"])
+    assert np.all(sizes[probes[:, 0]] >= K)          # so the seeding cluster is the nearest one
+    # M = K: the largest refined estimate of the K best 1-bit candidates
+    for i in range(len(Q)):
+        c = int(probes[i, 0])
+        a, b, _, est1, _ = s.pair(c, G[i, 0], E[i, 0], Qr[i], *prep[i])
+        sel = np.lexsort((np.arange(b - a), est1))[:K]
+        assert taus[K][i] == s.refined(a, b, G[i, 0], Qr[i], sel).max()
+    # M >= |cluster|: K-th smallest key of the whole nearest cluster (unpruned search with nprobe = 1)
+    _, d1, _ = s.search(Q, K, 1, prune=False)
+    assert np.allclose(taus[10 ** 6], d1[:, K - 1], rtol=0, atol=0)
+    # monotone in M and valid
+    assert np.all(taus[K] >= taus[16]) and np.all(taus[16] >= taus[search.SEED_M])
+    assert np.all(taus[search.SEED_M] >= taus[10 ** 6])
+    assert (taus[K] > taus[search.SEED_M]).mean() > 0.3   # the wider seed set really tightens it
+    _, dfull, info = s.search(Q, K, 4, prune=False)
+    assert np.all(dfull[:, K - 1] <= taus[search.SEED_M])
+    assert np.array_equal(info["tau"] >= dfull[:, K - 1], np.ones(len(Q), bool))
+
+
+def test_seeded_threshold_one_bit_and_small_clusters():
+    K = 10
+    X, Q, ix = _tiny(n=3000, nq=20, B=1)
+    s = search.Searcher(ix)
+    Qr, probes, G, E, prep = _seed_inputs(s, Q, 3)
+    for i in range(len(Q)):
+        c = int(probes[i, 0])
+        _, _, _, est1, _ = s.pair(c, G[i, 0], E[i, 0], Qr[i], *prep[i])
+        assert s.seed_threshold(probes[i], G[i], E[i], Qr[i], *prep[i], K) == np.sort(est1)[K - 1]
+    # a cluster smaller than M but not smaller than K: all of it is refined
+    w = synth.WORKLOADS["tiny"].scaled(n=400, nq=10, n_centres=20)
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    ix = build.build_index(X, 20, 4)
+    s = search.Searcher(ix)
+    Qr, probes, G, E, prep = _seed_inputs(s, Q, 20)
+    sizes = np.diff(ix["offsets"])
+    hit = 0
+    for i in range(len(Q)):
+        tau = s.seed_threshold(probes[i], G[i], E[i], Qr[i], *prep[i], K)
+        ok = np.nonzero(sizes[probes[i]] >= K)[0]
+        if len(ok) == 0:
+            assert tau == search.FLT_MAX
+            continue
+        j = int(ok[0]); c = int(probes[i, j])
+        a, b = int(ix["offsets"][c]), int(ix["offsets"][c + 1])
+        if b - a <= search.SEED_M:
+            hit += 1
+            assert tau == np.sort(s.refined(a, b, G[i, j], Qr[i]))[K - 1]
+    assert hit > 0
