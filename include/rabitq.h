@@ -74,6 +74,11 @@ typedef struct {
   const float* long_factors;    /* [n_slots][2] f_add, f_rescale of the B-bit code;
                                    NULL when B == 1                                     */
   const int32_t* ids;           /* [n_slots] original id (Pid) of each stored vector    */
+  const float* mean;            /* [D] or NULL: a translation the index was built under (L2 only):
+                                   codes, factors and centroids describe the vectors minus `mean`,
+                                   and the search rotates (q - mean).  Squared distances do not
+                                   change; the rotated query, which Section 3.4.1(2) quantises to
+                                   4 bits, loses the offset all vectors share                */
 } rabitq_index_desc;
 
 /* Estimator read by the search (Section 2.2 leaves the expressions to an external
@@ -109,6 +114,8 @@ typedef struct {
   int64_t train_size;    /* vectors used for k-means; <= 0 or > n: all of them            */
   float epsilon0;        /* multiplier of the 1-bit error bound stored as f_err (e.g. 1.9) */
   const float* rotation; /* host, [D*D] row-major orthogonal P                            */
+  int32_t center;        /* 1: build on the vectors minus their mean (see rabitq_index_desc.mean;
+                            L2 only), 0: on the vectors as given                          */
 } rabitq_build_params;
 int rabitq_index_build(const rabitq_build_params* params, const float* data, rabitq_index_t* out, void* stream);
 
@@ -117,7 +124,7 @@ int rabitq_index_build(const rabitq_build_params* params, const float* data, rab
  * skip that array.  Device-synchronising.  Errors: RABITQ_EINVAL, RABITQ_EHIP. */
 int rabitq_index_export(rabitq_index_t index, float* rotation, float* centroids, int64_t* offsets,
                         uint32_t* short_codes, float* short_factors, uint32_t* long_codes, float* long_factors,
-                        int32_t* ids);
+                        int32_t* ids, float* mean /* [D], zeros if the index is not centred */);
 
 /* Frees the handle and everything it owns (device-synchronising).  NULL is allowed. */
 int rabitq_index_free(rabitq_index_t index);
@@ -173,7 +180,7 @@ int rabitq_stage_ms(rabitq_index_t index, float* out_ms, int32_t* out_calls);
  * buffer supplied by the caller (device pointers).  They exist so that each stage can
  * be checked and profiled with the previous stage's reference output injected. ---- */
 
-/* Section 3.3.1: q_rot [nq*D] = queries [nq*D] x P (fp32 MFMA). */
+/* Section 3.3.1: q_rot [nq*D] = (queries [nq*D] - mean) x P (fp32 MFMA; mean = 0 unless the index is centred). */
 int rabitq_rotate(rabitq_index_t index, const float* queries, int64_t nq, float* q_rot, void* stream);
 
 /* Section 3.3.3 / 3.4.1(2): the per-query representation, computed once per query and
@@ -220,9 +227,10 @@ int rabitq_build_probe_lists(rabitq_index_t index, const int32_t* probe_ids, int
                              int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, void* stream);
 
 /* Section 3.3.4 threshold: tau [nq] fp32.  In the query's nearest probed cluster with at
- * least k vectors, the k smallest 1-bit estimates (ties: lower position) are refined and
- * tau is the largest refined estimate (B == 1: the k-th smallest 1-bit estimate);
- * FLT_MAX when no probed cluster has k vectors. */
+ * least k vectors, the max(k, 32) vectors with the smallest 1-bit estimates (ties: lower
+ * position; all vectors if the cluster has fewer) are refined and tau is the k-th smallest
+ * refined estimate (B == 1: the k-th smallest 1-bit estimate); FLT_MAX when no probed
+ * cluster has k vectors. */
 int rabitq_seed_threshold(rabitq_index_t index, const rabitq_query_repr* repr, const int32_t* probe_ids,
                           const float* probe_G, const float* probe_E, int64_t nq, int32_t k, int32_t nprobe,
                           float* tau, void* stream);

@@ -66,9 +66,13 @@ SEED_M = 32  # 1-bit candidates refined to seed the threshold (at least K are ta
 
 
 # ---- 3.3.1 -----------------------------------------------------------------
-def rotate_queries(Q: np.ndarray, P: np.ndarray) -> np.ndarray:
-    """``Q' = Q P`` evaluated in float64 and stored as fp32 [nq, D]."""
-    return (np.asarray(Q, np.float64) @ np.asarray(P, np.float64)).astype(np.float32)
+def rotate_queries(Q: np.ndarray, P: np.ndarray, mean: np.ndarray | None = None) -> np.ndarray:
+    """``Q' = (Q - mean) P`` evaluated in float64 and stored as fp32 [nq, D]; ``mean`` is the
+    translation of a centred index (none or zeros otherwise)."""
+    q = np.asarray(Q, np.float64)
+    if mean is not None:
+        q = q - np.asarray(mean, np.float64)[None, :]
+    return (q @ np.asarray(P, np.float64)).astype(np.float32)
 
 
 # ---- 3.3.2 -----------------------------------------------------------------
@@ -254,7 +258,7 @@ class Searcher:
         ``tau`` (optional [nq]) replaces the seeded thresholds (used by stage tests)."""
         ix = self.ix
         if Qr is None:
-            Qr = rotate_queries(Q, ix["P"])
+            Qr = rotate_queries(Q, ix["P"], ix.get("mean"))
         nq = Qr.shape[0]
         probes, G, E = coarse_probe(Qr, ix["centroids_rot"], nprobe, self.metric)
         out_ids = np.full((nq, k), -1, dtype=np.int64)

@@ -54,7 +54,7 @@ static void free_workspace(Workspace& w) {
 
 static void free_index(rabitq_index* ix) {
   if (!ix) return;
-  dev_free(ix->rotation); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off);
+  dev_free(ix->rotation); dev_free(ix->mean_rot); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off);
   dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
   dev_free(ix->long_factors); dev_free(ix->ids);
   free_workspace(ix->ws);
@@ -107,6 +107,31 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   w.cap_nq = c_nq; w.cap_pairs = c_pairs; w.cap_cand = c_cand; w.cap_scratch = c_scr;
   w.cap_lut = want_lut ? c_nq : 0;
   return RABITQ_OK;
+}
+
+
+int set_index_mean(rabitq_index* ix, const float* mean, const float* rotation_host, hipStream_t st) {
+  const int D = ix->dim;
+  bool any = false;
+  for (int i = 0; i < D; ++i) any = any || mean[i] != 0.f;
+  if (!any) return RABITQ_OK;
+  if (ix->metric != RABITQ_L2) { set_error("a centred index needs the L2 metric"); return RABITQ_EINVAL; }
+  ix->host_mean.assign(mean, mean + D);
+  std::vector<float> mr(D);
+  for (int j = 0; j < D; ++j) {
+    double s = 0.0;
+    for (int i = 0; i < D; ++i) s += (double)mean[i] * (double)rotation_host[(size_t)i * D + j];
+    mr[j] = (float)s;
+  }
+  int rc = dev_alloc(&ix->mean_rot, (int64_t)D);
+  if (rc != RABITQ_OK) return rc;
+  RQ_HIP(hipMemcpyAsync(ix->mean_rot, mr.data(), (size_t)D * sizeof(float), hipMemcpyHostToDevice, st));
+  RQ_HIP(hipStreamSynchronize(st));  // mr dies at return
+  return RABITQ_OK;
+}
+
+int launch_rotate(const rabitq_index* ix, const float* q, float* q_rot, int64_t nq, hipStream_t st) {
+  return launch_gemm(q, ix->rotation, q_rot, nq, ix->dim, ix->dim, ix->mean_rot ? 4 : 0, nullptr, ix->mean_rot, st);
 }
 
 }  // namespace rq
@@ -194,6 +219,7 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
   } else {
     (void)hipStreamSynchronize(st);
   }
+  if (rc == RABITQ_OK && d->mean) rc = set_index_mean(ix, d->mean, d->rotation, st);
   if (rc != RABITQ_OK) { free_index(ix); return rc; }
   *out = ix;
   return RABITQ_OK;
@@ -207,6 +233,8 @@ int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_i
   if (p->metric != RABITQ_L2 && p->metric != RABITQ_IP) { set_error("build: bad metric"); return RABITQ_EINVAL; }
   if (p->kmeans_iters < 0 || !(p->epsilon0 >= 0.f)) { set_error("build: bad kmeans_iters or epsilon0"); return RABITQ_EINVAL; }
   if (!p->rotation || (!data && p->n > 0)) { set_error("build: null array"); return RABITQ_EINVAL; }
+  if (p->center != 0 && p->center != 1) { set_error("build: center must be 0 or 1"); return RABITQ_EINVAL; }
+  if (p->center && p->metric != RABITQ_L2) { set_error("build: a centred index needs the L2 metric"); return RABITQ_EINVAL; }
   rabitq_index* ix = new (std::nothrow) rabitq_index();
   if (!ix) { set_error("build: out of host memory"); return RABITQ_ENOMEM; }
   ix->dim = p->dim; ix->W = p->dim / 32; ix->nlist = p->nlist; ix->n = p->n; ix->total_bits = p->total_bits;
@@ -214,7 +242,8 @@ int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_i
   hipError_t he = hipGetDevice(&ix->device);
   int rc = (he == hipSuccess) ? RABITQ_OK : hip_fail(he, "hipGetDevice");
   if (rc == RABITQ_OK)
-    rc = build_index_device(ix, data, p->rotation, p->kmeans_iters, p->train_size, p->epsilon0, (hipStream_t)stream);
+    rc = build_index_device(ix, data, p->rotation, p->kmeans_iters, p->train_size, p->epsilon0, p->center,
+                            (hipStream_t)stream);
   if (rc != RABITQ_OK) {
     (void)hipDeviceSynchronize();
     free_index(ix);
@@ -225,8 +254,10 @@ int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_i
 }
 
 int rabitq_index_export(rabitq_index_t ix, float* rotation, float* centroids, int64_t* offsets, uint32_t* short_codes,
-                        float* short_factors, uint32_t* long_codes, float* long_factors, int32_t* ids) {
+                        float* short_factors, uint32_t* long_codes, float* long_factors, int32_t* ids, float* mean) {
   if (!ix) { set_error("export: null index"); return RABITQ_EINVAL; }
+  if (mean)
+    for (int i = 0; i < ix->dim; ++i) mean[i] = ix->host_mean.empty() ? 0.f : ix->host_mean[i];
   RQ_HIP(hipDeviceSynchronize());
   const int D = ix->dim, nlist = ix->nlist;
   const int64_t slots = ix->n_slots, tiles = ix->n_tiles;
@@ -333,7 +364,7 @@ int rabitq_rotate(rabitq_index_t ix, const float* queries, int64_t nq, float* q_
   if (rc) return rc;
   if (nq == 0) return RABITQ_OK;
   if (!queries || !q_rot) { set_error("rotate: null pointer"); return RABITQ_EINVAL; }
-  return launch_gemm(queries, ix->rotation, q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, (hipStream_t)stream);
+  return launch_rotate(ix, queries, q_rot, nq, (hipStream_t)stream);
 }
 
 static bool repr_ok(const rabitq_query_repr* r) {
@@ -443,7 +474,7 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
 #define RQ_MARK() do { if (ev) RQ_HIP(hipEventRecord(ev[stage++], st)); } while (0)
 #define RQ_RUN(call) do { if ((rc = (call)) != RABITQ_OK) return rc; } while (0)
   RQ_MARK();
-  RQ_RUN(launch_gemm(queries, ix->rotation, w.q_rot, nq, ix->dim, ix->dim, 0, nullptr, nullptr, st));
+  RQ_RUN(launch_rotate(ix, queries, w.q_rot, nq, st));
   RQ_MARK();
   rabitq_query_repr repr = w.repr;
   if (ix->scan_impl != 2) repr.lut = nullptr;  // tables are only built for the scan that reads them

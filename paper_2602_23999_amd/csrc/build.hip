@@ -290,6 +290,29 @@ struct DevBuf {
   T* release() { T* r = p; p = nullptr; return r; }
 };
 
+// Column means of a row-major [n][D] matrix in two fixed-order passes (deterministic): every
+// workgroup sums its own block of rows per column in fp64, then one workgroup adds the
+// partial sums in block order.
+constexpr int MEAN_BLOCKS = 1024;
+__global__ __launch_bounds__(256) void column_partial_kernel(const float* __restrict__ x, int64_t n, int D,
+                                                            double* __restrict__ partial) {
+  const int64_t rows_per = (n + MEAN_BLOCKS - 1) / MEAN_BLOCKS;
+  const int64_t r0 = (int64_t)blockIdx.x * rows_per, r1 = r0 + rows_per < n ? r0 + rows_per : n;
+  for (int d = threadIdx.x; d < D; d += 256) {
+    double acc = 0.0;
+    for (int64_t r = r0; r < r1; ++r) acc += (double)x[r * D + d];
+    partial[(int64_t)blockIdx.x * D + d] = acc;
+  }
+}
+__global__ __launch_bounds__(256) void column_mean_kernel(const double* __restrict__ partial, int64_t n, int D,
+                                                         float* __restrict__ mean) {
+  for (int d = threadIdx.x; d < D; d += 256) {
+    double acc = 0.0;
+    for (int b = 0; b < MEAN_BLOCKS; ++b) acc += partial[(int64_t)b * D + d];
+    mean[d] = (float)(acc / (double)n);
+  }
+}
+
 static unsigned grid_for(int64_t n, int block = 256, int64_t cap = 65535) {
   return (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + block - 1) / block, cap));
 }
@@ -308,7 +331,7 @@ static int assign_rows(const float* x, int64_t rows, int D, int nlist, const flo
 }
 
 int build_index_device(rabitq_index* ix, const float* data, const float* rotation_host, int kmeans_iters,
-                       int64_t train_size, float eps0, hipStream_t st) {
+                       int64_t train_size, float eps0, int center, hipStream_t st) {
   const int D = ix->dim, nlist = ix->nlist, B = ix->total_bits;
   const int64_t N = ix->n;
   int rc;
@@ -321,7 +344,20 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
   DevBuf<int32_t> asg, off, members;
   DevBuf<uint32_t> scratch;
   RQ_TRY(xr.alloc(N * D));
-  RQ_TRY(launch_gemm(data, ix->rotation, xr.p, N, D, D, 0, nullptr, nullptr, st));
+  if (center && N > 0) {
+    // mean of the raw vectors; every later step sees (x - mean) P = x P - mean P
+    DevBuf<double> partial;
+    DevBuf<float> mean_dev;
+    RQ_TRY(partial.alloc((int64_t)MEAN_BLOCKS * D));
+    RQ_TRY(mean_dev.alloc(D));
+    hipLaunchKernelGGL(column_partial_kernel, dim3(MEAN_BLOCKS), dim3(256), 0, st, data, N, D, partial.p);
+    hipLaunchKernelGGL(column_mean_kernel, dim3(1), dim3(256), 0, st, partial.p, N, D, mean_dev.p);
+    std::vector<float> mean(D);
+    RQ_HIP(hipMemcpyAsync(mean.data(), mean_dev.p, (size_t)D * sizeof(float), hipMemcpyDeviceToHost, st));
+    RQ_HIP(hipStreamSynchronize(st));
+    RQ_TRY(set_index_mean(ix, mean.data(), rotation_host, st));
+  }
+  RQ_TRY(launch_rotate(ix, data, xr.p, N, st));
   const int64_t nt = std::max<int64_t>(nlist, std::min<int64_t>(train_size > 0 ? train_size : N, N));
   RQ_TRY(tr.alloc(nt * D));
   RQ_TRY(c_rows.alloc((int64_t)nlist * D));

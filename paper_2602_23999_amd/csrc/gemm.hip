@@ -78,6 +78,7 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
       if (MODE == 1) v = rv + colv[n] - 2.0f * v;
       if (MODE == 2) v = -v;
       if (MODE == 3) v = colv[n] - 2.0f * v;
+      if (MODE == 4) v = v - colv[n];
       C[m * (int64_t)N + n] = v;
     }
   }
@@ -100,6 +101,7 @@ int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int 
     case 1: hipLaunchKernelGGL(gemm_kernel<1>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     case 2: hipLaunchKernelGGL(gemm_kernel<2>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     case 3: hipLaunchKernelGGL(gemm_kernel<3>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
+    case 4: hipLaunchKernelGGL(gemm_kernel<4>, grid, dim3(256), 0, st, A, B, C, M, N, K, rowv, colv); break;
     default: set_error("gemm: bad mode"); return RABITQ_EINVAL;
   }
   RQ_HIP(hipGetLastError());

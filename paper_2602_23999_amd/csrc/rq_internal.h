@@ -47,6 +47,8 @@ struct rabitq_index {
   int device = 0;
   // device arrays
   float* rotation = nullptr;        // [D][D]
+  float* mean_rot = nullptr;        // [D] mean * P of a centred index (nullptr: not centred)
+  std::vector<float> host_mean;     // [D] the mean itself (empty: not centred)
   float* centroids_t = nullptr;     // [D][nlist]  (transposed c')
   float* centroid_sq = nullptr;     // [nlist]
   int32_t* tile_off = nullptr;      // [nlist+1]
@@ -95,6 +97,7 @@ __host__ __device__ inline float ord2f(uint32_t o) {
 // ---- launchers (each returns a rabitq_status) ----
 // C[M,N] = A[M,K] * B[K,N], row-major fp32.  mode 0: plain.  mode 1 (L2 coarse):
 // C = rowv[m] + colv[n] - 2*acc.  mode 2 (IP coarse): C = -acc.  mode 3 (assignment): C = colv[n] - 2*acc.
+// mode 4 (rotation of a centred index): C = acc - colv[n].
 int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,
                 const float* colv, hipStream_t st);
 int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st);
@@ -113,6 +116,10 @@ int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq,
                  int64_t* out_ids, float* out_dists, hipStream_t st);
 int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);
 int build_index_device(rabitq_index* ix, const float* data, const float* rotation_host, int kmeans_iters,
-                       int64_t train_size, float eps0, hipStream_t st);
+                       int64_t train_size, float eps0, int center, hipStream_t st);
+// stores `mean` [D] (host) in the handle together with mean * P on the device
+int set_index_mean(rabitq_index* ix, const float* mean, const float* rotation_host, hipStream_t st);
+// Q' = (Q - mean) P for the handle's rotation
+int launch_rotate(const rabitq_index* ix, const float* q, float* q_rot, int64_t nq, hipStream_t st);
 
 }  // namespace rq

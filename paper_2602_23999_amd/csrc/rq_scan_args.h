@@ -5,6 +5,10 @@
 
 namespace rq {
 
+// Threshold seeding (Section 3.3.4): the max(k, SEED_M) best 1-bit candidates of the nearest cluster are refined
+// and tau is the k-th smallest refined estimate.
+constexpr int SEED_M = 32;
+
 struct ScanArgs {
   // index
   const uint32_t* short_codes;

@@ -1,4 +1,6 @@
 // Threshold seeding and the fused cluster-local search kernel (Sections 3.3.4, 3.4.1(2), 3.4.2).
+#include <algorithm>
+
 #include "rq_device.h"
 #include "rq_scan_args.h"
 
@@ -45,7 +47,8 @@ __device__ inline void stage_query(float* dst, const float* __restrict__ src, in
 
 // ---------------------------------------------------------------------------------
 // Seeding: one workgroup (256 threads) per query.  In the nearest probed cluster with
-// at least k vectors: k smallest (est1, position) -> refine -> tau = max refined.
+// at least k vectors: the m = max(k, SEED_M) smallest (est1, position) -> refine -> tau = k-th
+// smallest refined estimate (B == 1: the k-th smallest est1).
 // ---------------------------------------------------------------------------------
 constexpr int SEED_CHUNK_TILES = 32;  // 2048 keys per selection round
 
@@ -53,7 +56,8 @@ template <int W, int F, int M>  // M = 1: lookup-table inner product
 __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   extern __shared__ unsigned char smem_raw[];
   // layout: chunk keys [2048] u64 | best [kpad] u64 | out [kpad] u64 | qf [D] f32 | tables [8W][16] f16 (M = 1)
-  const int kpad = next_pow2(a.k);
+  const int m = max(a.k, SEED_M);
+  const int kpad = next_pow2(m);
   uint64_t* chunk = reinterpret_cast<uint64_t*>(smem_raw);
   uint64_t* best = chunk + SEED_CHUNK_TILES * TILE;
   uint64_t* out = best + kpad;
@@ -108,7 +112,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     __syncthreads();
     const int nc = nt * TILE;
     auto key_at = [&](int i) -> uint64_t { return i < nc ? chunk[i] : best[i - nc]; };
-    block_select_smallest(nc + kpad, a.k, kpad, key_at, out, &sh);
+    block_select_smallest(nc + kpad, m, kpad, key_at, out, &sh);
     for (int i = tid; i < kpad; i += 256) best[i] = out[i];
     __syncthreads();
   }
@@ -116,30 +120,34 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     if (tid == 0) a.tau_out[q] = ord2f((uint32_t)(best[a.k - 1] >> 32));
     return;
   }
-  // refine the k seeds, G lanes per seed
+  // refine the m seeds (fewer if the cluster is smaller), GL lanes per seed; their keys replace `out`
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF, GL = RefineShape<LW>::G;
   const int grp = tid / GL, t = tid % GL;
-  for (int base = 0; base < a.k; base += 256 / GL) {
+  for (int i = tid; i < kpad; i += 256) out[i] = KEY_NONE;
+  __syncthreads();
+  for (int base = 0; base < m; base += 256 / GL) {
     const int sidx = base + grp;
+    const bool valid = sidx < m && best[min(sidx, kpad - 1)] != KEY_NONE;
     float part = 0.f;
     int64_t slot = 0;
-    if (sidx < a.k) {
+    if (valid) {
       slot = (int64_t)t0 * TILE + (uint32_t)best[sidx];
       part = refine_lane<FF, LW>(a.long_codes + slot * LW, qf, t);
     }
     const float ip = group_sum<GL>(part);
-    if (sidx < a.k && t == 0) {
+    if (valid && t == 0) {
       const float eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - a.cB * a.sum_q[q]);
-      atomicMax(&s_max, f2ord(eB));
+      out[sidx] = make_key(eB, (uint32_t)sidx);
     }
   }
   __syncthreads();
-  if (tid == 0) a.tau_out[q] = fminf(ord2f(s_max), 3.402823466e+38f);
+  block_bitonic_sort(out, kpad);
+  if (tid == 0) a.tau_out[q] = fminf(ord2f((uint32_t)(out[a.k - 1] >> 32)), 3.402823466e+38f);
 }
 
 // ---------------------------------------------------------------------------------
 // Seeding with one wavefront per query (k <= 64, popcount inner products): the same
-// selection and refinement as seed_kernel, but the k smallest (est1, position) keys are
+// selection and refinement as seed_kernel, but the m <= 64 smallest (est1, position) keys are
 // kept in registers while the cluster streams by, so there is no LDS and no barrier.
 // ---------------------------------------------------------------------------------
 template <int W, int F>
@@ -165,6 +173,7 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   const int S = a.sum_qhat[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
   const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  const int m = max(a.k, SEED_M);  // <= 64
   WaveTopK top;
   // U tiles are requested together so that their load latencies overlap (tiles past the end
   // re-read the last tile and contribute no key)
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
       int I;
       const float e1 = est1_of<W>(cw[u], pl, fa[u], fr[u], G, hd, S, &I);
       const uint64_t key = real[u] ? make_key(e1, (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
-      if (tb + u == t0) top.init_sorted(key, lane); else top.push_tile(key, a.k, lane);
+      if (tb + u == t0) top.init_sorted(key, lane); else top.push_tile(key, m, lane);
     }
   }
   if (F == 0) {
@@ -195,28 +204,35 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
     if (lane == 0) a.tau_out[q] = ord2f((uint32_t)(kth >> 32));
     return;
   }
-  // refine the k seeds, GL lanes per seed
+  // refine the m seeds (fewer if the cluster is smaller), GL lanes per seed; lane i ends up with the
+  // refined key of seed i, and the k-th smallest of those is tau
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF, GL = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
   const int grp = lane / GL, t = lane % GL;
   const float csq = a.cB * a.sum_q[q];
-  uint32_t best = 0u;
-  for (int base = 0; base < a.k; base += NS) {
+  uint64_t rkey = KEY_NONE;
+  for (int base = 0; base < m; base += NS) {
     const int sidx = base + grp;
-    const uint32_t pos = (uint32_t)__shfl((int)(uint32_t)top.v, min(sidx, 63), 64);
+    const uint64_t skey = shfl_u64(top.v, min(sidx, 63));
+    const bool valid = sidx < m && skey != KEY_NONE;
     float part = 0.f;
     int64_t slot = 0;
-    if (sidx < a.k) {
-      slot = (int64_t)t0 * TILE + pos;
+    if (valid) {
+      slot = (int64_t)t0 * TILE + (uint32_t)skey;
       part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + q * a.D, t);
     }
     const float ip = group_sum<GL>(part);
-    if (sidx < a.k && t == 0) {
-      const float eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq);
-      best = max(best, f2ord(eB));
-    }
+    float eB = 0.f;
+    if (valid) eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq);
+    // seed base + g was refined by lanes g*GL ..; hand its estimate to lane base + g
+    const int g = (lane - base) & (NS - 1);
+    const float mine = __shfl(eB, g * GL, 64);
+    const bool mine_valid = __shfl((int)valid, g * GL, 64) != 0;
+    if (lane >= base && lane < base + NS && mine_valid) rkey = make_key(mine, (uint32_t)lane);
   }
-  best = wave_reduce_u32(best, [](uint32_t x, uint32_t y) { return x > y ? x : y; });
-  if (lane == 0) a.tau_out[q] = fminf(ord2f(best), 3.402823466e+38f);
+  WaveTopK fin;
+  fin.init_sorted(rkey, lane);
+  const uint64_t kth = readlane_u64(fin.v, a.k - 1);
+  if (lane == 0) a.tau_out[q] = fminf(ord2f((uint32_t)(kth >> 32)), 3.402823466e+38f);
 }
 
 // ---------------------------------------------------------------------------------
@@ -708,7 +724,7 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
 
 template <int W, int F>
 static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t st) {
-  const int kpad = next_pow2(a.k);
+  const int kpad = next_pow2(std::max(a.k, SEED_M));
   const size_t smem = (size_t)(SEED_CHUNK_TILES * TILE + 2 * kpad) * sizeof(uint64_t) + (size_t)a.D * sizeof(float);
   if (impl == 2)
     hipLaunchKernelGGL((seed_kernel<W, F, 1>), dim3((unsigned)nq), dim3(256), smem + (size_t)W * 256, st, a);

@@ -37,7 +37,8 @@ class _Desc(C.Structure):
     _fields_ = [("dim", C.c_int32), ("nlist", C.c_int32), ("n", C.c_int64), ("total_bits", C.c_int32),
                 ("metric", C.c_int32), ("rotation", C.c_void_p), ("centroids", C.c_void_p),
                 ("offsets", C.c_void_p), ("short_codes", C.c_void_p), ("short_factors", C.c_void_p),
-                ("long_codes", C.c_void_p), ("long_factors", C.c_void_p), ("ids", C.c_void_p)]
+                ("long_codes", C.c_void_p), ("long_factors", C.c_void_p), ("ids", C.c_void_p),
+                ("mean", C.c_void_p)]
 
 
 class _QueryRepr(C.Structure):
@@ -48,7 +49,7 @@ class _QueryRepr(C.Structure):
 class _BuildParams(C.Structure):
     _fields_ = [("dim", C.c_int32), ("nlist", C.c_int32), ("n", C.c_int64), ("total_bits", C.c_int32),
                 ("metric", C.c_int32), ("kmeans_iters", C.c_int32), ("train_size", C.c_int64),
-                ("epsilon0", C.c_float), ("rotation", C.c_void_p)]
+                ("epsilon0", C.c_float), ("rotation", C.c_void_p), ("center", C.c_int32)]
 
 
 _lib = None
@@ -68,7 +69,7 @@ def load_library() -> C.CDLL:
     lib.rabitq_last_error.argtypes = []
     lib.rabitq_index_upload.argtypes = [C.POINTER(_Desc), C.POINTER(vp), vp]
     lib.rabitq_index_build.argtypes = [C.POINTER(_BuildParams), vp, C.POINTER(vp), vp]
-    lib.rabitq_index_export.argtypes = [vp] * 9
+    lib.rabitq_index_export.argtypes = [vp] * 10
     lib.rabitq_index_free.argtypes = [vp]
     lib.rabitq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.rabitq_set_option.argtypes = [vp, C.c_char_p, i64]
@@ -116,7 +117,7 @@ class Index:
     rabitq_index_desc (see include/rabitq.h)."""
 
     def __init__(self, *, dim, nlist, n, total_bits, metric, rotation, centroids, offsets, short_codes,
-                 short_factors, ids, long_codes=None, long_factors=None):
+                 short_factors, ids, long_codes=None, long_factors=None, mean=None):
         lib = load_library()
         if not torch.cuda.is_available():
             raise RabitqError("no HIP device: the search path has no CPU fallback")
@@ -126,10 +127,13 @@ class Index:
         self._keep = dict(rotation=host(rotation, np.float32), centroids=host(centroids, np.float32),
                           offsets=host(offsets, np.int64), short_codes=host(short_codes, np.uint32),
                           short_factors=host(short_factors, np.float32), long_codes=host(long_codes, np.uint32),
-                          long_factors=host(long_factors, np.float32), ids=host(ids, np.int32))
+                          long_factors=host(long_factors, np.float32), ids=host(ids, np.int32),
+                          mean=host(mean, np.float32))
         k = self._keep
         if k["rotation"].size != dim * dim or k["centroids"].size != nlist * dim or k["offsets"].size != nlist + 1:
             raise RabitqError("rotation / centroids / offsets have the wrong size")
+        if k["mean"] is not None and k["mean"].size != dim:
+            raise RabitqError("mean must hold D elements")
         counts = np.diff(k["offsets"])
         n_tiles = int(((counts + TILE - 1) // TILE).sum())
         W = dim // 32
@@ -143,7 +147,7 @@ class Index:
         p = lambda a: None if a is None else a.ctypes.data
         desc = _Desc(dim, nlist, n, total_bits, {"l2": 0, "ip": 1}[metric], p(k["rotation"]), p(k["centroids"]),
                      p(k["offsets"]), p(k["short_codes"]), p(k["short_factors"]), p(k["long_codes"]),
-                     p(k["long_factors"]), p(k["ids"]))
+                     p(k["long_factors"]), p(k["ids"]), p(k["mean"]))
         h = C.c_void_p()
         _check(lib.rabitq_index_upload(C.byref(desc), C.byref(h), _stream()))
         self._h = h
@@ -153,16 +157,17 @@ class Index:
 
     @classmethod
     def build(cls, data: torch.Tensor, nlist: int, total_bits: int, rotation, metric: str = "l2",
-              kmeans_iters: int = 10, train_size: int = 0, epsilon0: float = 1.9) -> "Index":
+              kmeans_iters: int = 10, train_size: int = 0, epsilon0: float = 1.9, center: bool = False) -> "Index":
         """rabitq_index_build: builds the index on the device from raw vectors `data` [n, D]
-        (CUDA fp32) and a host rotation matrix [D, D]."""
+        (CUDA fp32) and a host rotation matrix [D, D]; `center` builds on the vectors minus
+        their mean (L2 only)."""
         lib = load_library()
         n, dim = data.shape
         rot = np.ascontiguousarray(rotation, dtype=np.float32)
         if rot.shape != (dim, dim):
             raise RabitqError("rotation must be [D, D]")
         prm = _BuildParams(dim, nlist, n, total_bits, {"l2": 0, "ip": 1}[metric], kmeans_iters, train_size, epsilon0,
-                           rot.ctypes.data)
+                           rot.ctypes.data, int(bool(center)))
         h = C.c_void_p()
         _check(lib.rabitq_index_build(C.byref(prm), _dev(data, torch.float32), C.byref(h), _stream()))
         self = cls.__new__(cls)
@@ -179,14 +184,14 @@ class Index:
                    rotation=np.empty((D, D), np.float32), centroids=np.empty((nlist, D), np.float32),
                    offsets=np.empty(nlist + 1, np.int64), short_codes=np.empty(tiles * W * TILE, np.uint32),
                    short_factors=np.empty(tiles * 3 * TILE, np.float32), ids=np.empty(slots, np.int32),
-                   long_codes=None, long_factors=None)
+                   long_codes=None, long_factors=None, mean=np.empty(D, np.float32))
         if self.total_bits > 1:
             out["long_codes"] = np.empty(slots * D * F // 32, np.uint32)
             out["long_factors"] = np.empty(slots * 2, np.float32)
         p = lambda a: None if a is None else a.ctypes.data
         _check(lib.rabitq_index_export(self._h, p(out["rotation"]), p(out["centroids"]), p(out["offsets"]),
                                        p(out["short_codes"]), p(out["short_factors"]), p(out["long_codes"]),
-                                       p(out["long_factors"]), p(out["ids"])))
+                                       p(out["long_factors"]), p(out["ids"]), p(out["mean"])))
         return out
 
     def close(self):
@@ -328,4 +333,4 @@ def index_from_arrays(meta: dict, dev: dict) -> Index:
     return Index(dim=meta["dim"], nlist=meta["nlist"], n=meta["n"], total_bits=meta["total_bits"],
                  metric=meta["metric"], rotation=meta["P"], centroids=meta["centroids_rot"], offsets=meta["offsets"],
                  short_codes=dev["short_codes"], short_factors=dev["short_factors"], ids=dev["ids"],
-                 long_codes=dev["long_codes"], long_factors=dev["long_factors"])
+                 long_codes=dev["long_codes"], long_factors=dev["long_factors"], mean=meta.get("mean"))

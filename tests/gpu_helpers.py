@@ -15,7 +15,7 @@ def upload(ix: dict) -> rabitq.Index:
 def oracle_stages(s: search.Searcher, Q: np.ndarray, k: int, nprobe: int) -> dict:
     """Every intermediate of the search as the oracle computes it (numpy)."""
     ix = s.ix
-    Qr = search.rotate_queries(Q, ix["P"])
+    Qr = search.rotate_queries(Q, ix["P"], ix.get("mean"))
     nq, D = Qr.shape
     W = D // 32
     planes = np.empty((nq, 4, W), np.uint32)

@@ -35,6 +35,40 @@ def test_device_builder_against_oracle_formulas(wl, n, nlist, B, metric):
     gi.close(); gi2.close()
 
 
+def test_centred_device_build():
+    # center = 1: the builder works on the vectors minus their mean and the search subtracts it from
+    # the queries; every check of the plain build must hold for the translated vectors
+    w = synth.WORKLOADS["l2_128"].scaled(n=20_000, nq=100, n_centres=32)
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    P = build.random_rotation(w.dim, 7)
+    gi = rabitq.Index.build(torch.from_numpy(X).cuda(), 40, 4, P, kmeans_iters=4, train_size=10_000, center=True)
+    out = gi.export()
+    mean = X.mean(0, dtype=np.float64)
+    assert np.allclose(out["mean"], mean, rtol=1e-6, atol=1e-6)
+    check_built_index(out, (X.astype(np.float64) - out["mean"].astype(np.float64)).astype(np.float32), 4)
+    # rotated queries are (q - mean) P
+    qr = gi.rotate(torch.from_numpy(Q).cuda()).cpu().numpy()
+    want = search.rotate_queries(Q, P, out["mean"])
+    assert np.max(np.abs(qr - want)) < 2e-6 * np.abs(Q).sum(1).max()
+    # distances refer to the original vectors; recall is that of an oracle-built centred index
+    ids, d = gi.search(torch.from_numpy(Q).cuda(), 10, 8)
+    gt, gd = exact.exact_knn(X, Q, 10)
+    ix = build.build_index(X, 40, 4, kmeans_iters=4, center=True)
+    o_ids, _, _ = search.Searcher(ix).search(Q, 10, 8)
+    assert exact.recall_at_k(ids.cpu().numpy(), gt) > exact.recall_at_k(o_ids, gt) - 0.03
+    assert np.median(np.abs(d.cpu().numpy()[:, 0] - gd[:, 0]) / gd[:, 0]) < 0.1
+    # export -> upload round trip keeps the translation
+    gj = rabitq.Index(**out)
+    ids2, d2 = gj.search(torch.from_numpy(Q).cuda(), 10, 8)
+    # (the upload recomputes the centroid norms on the host; the coarse term is a difference of large squares)
+    atol = 2e-6 * float(((Q - out["mean"]).astype(np.float64) ** 2).sum(1).max())
+    assert torch.equal(ids, ids2) and torch.allclose(d, d2, rtol=1e-5, atol=atol)
+    # an inner-product index cannot be centred
+    with pytest.raises(rabitq.RabitqError):
+        rabitq.Index.build(torch.from_numpy(X).cuda(), 40, 4, P, metric="ip", center=True)
+    gi.close(); gj.close()
+
+
 def test_device_built_index_searches_like_an_oracle_built_one():
     w = synth.WORKLOADS["l2_128"].scaled(n=40_000, nq=200, n_centres=64)
     X, Q = synth.make_base(w), synth.make_queries(w)

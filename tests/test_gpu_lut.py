@@ -12,7 +12,7 @@ from test_gpu_parity import case
 
 pytestmark = pytest.mark.gpu
 
-NAMES = ["tiny_b1", "l2_128_b4", "l2_96_b3_k100", "l2_960_b5", "ragged_b2"]
+NAMES = ["tiny_b1", "l2_128_b4", "l2_96_b3_k100", "l2_960_b5", "ragged_b2", "centred_b4"]
 _lut = {}
 
 

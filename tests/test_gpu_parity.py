@@ -18,6 +18,7 @@ CASES = {
     "l2_96_b3_k100": ("l2_96", 20_000, 64, 64, 40, 3, 100, 8),   # config 4 shape (W = 3, K = 100)
     "l2_960_b5": ("l2_960", 4_000, 24, 16, 12, 5, 10, 4),        # config 3 shape (W = 30)
     "ragged_b2": ("tiny", 1_500, 40, 50, 50, 2, 10, 50),          # many small / empty lists, nprobe = nlist
+    "centred_b4": ("l2_128", 20_000, 64, 64, 32, 4, 10, 6),      # index built on the vectors minus their mean
 }
 _cache = {}
 
@@ -27,7 +28,7 @@ def case(name):
         wl, n, nq, nc, nlist, B, k, nprobe = CASES[name]
         w = synth.WORKLOADS[wl].scaled(n=n, nq=nq, n_centres=nc)
         X, Q = synth.make_base(w), synth.make_queries(w)
-        ix = build.build_index(X, nlist, B, metric=w.metric, kmeans_iters=4)
+        ix = build.build_index(X, nlist, B, metric=w.metric, kmeans_iters=4, center=name.startswith("centred"))
         s = search.Searcher(ix)
         st = oracle_stages(s, Q, k, nprobe)
         _cache[name] = dict(X=X, Q=Q, ix=ix, s=s, st=st, gi=upload(ix), k=k, nprobe=nprobe, dev=to_dev(st))

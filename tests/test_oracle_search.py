@@ -198,3 +198,30 @@ def test_seeded_threshold_one_bit_and_small_clusters():
             hit += 1
             assert tau == np.sort(s.refined(a, b, G[i, j], Qr[i]))[K - 1]
     assert hit > 0
+
+
+def test_centred_index_is_a_pure_translation():
+    # a common translation leaves squared distances alone: the centred index must rank like the
+    # plain one up to estimation noise, report distances of the original vectors, and its rotated
+    # queries must have lost the shared offset
+    w = synth.WORKLOADS["l2_128"].scaled(n=4000, nq=30, n_centres=16)
+    X, Q = synth.make_base(w), synth.make_queries(w)
+    plain = build.build_index(X, 16, 8)
+    cent = build.build_index(X, 16, 8, center=True)
+    assert not plain["mean"].any()
+    assert np.allclose(cent["mean"], X.mean(0), rtol=1e-6)
+    # the stored centroids are those of the translated data
+    assert np.abs(cent["centroids"].mean(0)).max() < np.abs(plain["centroids"].mean(0)).max() * 0.2
+    gt, gd = exact.exact_knn(X, Q, 10)
+    for ix in (plain, cent):
+        ids, d, _ = search.Searcher(ix).search(Q, 10, 16, prune=False)
+        assert exact.recall_at_k(ids, gt) >= 0.97
+        assert np.median(np.abs(d[:, 0] - gd[:, 0]) / gd[:, 0]) < 0.01   # distances to the ORIGINAL vectors
+    qp = search.rotate_queries(Q, plain["P"], plain["mean"])
+    qc = search.rotate_queries(Q, cent["P"], cent["mean"])
+    assert np.allclose(qc, qp - (cent["mean"].astype(np.float64) @ cent["P"].astype(np.float64)), atol=2e-3)
+    dp = np.mean([search.quantize_query(q)[0] for q in qp])
+    dc = np.mean([search.quantize_query(q)[0] for q in qc])
+    assert dc < 0.8 * dp                                                 # finer 4-bit query grid
+    with pytest.raises(AssertionError):
+        build.build_index(X, 16, 4, metric="ip", center=True)
