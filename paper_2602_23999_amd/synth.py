@@ -52,6 +52,9 @@ WORKLOADS = {
     "l2_96": Workload("l2_96", 10_000_000, 96, 16384, 16384, 3, 10_000, 100, (32, 64, 128, 256, 512)),
     # 768-d unit-norm text embeddings, maximum inner product.
     "ip_768": Workload("ip_768", 5_000_000, 768, 4096, 8192, 8, 10_000, 10, (64,), metric="ip"),
+    # The same with concentrated clusters (noise norm 0.15, cos(x, centre) ~ 0.99): the literal recipe above is so
+    # diffuse (cos ~ 0.25) that no list structure helps; this variant is the one with a meaningful recall.
+    "ip_768_tight": Workload("ip_768_tight", 5_000_000, 768, 4096, 8192, 8, 10_000, 10, (64,), metric="ip"),
 }
 
 
@@ -74,7 +77,7 @@ def _centres(w: Workload) -> np.ndarray:
         return modes[which] + np.einsum("nk,nkd->nd", z, basis[which])
     if w.name == "l2_960":
         return r.standard_normal((w.n_centres, D))
-    if w.name in ("l2_96", "ip_768"):
+    if w.name in ("l2_96", "ip_768", "ip_768_tight"):
         c = r.standard_normal((w.n_centres, D))
         return c / np.linalg.norm(c, axis=1, keepdims=True)
     raise KeyError(w.name)
@@ -123,6 +126,9 @@ def _draw(w: Workload, centres: np.ndarray, n: int, seed: int, stream: int, chun
             x /= np.linalg.norm(x, axis=1, keepdims=True)
         elif w.name == "ip_768":
             x = centres[comp] + g / np.sqrt(50.0)  # tangent variance 1/kappa, kappa = 50
+            x /= np.linalg.norm(x, axis=1, keepdims=True)
+        elif w.name == "ip_768_tight":
+            x = centres[comp] + (0.15 / np.sqrt(D)) * g
             x /= np.linalg.norm(x, axis=1, keepdims=True)
         else:
             raise KeyError(w.name)
