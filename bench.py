@@ -169,6 +169,45 @@ def stream_scan(args):
     gi.close()
 
 
+def batch_sweep(args, gi, Qd, w, nprobe):
+    """Latency of one synchronised rabitq_search by batch size (the paper's batch-size experiment, Section 4.2.2),
+    launched eagerly and as a replay of a HIP graph holding the same search."""
+    import torch
+    rows = []
+    for nq in (1, 10, 100, 1000, 10000):
+        if nq > Qd.shape[0]:
+            continue
+        q = Qd[:nq].contiguous()
+        oi = torch.empty((nq, w.k), dtype=torch.int64, device="cuda")
+        od = torch.empty((nq, w.k), dtype=torch.float32, device="cuda")
+        for _ in range(5):
+            gi.search(q, w.k, nprobe, oi, od)
+        torch.cuda.synchronize()
+
+        def timed(call, reps=50):
+            ts = []
+            for _ in range(reps):
+                t = time.perf_counter()
+                call()
+                torch.cuda.synchronize()
+                ts.append(time.perf_counter() - t)
+            return float(np.median(ts)) * 1e3
+        eager_ms = timed(lambda: gi.search(q, w.k, nprobe, oi, od))
+        ref = oi.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            gi.search(q, w.k, nprobe, oi, od)
+        oi.fill_(-7)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(oi, ref), "graph replay differs from the eager search"
+        graph_ms = timed(g.replay)
+        rows.append(dict(nq=nq, eager_ms=round(eager_ms, 4), graph_ms=round(graph_ms, 4),
+                         qps=round(nq / min(eager_ms, graph_ms) * 1e3)))
+        log(f"[bench] batch {nq}: eager {eager_ms:.4f} ms, graph replay {graph_ms:.4f} ms")
+    return rows
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +222,9 @@ def main():
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
                          "kernel that scales rocprofv3's FETCH_SIZE / WRITE_SIZE readings")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time one synchronised search at batch sizes 1..10^4, eager and as a HIP-graph replay "
+                         "(adds config.batch_sweep)")
     ap.add_argument("--stream-scan", action="store_true",
                     help="measure the code scan in the streaming regime instead (index far larger than the caches, "
                          "one query per list); prints its own JSON line")
@@ -253,13 +295,18 @@ def main():
     op = ok[0]
     nprobe = op["nprobe"]
 
+    # timed region: only the scan kernel's two events are recorded (every recorded stage costs two event records
+    # per search); the other stages are timed in a separate short pass afterwards
+    gi.set_option("profile_stages", 1 << 7)
     sec = timed(nprobe, args.steps, args.warmup, profile=True)
+    scan_ms = gi.stage_ms()[0]["scan"]
+    gi.set_option("profile_stages", 0x1ff)
+    timed(nprobe, min(args.steps, 20), 0, profile=True)
     stage_ms, calls = gi.stage_ms()
     gi.set_option("profile", 0)
     r_op = recall(out_ids, gt)
     qps = w.nq / sec
     alg_bytes, qv = scan_algorithmic_bytes(gi, Qd, nprobe, cluster_sizes, w.dim)
-    scan_ms = stage_ms["scan"]
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
     traffic = None
     # measured fabric traffic per launch (bytes), from the rocprofv3 --pmc summaries under profiles/
@@ -291,11 +338,15 @@ def main():
                                f"nq={w.nq} k={w.k} nprobe={nprobe}",
                    "recall_at_k": round(r_op, 4), "recall_target": 0.95, "nprobe_sweep": sweep,
                    "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "stage_ms_calls": calls,
+                   "stage_ms_note": "separate pass with every stage's events recorded; list_build and scan_setup run on a "
+                                    "second stream beside seed, so the stages add up to more than ms_per_step",
                    "query_vector_evaluations": qv, "index_builder": "rabitq_index_build (HIP: k-means + two-phase grid search"
                                     + (", vectors centred on their mean)" if w.metric == "l2" else ")"),
                    "index_build_s": round(build_s, 4)},
         "roofline": roofline,
     }
+    if args.batch_sweep:
+        res["config"]["batch_sweep"] = batch_sweep(args, gi, Qd, w, nprobe)
     if not args.no_cpu_baseline:
         t0 = time.perf_counter()
         res["cpu_baseline"] = cpu_baseline(w, nprobe)

@@ -149,6 +149,11 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *   "prune"   1 (default): filter with the per-query seeded threshold (Section 3.3.4);
  *             0: refine every vector of every probed cluster (the unpruned definition).
  *   "profile" n: see rabitq_stage_ms.
+ *   "profile_stages" m: bit s of m (1..511, default all) selects whether stage s of rabitq_stage_ms is
+ *             recorded; unrecorded stages report 0.  Recording costs two event records per stage and search.
+ *   "overlap" 1 (default): inside a search the pair lists and the scan's work-item table are built on a second
+ *             stream owned by the handle (default priority), beside the threshold seeding; the scan kernel waits
+ *             for both and everything joins the caller's stream again before the call returns to it.  0: one stream.
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per
  *             wavefront; 1: the same integer inner products on the matrix cores (the sign
  *             bits of a tile are expanded to int8 once and contracted against 16 queries'
@@ -171,7 +176,8 @@ int64_t rabitq_index_info(rabitq_index_t index, const char* name);
  * last recorded search and returns the MEAN duration in milliseconds of each stage over
  * the recorded searches.
  *   out_ms: host, [9]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
- *           scan set-up (work-item offsets), scan kernel, merge
+ *           scan set-up (work-item offsets), scan kernel, merge; each is the time between two events on the
+ *           stream the stage ran on, so with "overlap" their sum exceeds the duration of the search
  *   out_calls: host, number of searches the means were taken over (may be NULL)
  * Errors: RABITQ_EINVAL (null pointer, nothing recorded), RABITQ_EHIP. */
 int rabitq_stage_ms(rabitq_index_t index, float* out_ms, int32_t* out_calls);

@@ -58,9 +58,15 @@ static void free_index(rabitq_index* ix) {
   dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
   dev_free(ix->long_factors); dev_free(ix->ids);
   free_workspace(ix->ws);
-  for (auto& set : ix->prof_sets)
-    for (auto& e : set.ev)
+  for (auto& set : ix->prof_sets) {
+    for (auto& e : set.b)
       if (e) (void)hipEventDestroy(e);
+    for (auto& e : set.e)
+      if (e) (void)hipEventDestroy(e);
+  }
+  if (ix->ev_fork) (void)hipEventDestroy(ix->ev_fork);
+  if (ix->ev_join) (void)hipEventDestroy(ix->ev_join);
+  if (ix->side) (void)hipStreamDestroy(ix->side);
   delete ix;
 }
 
@@ -109,6 +115,14 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   return RABITQ_OK;
 }
 
+
+// second stream (default priority) and fork / join events of a handle; called once when the handle is made
+static int init_streams(rabitq_index* ix) {
+  RQ_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
+  RQ_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
+  RQ_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
+  return RABITQ_OK;
+}
 
 int set_index_mean(rabitq_index* ix, const float* mean, const float* rotation_host, hipStream_t st) {
   const int D = ix->dim;
@@ -220,6 +234,7 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
     (void)hipStreamSynchronize(st);
   }
   if (rc == RABITQ_OK && d->mean) rc = set_index_mean(ix, d->mean, d->rotation, st);
+  if (rc == RABITQ_OK) rc = init_streams(ix);
   if (rc != RABITQ_OK) { free_index(ix); return rc; }
   *out = ix;
   return RABITQ_OK;
@@ -244,6 +259,7 @@ int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_i
   if (rc == RABITQ_OK)
     rc = build_index_device(ix, data, p->rotation, p->kmeans_iters, p->train_size, p->epsilon0, p->center,
                             (hipStream_t)stream);
+  if (rc == RABITQ_OK) rc = init_streams(ix);
   if (rc != RABITQ_OK) {
     (void)hipDeviceSynchronize();
     free_index(ix);
@@ -295,14 +311,23 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 2) { ix->scan_impl = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
+    ix->prof_mask = (unsigned)value;
+    ix->prof_used = 0;
+    return RABITQ_OK;
+  }
   if (!std::strcmp(name, "profile") && value >= 0 && value <= 4096) {
     const size_t have = ix->prof_sets.size();
     if ((size_t)value > have) {
       ix->prof_sets.resize((size_t)value);
       for (size_t i = have; i < (size_t)value; ++i)
-        for (auto& e : ix->prof_sets[i].ev) e = nullptr;
+        for (int s2 = 0; s2 < rabitq_index::N_STAGES; ++s2) ix->prof_sets[i].b[s2] = ix->prof_sets[i].e[s2] = nullptr;
       for (size_t i = have; i < (size_t)value; ++i)
-        for (auto& e : ix->prof_sets[i].ev) RQ_HIP(hipEventCreate(&e));
+        for (int s2 = 0; s2 < rabitq_index::N_STAGES; ++s2) {
+          RQ_HIP(hipEventCreate(&ix->prof_sets[i].b[s2]));
+          RQ_HIP(hipEventCreate(&ix->prof_sets[i].e[s2]));
+        }
     }
     ix->prof_used = 0;
     ix->prof_limit = (int)value;
@@ -330,12 +355,13 @@ int rabitq_stage_ms(rabitq_index_t ix, float* out_ms, int32_t* out_calls) {
   if (!ix || !out_ms) { set_error("stage_ms: null argument"); return RABITQ_EINVAL; }
   const int n = ix->prof_used;
   if (n <= 0) { set_error("stage_ms: no search was recorded (set the option \"profile\" first)"); return RABITQ_EINVAL; }
-  RQ_HIP(hipEventSynchronize(ix->prof_sets[n - 1].ev[rabitq_index::N_STAGES]));
   double acc[rabitq_index::N_STAGES] = {0};
-  for (int i = 0; i < n; ++i) {
-    for (int s = 0; s < rabitq_index::N_STAGES; ++s) {
+  for (int s = 0; s < rabitq_index::N_STAGES; ++s) {
+    if (!((ix->prof_mask >> s) & 1u)) continue;  // not recorded: reported as 0
+    RQ_HIP(hipEventSynchronize(ix->prof_sets[n - 1].e[s]));
+    for (int i = 0; i < n; ++i) {
       float ms = 0.f;
-      RQ_HIP(hipEventElapsedTime(&ms, ix->prof_sets[i].ev[s], ix->prof_sets[i].ev[s + 1]));
+      RQ_HIP(hipEventElapsedTime(&ms, ix->prof_sets[i].b[s], ix->prof_sets[i].e[s]));
       acc[s] += ms;
     }
   }
@@ -443,8 +469,10 @@ int rabitq_scan(rabitq_index_t ix, const rabitq_query_repr* repr, const float* p
     set_error("scan: null pointer"); return RABITQ_EINVAL;
   }
   if (nq * nprobe > 0x7fffffff) { set_error("scan: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
+  ScanStreams ss;
+  ss.main = ss.setup = (hipStream_t)stream;
   return launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
-                     dbg_off, (hipStream_t)stream);
+                     dbg_off, ss);
 }
 
 int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int32_t k,
@@ -468,39 +496,47 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
   Workspace& w = ix->ws;
   hipStream_t st = (hipStream_t)stream;
-  hipEvent_t* ev = nullptr;  // event set of this call when it is being recorded
-  if (ix->prof_used < ix->prof_limit) ev = ix->prof_sets[ix->prof_used++].ev;
-  int stage = 0;
-#define RQ_MARK() do { if (ev) RQ_HIP(hipEventRecord(ev[stage++], st)); } while (0)
-#define RQ_RUN(call) do { if ((rc = (call)) != RABITQ_OK) return rc; } while (0)
-  RQ_MARK();
-  RQ_RUN(launch_rotate(ix, queries, w.q_rot, nq, st));
-  RQ_MARK();
+  rabitq_index::EventSet* ev = nullptr;  // event set of this call when it is being recorded
+  if (ix->prof_used < ix->prof_limit) ev = &ix->prof_sets[ix->prof_used++];
+  // stage s runs between its begin and end events, both recorded on the stream the stage is put on
+#define RQ_STAGE(s, stream_, call)                                              \
+  do {                                                                          \
+    const bool on_ = ev && ((ix->prof_mask >> (s)) & 1u);                       \
+    if (on_) RQ_HIP(hipEventRecord(ev->b[s], (stream_)));                       \
+    if ((rc = (call)) != RABITQ_OK) return rc;                                  \
+    if (on_) RQ_HIP(hipEventRecord(ev->e[s], (stream_)));                       \
+  } while (0)
+  RQ_STAGE(0, st, launch_rotate(ix, queries, w.q_rot, nq, st));
   rabitq_query_repr repr = w.repr;
   if (ix->scan_impl != 2) repr.lut = nullptr;  // tables are only built for the scan that reads them
-  RQ_RUN(launch_query_prep(w.q_rot, nq, ix->dim, ix->F, repr, st));
-  RQ_MARK();
-  RQ_RUN(launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
-                     w.repr.sq_norm, ix->centroid_sq, st));
-  RQ_MARK();
-  RQ_RUN(launch_select_probes(w.scores, w.repr.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric, w.probe_ids,
-                              w.probe_G, w.probe_E, st));
-  RQ_MARK();
-  RQ_RUN(launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, st));
-  RQ_MARK();
-  if (ix->prune) {
-    RQ_RUN(launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
-  } else {
-    RQ_RUN(launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));
+  RQ_STAGE(1, st, launch_query_prep(w.q_rot, nq, ix->dim, ix->F, repr, st));
+  RQ_STAGE(2, st, launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
+                              w.repr.sq_norm, ix->centroid_sq, st));
+  RQ_STAGE(3, st, launch_select_probes(w.scores, w.repr.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric,
+                                       w.probe_ids, w.probe_G, w.probe_E, st));
+  // The pair lists and the scan's work-item table depend on the probes only, and so does the threshold seeding:
+  // the former run on the handle's second stream beside the latter, and the scan kernel waits for both.
+  hipStream_t lst = st;
+  if (ix->overlap) {
+    lst = ix->side;
+    RQ_HIP(hipEventRecord(ix->ev_fork, st));
+    RQ_HIP(hipStreamWaitEvent(lst, ix->ev_fork, 0));
   }
-  RQ_MARK();
-  RQ_RUN(launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids,
-                     w.tau, nq, k, nprobe, w.cand_keys, w.cand_cnt, nullptr, nullptr, st, ev ? ev[stage++] : nullptr));
-  RQ_MARK();
-  RQ_RUN(launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
-  RQ_MARK();
-#undef RQ_MARK
-#undef RQ_RUN
+  RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst));
+  if (ix->prune) {
+    RQ_STAGE(5, st, launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
+  } else {
+    RQ_STAGE(5, st, launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));
+  }
+  ScanStreams ss;
+  ss.main = st; ss.setup = lst; ss.join = ix->ev_join;
+  if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; }
+  if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; }
+  if ((rc = launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids, w.tau, nq, k, nprobe, w.cand_keys,
+                        w.cand_cnt, nullptr, nullptr, ss)) != RABITQ_OK)
+    return rc;
+  RQ_STAGE(8, st, launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
+#undef RQ_STAGE
   return RABITQ_OK;
 }
 

@@ -66,10 +66,15 @@ struct rabitq_index {
   // options
   int prune = 1;
   int scan_impl = 0;
+  int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
+  // second stream of a search (default priority) and the events that fork it from and join it to the caller's
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   static constexpr int N_STAGES = 9;
-  struct EventSet { hipEvent_t ev[N_STAGES + 1]; };
+  struct EventSet { hipEvent_t b[N_STAGES], e[N_STAGES]; };  // begin / end of every stage, on the stream it ran on
   std::vector<EventSet> prof_sets;  // one per recorded search
   int prof_used = 0, prof_limit = 0;
+  unsigned prof_mask = 0x1ffu;  // stages whose events are recorded (bit s = stage s)
   rq::Workspace ws;
 };
 
@@ -108,10 +113,17 @@ int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nli
                        int32_t* pair_ids, uint32_t* scratch, hipStream_t st);
 int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st);
+// Streams and events of one scan launch: the set-up kernels (work-item offsets, counter clearing) run on `setup`
+// and the scan kernel on `main`; when the two differ, `join` is recorded on `setup` and awaited on `main`.  The
+// four profiling events may be null.
+struct ScanStreams {
+  hipStream_t main = nullptr, setup = nullptr;
+  hipEvent_t join = nullptr;
+  hipEvent_t setup_b = nullptr, setup_e = nullptr, scan_b = nullptr, scan_e = nullptr;
+};
 int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
-                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
-                hipEvent_t after_setup = nullptr);
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, const ScanStreams& ss);
 int launch_merge(const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int k, int nprobe, int metric,
                  int64_t* out_ids, float* out_dists, hipStream_t st);
 int launch_fill_f32(float* p, int64_t n, float v, hipStream_t st);

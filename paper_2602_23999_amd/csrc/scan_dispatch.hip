@@ -112,9 +112,9 @@ int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int
 
 int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
-                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, hipStream_t st,
-                hipEvent_t after_setup) {
+                uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, const ScanStreams& ss) {
   if (nq <= 0) return RABITQ_OK;
+  const hipStream_t st = ss.main, sst = ss.setup;
   if (int rc = need_lut(ix, repr)) return rc;
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
@@ -143,11 +143,17 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     a.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
   }
   a.segmax = std::max(1, a.cand_stride / k);
-  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, st, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
+  if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
+  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
                      a.segmax, item_off);
-  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nq * nprobe + 255) / 256, 4096)), dim3(256), 0, st,
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nq * nprobe + 255) / 256, 4096)), dim3(256), 0, sst,
                      cand_cnt, nq * nprobe);
-  if (after_setup) RQ_HIP(hipEventRecord(after_setup, st));
+  if (ss.setup_e) RQ_HIP(hipEventRecord(ss.setup_e, sst));
+  if (sst != st) {
+    RQ_HIP(hipEventRecord(ss.join, sst));
+    RQ_HIP(hipStreamWaitEvent(st, ss.join, 0));
+  }
+  if (ss.scan_b) RQ_HIP(hipEventRecord(ss.scan_b, st));
   // Grid bound.  Cluster c with cnt_c pairs and nseg_c segments has ceil(cnt_c / qw) * nseg_c work items, at most
   // (cnt_c / qw + 1) * nseg_c.  Every query probes nprobe distinct clusters, so cnt_c <= nq and sum cnt_c = nq * nprobe:
   // the sum is largest when the nprobe clusters with the most segments are probed by every query.  The kernel
@@ -178,6 +184,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
         scan_part2(a, W, F, impl, grid, dbg, st)))
     return bad_width();
   RQ_HIP(hipGetLastError());
+  if (ss.scan_e) RQ_HIP(hipEventRecord(ss.scan_e, st));
   return RABITQ_OK;
 }
 
