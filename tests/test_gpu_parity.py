@@ -19,6 +19,7 @@ CASES = {
     "l2_960_b5": ("l2_960", 4_000, 24, 16, 12, 5, 10, 4),        # config 3 shape (W = 30)
     "ragged_b2": ("tiny", 1_500, 40, 50, 50, 2, 10, 50),          # many small / empty lists, nprobe = nlist
     "centred_b4": ("l2_128", 20_000, 64, 64, 32, 4, 10, 6),      # index built on the vectors minus their mean
+    "many_probes_b2": ("tiny", 12_000, 48, 64, 160, 2, 10, 100),  # nprobe > 64: workgroup-wide probe selection
 }
 _cache = {}
 
