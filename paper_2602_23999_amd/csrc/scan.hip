@@ -7,13 +7,13 @@
 namespace rq {
 
 // 1-bit estimate of one lane's vector for one query (Section 3.4.1(2) + factors):
-// est1 = G + f_add + f_rescale * delta * (2I - S)/2.
+// est1 = G + f_add + f_rescale * (delta * I - delta * S / 2).
 template <int W>
-__device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float fa, float fr, float G, float hd,
-                                int S, int* I_out) {
+__device__ inline float est1_of(const uint32_t (&cw)[W], const_u32_ptr pl, float fa, float fr, float G, float dl,
+                                float be, int* I_out) {
   const int I = ip_bitplanes<W>(cw, pl);
   *I_out = I;
-  return G + fa + fr * (hd * (float)(2 * I - S));
+  return G + fa + fr * fmaf(dl, (float)I, -be);  // dl = delta, be = delta * S / 2 (one fused step per vector)
 }
 
 // Lookup-table variant (Section 3.4.1(1), U = 4): <x_b, q'> as the fp32 sum, in ascending
@@ -89,8 +89,8 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   const int64_t p = q * a.nprobe + rank;
   const int c = a.probe_ids[p];
   const float G = a.probe_G[p];
-  const float hd = 0.5f * a.delta[q];
-  const int S = a.sum_qhat[q];
+  const float dl = a.delta[q];
+  const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const float hsq = 0.5f * a.sum_q[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
   const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
       const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
       const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
       int I;
-      const float e1 = (M == 1) ? G + fa + fr * (ip_lut_of<W>(cw, lut_s) - hsq) : est1_of<W>(cw, pl, fa, fr, G, hd, S, &I);
+      const float e1 = (M == 1) ? G + fa + fr * (ip_lut_of<W>(cw, lut_s) - hsq) : est1_of<W>(cw, pl, fa, fr, G, dl, be, &I);
       const bool real = a.ids[(int64_t)tile * TILE + lane] >= 0;
       chunk[tl * TILE + lane] = real ? make_key(e1, (uint32_t)((tile - t0) * TILE + lane)) : KEY_NONE;
     }
@@ -169,8 +169,8 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   const int64_t p = q * a.nprobe + rank;
   const int c = a.probe_ids[p];
   const float G = a.probe_G[p];
-  const float hd = 0.5f * a.delta[q];
-  const int S = a.sum_qhat[q];
+  const float dl = a.delta[q];
+  const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
   const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
   const int m = max(a.k, SEED_M);  // <= 64
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       int I;
-      const float e1 = est1_of<W>(cw[u], pl, fa[u], fr[u], G, hd, S, &I);
+      const float e1 = est1_of<W>(cw[u], pl, fa[u], fr[u], G, dl, be, &I);
       const uint64_t key = real[u] ? make_key(e1, (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
       if (tb + u == t0) top.init_sorted(key, lane); else top.push_tile(key, m, lane);
     }
@@ -295,7 +295,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int np = min(QW, a.pair_off[c + 1] - pbeg);
 
   int pj[QW], Sj[QW], cnt[QW];
-  float Gj[QW], Ej[QW], hdj[QW], tauj[QW], hsqj[QW];
+  float Gj[QW], Ej[QW], dlj[QW], bej[QW], tauj[QW], hsqj[QW];
   int64_t qj[QW];
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
@@ -305,8 +305,9 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     qj[j] = q;
     Gj[j] = a.probe_G[pp];
     Ej[j] = a.probe_E[pp];
-    hdj[j] = 0.5f * a.delta[q];
+    dlj[j] = a.delta[q];
     Sj[j] = a.sum_qhat[q];
+    bej[j] = 0.5f * dlj[j] * (float)Sj[j];
     hsqj[j] = 0.5f * a.sum_q[q];
     if (M == 1) stage_lut(lut_s + j * W * 128, a.lut + q * (int64_t)W * 128, W, lane, 64);
     tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
@@ -386,7 +387,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
         I = __float_as_int(ipf);
         e1 = Gj[j] + fa + fr * (ipf - hsqj[j]);
       } else {
-        e1 = est1_of<W>(cw, pl, fa, fr, Gj[j], hdj[j], Sj[j], &I);
+        e1 = est1_of<W>(cw, pl, fa, fr, Gj[j], dlj[j], bej[j], &I);
       }
       if (DBG) {
         if (j < np) a.dbg_ip[a.dbg_off[pbeg + j] + (int64_t)(tile - t0) * TILE + lane] = I;
