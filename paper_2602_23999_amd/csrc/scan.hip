@@ -178,7 +178,8 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   // U tiles are requested together so that their load latencies overlap (tiles past the end
   // re-read the last tile and contribute no key)
   constexpr int U = (W <= 4) ? 4 : (W <= 8 ? 2 : 1);
-  for (int tb = t0; tb < t1; tb += U) {
+  // est1 of U tiles starting at tb, as order-preserving words (all ones where there is no vector)
+  auto estimate = [&](int tb, uint32_t (&ord)[U]) {
     uint32_t cw[U][W];
     float fa[U], fr[U];
     bool real[U];
@@ -195,8 +196,40 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
     for (int u = 0; u < U; ++u) {
       int I;
       const float e1 = est1_of<W>(cw[u], pl, fa[u], fr[u], G, dl, be, &I);
-      const uint64_t key = real[u] ? make_key(e1, (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
-      if (tb + u == t0) top.init_sorted(key, lane); else top.push_tile(key, m, lane);
+      ord[u] = real[u] ? f2ord(e1) : 0xffffffffu;
+    }
+  };
+  // The first R tiles are estimated before anything is selected: the 64 per-lane minima (distinct vectors) start
+  // the sorted list, so its m-th key is small from the outset and few of the remaining keys have to be inserted.
+  constexpr int R = (W <= 4) ? 16 : (W <= 8 ? 8 : 4);
+  {
+    uint32_t ord[R];
+#pragma unroll
+    for (int c = 0; c < R; c += U) {
+      uint32_t o[U];
+      estimate(t0 + c, o);
+#pragma unroll
+      for (int u = 0; u < U; ++u) ord[c + u] = (t0 + c + u < t1) ? o[u] : 0xffffffffu;
+    }
+    uint32_t mo = ord[0];
+    int mr = 0;
+#pragma unroll
+    for (int r = 1; r < R; ++r)
+      if (ord[r] < mo) { mo = ord[r]; mr = r; }  // ties keep the lower position, as the key order does
+    top.init_sorted(mo == 0xffffffffu ? KEY_NONE : (((uint64_t)mo << 32) | (uint32_t)(mr * TILE + lane)), lane);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const bool take = r != mr && ord[r] != 0xffffffffu;
+      top.push_tile(take ? (((uint64_t)ord[r] << 32) | (uint32_t)(r * TILE + lane)) : KEY_NONE, m, lane);
+    }
+  }
+  for (int tb = t0 + R; tb < t1; tb += U) {
+    uint32_t o[U];
+    estimate(tb, o);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t key = o[u] != 0xffffffffu ? (((uint64_t)o[u] << 32) | (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
+      top.push_tile(key, m, lane);
     }
   }
   if (F == 0) {
