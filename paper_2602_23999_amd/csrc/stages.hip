@@ -152,7 +152,7 @@ __global__ __launch_bounds__(64) void select_probes_wave_kernel(const float* __r
 }
 
 // The selection for nprobe <= 64 and any nlist, one wavefront per query: the score row is read
-// once, four 64-score tiles in flight, through a register-resident sorted list of the best.
+// once through a register-resident sorted list of the best.
 __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* __restrict__ scores,
                                                                   const float* __restrict__ sq_norm,
                                                                   const float* __restrict__ centroid_sq, int64_t nq,
@@ -165,8 +165,31 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
   if (q >= nq) return;
   const float* row = scores + q * nlist;
   WaveTopK top;
-  top.v = KEY_NONE;
-  for (int tb = 0; tb < nlist; tb += 256) {
+  // The first 16 tiles (1024 scores) are held in registers: the 64 per-lane minima start the sorted list, so
+  // its nprobe-th key is small from the outset and few of the remaining scores have to be inserted.
+  constexpr int R = 16;
+  {
+    uint32_t ord[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int i = r * 64 + lane;
+      ord[r] = (i < nlist) ? f2ord(row[i]) : 0xffffffffu;
+    }
+    uint32_t mo = ord[0];
+    int mr = 0;
+#pragma unroll
+    for (int r = 1; r < R; ++r)
+      if (ord[r] < mo) { mo = ord[r]; mr = r; }  // ties keep the lower index, as the key order does
+    top.init_sorted(mo == 0xffffffffu ? KEY_NONE : (((uint64_t)mo << 32) | (uint32_t)(mr * 64 + lane)), lane);
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      if (r * 64 < nlist) {
+        const bool take = r != mr && ord[r] != 0xffffffffu;
+        top.push_tile(take ? (((uint64_t)ord[r] << 32) | (uint32_t)(r * 64 + lane)) : KEY_NONE, nprobe, lane);
+      }
+    }
+  }
+  for (int tb = R * 64; tb < nlist; tb += 256) {
     uint64_t kk[4];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -175,9 +198,7 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      if (tb + u * 64 < nlist) {
-        if (tb + u == 0) top.init_sorted(kk[u], lane); else top.push_tile(kk[u], nprobe, lane);
-      }
+      if (tb + u * 64 < nlist) top.push_tile(kk[u], nprobe, lane);
     }
   }
   if (lane < nprobe) {
@@ -196,7 +217,7 @@ int launch_select_probes(const float* scores, const float* sq_norm, const float*
   if (nq <= 0) return RABITQ_OK;
   const int npad = next_pow2(nprobe);
   const size_t smem = npad * sizeof(uint64_t);
-  if (nprobe <= 64 && nlist > 64 * 32)  // rows too long for the register-resident kernels below
+  if (nprobe <= 64)
     hipLaunchKernelGGL(select_probes_stream_kernel, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, scores, sq_norm,
                        centroid_sq, nq, nlist, nprobe, metric, probe_ids, probe_G, probe_E);
   else if (nlist <= 64 * 8)
