@@ -450,12 +450,23 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(const uint64_t* __restr
         const int e = e0 + u * G + g;
         kk[u] = (e < n) ? row[e] : KEY_NONE;
       }
+      if (first) {
+        // the lanes' smallest keys start the sorted list; the other keys are then offered to it
+        uint64_t mn = kk[0];
+        int mu = 0;
+#pragma unroll
+        for (int u = 1; u < 4; ++u)
+          if (kk[u] < mn) { mn = kk[u]; mu = u; }
+        top.init_sorted(mn, lane);
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          if (e0 + u * G < nmax) top.push_tile(u == mu ? KEY_NONE : kk[u], k, lane);
+        first = false;
+        continue;
+      }
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
-        if (e0 + u * G < nmax) {
-          if (first) top.init_sorted(kk[u], lane); else top.push_tile(kk[u], k, lane);
-          first = false;
-        }
+        if (e0 + u * G < nmax) top.push_tile(kk[u], k, lane);
       }
     }
   }
