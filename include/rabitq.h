@@ -57,7 +57,8 @@ typedef struct rabitq_index* rabitq_index_t; /* opaque; owns device copies of th
  * query bit-planes alike.
  */
 typedef struct {
-  int32_t dim;        /* D, multiple of 32, 32..2048                                   */
+  int32_t dim;        /* D: 32, 64, 96, 128, 256, 512, 768, 960 or 1024 (the scan kernels are
+                         instantiated per D/32; other values are rejected)              */
   int32_t nlist;      /* n_k, number of inverted lists                                 */
   int64_t n;          /* N, number of stored vectors                                   */
   int32_t total_bits; /* B in 1..8: 1 sign bit + (B-1) ex bits per dimension           */

@@ -156,9 +156,17 @@ extern "C" {
 
 const char* rabitq_last_error(void) { return g_err.c_str(); }
 
+// the scan kernels are instantiated for these code widths (dim / 32)
+static bool width_supported(int dim) {
+  const int W = dim / 32;
+  return W == 1 || W == 2 || W == 3 || W == 4 || W == 8 || W == 16 || W == 24 || W == 30 || W == 32;
+}
+static const char* kWidthMsg = "dim must be one of 32, 64, 96, 128, 256, 512, 768, 960, 1024 in this build";
+
 int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* stream) {
   if (!d || !out) { set_error("upload: null argument"); return RABITQ_EINVAL; }
   if (d->dim < 32 || d->dim > 2048 || (d->dim % 32) != 0) { set_error("upload: dim must be a multiple of 32 in 32..2048"); return RABITQ_EINVAL; }
+  if (!width_supported(d->dim)) { set_error(std::string("upload: ") + kWidthMsg); return RABITQ_EINVAL; }
   if (d->nlist < 1 || d->n < 0) { set_error("upload: bad nlist or n"); return RABITQ_EINVAL; }
   if (d->total_bits < 1 || d->total_bits > 8) { set_error("upload: total_bits must be 1..8"); return RABITQ_EINVAL; }
   if (d->metric != RABITQ_L2 && d->metric != RABITQ_IP) { set_error("upload: bad metric"); return RABITQ_EINVAL; }
@@ -243,6 +251,7 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
 int rabitq_index_build(const rabitq_build_params* p, const float* data, rabitq_index_t* out, void* stream) {
   if (!p || !out) { set_error("build: null argument"); return RABITQ_EINVAL; }
   if (p->dim < 32 || p->dim > 2048 || (p->dim % 32) != 0) { set_error("build: dim must be a multiple of 32 in 32..2048"); return RABITQ_EINVAL; }
+  if (!width_supported(p->dim)) { set_error(std::string("build: ") + kWidthMsg); return RABITQ_EINVAL; }
   if (p->nlist < 1 || p->n < 0 || p->n > 0x7fffffff) { set_error("build: bad nlist or n"); return RABITQ_EINVAL; }
   if (p->total_bits < 1 || p->total_bits > 8) { set_error("build: total_bits must be 1..8"); return RABITQ_EINVAL; }
   if (p->metric != RABITQ_L2 && p->metric != RABITQ_IP) { set_error("build: bad metric"); return RABITQ_EINVAL; }

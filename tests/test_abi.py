@@ -53,6 +53,14 @@ def test_host_side_argument_errors_need_no_device():
     assert lib.rabitq_search(None, None, 1, 1, 1, None, None, None) == -1
     assert lib.rabitq_probe_list_scratch_words(1024, 10000) == 2 * 1024 * 313 + 1024
     assert lib.rabitq_index_free(None) == 0
+    # a dimension without scan kernels is rejected before anything touches the device
+    desc = rabitq._Desc(160, 4, 0, 1, 0, None, None, None, None, None, None, None, None, None)
+    h = ctypes.c_void_p()
+    assert lib.rabitq_index_upload(ctypes.byref(desc), ctypes.byref(h), None) == -1
+    assert b"dim must be one of" in lib.rabitq_last_error()
+    prm = rabitq._BuildParams(3072, 4, 0, 1, 0, 1, 0, 1.9, None, 0)
+    assert lib.rabitq_index_build(ctypes.byref(prm), None, ctypes.byref(h), None) == -1
+    assert b"dim must be one of" in lib.rabitq_last_error()
 
 
 def _header_structs():
