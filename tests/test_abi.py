@@ -58,7 +58,7 @@ def test_host_side_argument_errors_need_no_device():
     h = ctypes.c_void_p()
     assert lib.rabitq_index_upload(ctypes.byref(desc), ctypes.byref(h), None) == -1
     assert b"dim must be one of" in lib.rabitq_last_error()
-    prm = rabitq._BuildParams(3072, 4, 0, 1, 0, 1, 0, 1.9, None, 0)
+    prm = rabitq._BuildParams(1536, 4, 0, 1, 0, 1, 0, 1.9, None, 0)
     assert lib.rabitq_index_build(ctypes.byref(prm), None, ctypes.byref(h), None) == -1
     assert b"dim must be one of" in lib.rabitq_last_error()
 
