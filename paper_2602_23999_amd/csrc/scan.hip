@@ -459,12 +459,26 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
-    uint64_t* pool = pools + (size_t)j * a.pool;
-    if (nseg > 1 && cnt[j] > a.k) cnt[j] = pool_compact(pool, a.pool, cnt[j], a.k);
-    __syncthreads();
-    int base = 0;
-    if (lane == 0 && cnt[j] > 0) base = atomicAdd(&a.cand_cnt[pj[j]], cnt[j]);
-    base = __builtin_amdgcn_readfirstlane(base);
+    if (nseg > 1 && cnt[j] > a.k) cnt[j] = pool_compact(pools + (size_t)j * a.pool, a.pool, cnt[j], a.k);
+  }
+  __syncthreads();
+  // lane j reserves pair j's part of its candidate region: the atomics of the work item are in flight together
+  int mine = 0, base_l = 0;
+#pragma unroll
+  for (int j = 0; j < QW; ++j)
+    if (lane == j && j < np) mine = cnt[j];
+  if (mine > 0) {
+    int pp = pj[0];
+#pragma unroll
+    for (int j = 1; j < QW; ++j)
+      if (lane == j) pp = pj[j];
+    base_l = atomicAdd(&a.cand_cnt[pp], mine);
+  }
+#pragma unroll
+  for (int j = 0; j < QW; ++j) {
+    if (j >= np) break;
+    const uint64_t* pool = pools + (size_t)j * a.pool;
+    const int base = __builtin_amdgcn_readlane(base_l, j);
     for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.cand_stride + base + e] = pool[e];
   }
 }
@@ -550,8 +564,8 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QM);              // [QM]
   int* qidx = pool_cnt + QM;                                        // [QM] query of each pair
   int* s_list_cnt = qidx + QM;                                      // [MWAVES] entries in each owner list
-  int* s_misc = s_list_cnt + MWAVES;                                // [4]
-  uint32_t* lists = reinterpret_cast<uint32_t*>(s_misc + 4);        // [MWAVES][MLIST_CAP] (F > 0)
+  int* s_out = s_list_cnt + MWAVES;                                 // [QM] first output slot of each pair
+  uint32_t* lists = reinterpret_cast<uint32_t*>(s_out + QM);        // [MWAVES][MLIST_CAP] (F > 0)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lj = lane & 15, g = lane >> 4;
 
   const int n_items = a.item_off[a.nlist];
@@ -725,16 +739,20 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   }
   // a pool larger than the output region, or any pool of a split cluster, is cut to its k best
   block_compact_if_full(nseg > 1 ? a.pool - a.k : a.pool - a.cand_stride);
-#pragma unroll 1
-  for (int j = 0; j < np; ++j) {
+  // every pair reserves its part of the candidate region at once (one atomic per pair, all in flight together);
+  // the wavefronts then copy the pools out, a pair each
+  if (tid < np) {
+    const int cj = pool_cnt[tid];
+    const int pp = a.pair_ids[pbeg + tid];
+    qidx[tid] = pp;  // the query indices are no longer needed
+    s_out[tid] = cj > 0 ? atomicAdd(&a.cand_cnt[pp], cj) : 0;
+  }
+  __syncthreads();
+  for (int j = wave; j < np; j += MWAVES) {
     const uint64_t* pool = pools + (size_t)j * a.pool;
-    const int cj = pool_cnt[j];
-    const int pp = a.pair_ids[pbeg + j];
-    if (tid == 0) s_misc[0] = cj > 0 ? atomicAdd(&a.cand_cnt[pp], cj) : 0;
-    __syncthreads();
-    const int base = s_misc[0];
-    for (int e = tid; e < cj; e += 64 * MWAVES) a.cand_keys[(int64_t)pp * a.cand_stride + base + e] = pool[e];
-    __syncthreads();
+    const int cj = pool_cnt[j], base = s_out[j];
+    const int64_t pp = qidx[j];
+    for (int e = lane; e < cj; e += 64) a.cand_keys[pp * a.cand_stride + base + e] = pool[e];
   }
 }
 
@@ -771,7 +789,7 @@ static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t 
 template <int W, int F>
 static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   const size_t smem = (size_t)QM * a.pool * sizeof(uint64_t) +
-                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + 4) * sizeof(int) +
+                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + QM) * sizeof(int) +
                       (F > 0 ? (size_t)MWAVES * MLIST_CAP * sizeof(uint32_t) : 0);
   if (dbg)
     hipLaunchKernelGGL((scan_mfma_kernel<W, F, true>), dim3(grid), dim3(64 * MWAVES), smem, st, a);
