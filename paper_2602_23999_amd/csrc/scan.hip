@@ -150,10 +150,13 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 // selection and refinement as seed_kernel, but the m <= 64 smallest (est1, position) keys are
 // kept in registers while the cluster streams by, so there is no LDS and no barrier.
 // ---------------------------------------------------------------------------------
-template <int W, int F>
+// SPLIT (small batches): the four wavefronts of a workgroup share one query, each streaming a quarter of the
+// cluster; their sorted lists meet in LDS and the first wavefront finishes alone.
+template <int W, int F, bool SPLIT>
 __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) {
-  const int lane = threadIdx.x & 63;
-  const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  __shared__ uint64_t s_lists[SPLIT ? 3 * 64 : 1];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int64_t q = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
   if (q >= nq) return;
   int rank = -1;
   for (int b = 0; b < a.nprobe && rank < 0; b += 64) {
@@ -172,9 +175,16 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   const float dl = a.delta[q];
   const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
-  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  const int t0 = a.tile_off[c];  // positions in the keys are relative to the cluster's first tile
+  int tw0 = t0, t1 = a.tile_off[c + 1];
+  if (SPLIT) {  // this wavefront's quarter of the tiles (possibly empty)
+    const int per = (t1 - t0 + 3) >> 2;
+    tw0 = min(t0 + wave * per, t1);
+    t1 = min(tw0 + per, t1);
+  }
   const int m = max(a.k, SEED_M);  // <= 64
   WaveTopK top;
+  top.v = KEY_NONE;
   // U tiles are requested together so that their load latencies overlap (tiles past the end
   // re-read the last tile and contribute no key)
   constexpr int U = (W <= 4) ? 4 : (W <= 8 ? 2 : 1);
@@ -202,35 +212,43 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   // The first R tiles are estimated before anything is selected: the 64 per-lane minima (distinct vectors) start
   // the sorted list, so its m-th key is small from the outset and few of the remaining keys have to be inserted.
   constexpr int R = (W <= 4) ? 16 : (W <= 8 ? 8 : 4);
-  {
+  if (tw0 < t1) {
+    const uint32_t pos0 = (uint32_t)(tw0 - t0) * TILE + lane;
     uint32_t ord[R];
 #pragma unroll
-    for (int c = 0; c < R; c += U) {
+    for (int c2 = 0; c2 < R; c2 += U) {
       uint32_t o[U];
-      estimate(t0 + c, o);
+      estimate(tw0 + c2, o);
 #pragma unroll
-      for (int u = 0; u < U; ++u) ord[c + u] = (t0 + c + u < t1) ? o[u] : 0xffffffffu;
+      for (int u = 0; u < U; ++u) ord[c2 + u] = (tw0 + c2 + u < t1) ? o[u] : 0xffffffffu;
     }
     uint32_t mo = ord[0];
     int mr = 0;
 #pragma unroll
     for (int r = 1; r < R; ++r)
       if (ord[r] < mo) { mo = ord[r]; mr = r; }  // ties keep the lower position, as the key order does
-    top.init_sorted(mo == 0xffffffffu ? KEY_NONE : (((uint64_t)mo << 32) | (uint32_t)(mr * TILE + lane)), lane);
+    top.init_sorted(mo == 0xffffffffu ? KEY_NONE : (((uint64_t)mo << 32) | (pos0 + (uint32_t)(mr * TILE))), lane);
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const bool take = r != mr && ord[r] != 0xffffffffu;
-      top.push_tile(take ? (((uint64_t)ord[r] << 32) | (uint32_t)(r * TILE + lane)) : KEY_NONE, m, lane);
+      top.push_tile(take ? (((uint64_t)ord[r] << 32) | (pos0 + (uint32_t)(r * TILE))) : KEY_NONE, m, lane);
+    }
+    for (int tb = tw0 + R; tb < t1; tb += U) {
+      uint32_t o[U];
+      estimate(tb, o);
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint64_t key = o[u] != 0xffffffffu ? (((uint64_t)o[u] << 32) | (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
+        top.push_tile(key, m, lane);
+      }
     }
   }
-  for (int tb = t0 + R; tb < t1; tb += U) {
-    uint32_t o[U];
-    estimate(tb, o);
+  if (SPLIT) {  // the other wavefronts hand their lists to the first and leave
+    if (wave > 0) s_lists[(wave - 1) * 64 + lane] = top.v;
+    __syncthreads();
+    if (wave > 0) return;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const uint64_t key = o[u] != 0xffffffffu ? (((uint64_t)o[u] << 32) | (uint32_t)((tb + u - t0) * TILE + lane)) : KEY_NONE;
-      top.push_tile(key, m, lane);
-    }
+    for (int w2 = 0; w2 < 3; ++w2) top.push_tile(s_lists[w2 * 64 + lane], m, lane);
   }
   if (F == 0) {
     const uint64_t kth = readlane_u64(top.v, a.k - 1);
@@ -780,8 +798,10 @@ static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t 
   const size_t smem = (size_t)(SEED_CHUNK_TILES * TILE + 2 * kpad) * sizeof(uint64_t) + (size_t)a.D * sizeof(float);
   if (impl == 2)
     hipLaunchKernelGGL((seed_kernel<W, F, 1>), dim3((unsigned)nq), dim3(256), smem + (size_t)W * 256, st, a);
+  else if (a.k <= 64 && nq <= 2048)  // few queries: four wavefronts per query
+    hipLaunchKernelGGL((seed_wave_kernel<W, F, true>), dim3((unsigned)nq), dim3(256), 0, st, a, nq);
   else if (a.k <= 64)
-    hipLaunchKernelGGL((seed_wave_kernel<W, F>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, a, nq);
+    hipLaunchKernelGGL((seed_wave_kernel<W, F, false>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, a, nq);
   else
     hipLaunchKernelGGL((seed_kernel<W, F, 0>), dim3((unsigned)nq), dim3(256), smem, st, a);
 }
