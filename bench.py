@@ -162,7 +162,8 @@ def stream_scan(args):
                    "query_vector_evaluations": qv},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": None,
-                     "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[args.scan_impl],
+                     "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)",
+                                "scan_kernel")[args.scan_impl],  # D = 128: the default choice is the popcount kernel
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},
     }
     print(json.dumps(res), flush=True)
@@ -216,8 +217,9 @@ def main():
     ap.add_argument("--workload", default="l2_128")
     ap.add_argument("--nprobe", type=int, default=0, help="fix the operating point instead of choosing it by recall")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
-    ap.add_argument("--scan-impl", type=int, default=0,
-                    help="0: popcount scan (default), 1: matrix-core scan, 2: lookup-table scan")
+    ap.add_argument("--scan-impl", type=int, default=3,
+                    help="0: popcount scan, 1: matrix-core scan, 2: lookup-table scan, 3 (default): the library's choice "
+                         "by code width (popcount below D = 960)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one elementwise add over 256 MiB (reads 256 MiB, writes 256 MiB): the known-size "
@@ -319,11 +321,12 @@ def main():
     # The scan of this workload is served by the caches (every list is probed by ~160 queries of the batch) and is
     # bound by the vector ALUs: 8W + 6 lane-operations per query-vector evaluation (W AND + W popcount per bit-plane,
     # 4 planes, then combine, estimate, bound and compare).  The HBM view of the same launch is kept beside it.
+    impl = args.scan_impl if args.scan_impl != 3 else (1 if w.dim >= 960 else 0)
     alu_ops = qv * (8 * (w.dim // 32) + 6)
     alu_achieved = alu_ops / (scan_ms * 1e-3) / 1e12
     roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TOPS, "unit": "TOP/s (integer lane-operations)",
-                "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic if args.scan_impl == 0 else None,
-                "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[args.scan_impl],
+                "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic if impl == 0 else None,
+                "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[impl],
                 "algorithmic_ops_per_launch": alu_ops, "kernel_ms": scan_ms,
                 "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_gbs": achieved, "peak_gbs": HBM_PEAK_GBS,
                              "frac": achieved / HBM_PEAK_GBS,
@@ -333,7 +336,7 @@ def main():
         "metric": "queries/sec at recall@10~0.95 (1 GPU); code-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("u32 popcount + f32", "i8 matrix cores + f32", "f16 tables + f32")[args.scan_impl], "data": "synthetic",
+        "dtype": ("u32 popcount + f32", "i8 matrix cores + f32", "f16 tables + f32")[impl], "data": "synthetic",
         "config": {"workload": f"{w.name}: N={w.n} D={w.dim} nlist={w.nlist} B={w.total_bits} "
                                f"nq={w.nq} k={w.k} nprobe={nprobe}",
                    "recall_at_k": round(r_op, 4), "recall_target": 0.95, "nprobe_sweep": sweep,

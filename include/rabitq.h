@@ -159,6 +159,7 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *             wavefront; 1: the same integer inner products on the matrix cores (the sign
  *             bits of a tile are expanded to int8 once and contracted against 16 queries'
  *             qhat with v_mfma_i32_16x16x64_i8).  Results of 0 and 1 are identical; only speed differs.
+ *             3 (default): 1 for D >= 960, 0 below (the faster of the two in measurements).
  *             2: the lookup-table scheme of Section 3.4.1(1) instead of the quantised query:
  *             <x_b, q'> is the fp32 sum, in ascending block order, of one binary16 table entry per
  *             4 dimensions (tables in LDS, 4 queries per wavefront).  Used by the threshold

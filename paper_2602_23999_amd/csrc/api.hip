@@ -319,7 +319,7 @@ int rabitq_index_free(rabitq_index_t ix) {
 int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!ix || !name) { set_error("set_option: null argument"); return RABITQ_EINVAL; }
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
-  if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 2) { ix->scan_impl = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 3) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
     ix->prof_mask = (unsigned)value;

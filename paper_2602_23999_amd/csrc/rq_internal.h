@@ -65,7 +65,7 @@ struct rabitq_index {
   mutable int64_t seg_total = 0;
   // options
   int prune = 1;
-  int scan_impl = 0;
+  int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl)
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   // second stream of a search (default priority) and the events that fork it from and join it to the caller's
   hipStream_t side = nullptr;
@@ -79,6 +79,11 @@ struct rabitq_index {
 };
 
 namespace rq {
+
+// The scan the handle's option selects: "by code width" takes the matrix-core kernel from D = 960 on, where it was
+// measured 2.8x faster than the popcount kernel (0.98 against 2.79 ms), and the popcount kernel below (D = 768: 22 against
+// 31 ms, D = 128: 0.30 against 0.41 ms).
+inline int effective_impl(const rabitq_index* ix) { return ix->scan_impl == 3 ? (ix->W >= 30 ? 1 : 0) : ix->scan_impl; }
 
 void set_error(const std::string& s);
 int hip_fail(hipError_t e, const char* what);

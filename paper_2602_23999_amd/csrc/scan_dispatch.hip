@@ -103,7 +103,7 @@ int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int
   a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
   a.nprobe = nprobe; a.k = k; a.tau_out = tau;
   const int W = ix->W, F = field_bits(ix->total_bits);
-  const int impl = ix->scan_impl;
+  const int impl = effective_impl(ix);
   if (!(seed_part0(a, W, F, impl, nq, st) || seed_part1(a, W, F, impl, nq, st) || seed_part2(a, W, F, impl, nq, st)))
     return bad_width();
   RQ_HIP(hipGetLastError());
@@ -118,7 +118,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   if (int rc = need_lut(ix, repr)) return rc;
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
-  const int impl = ix->scan_impl;
+  const int impl = effective_impl(ix);
   const int qw = impl == 1 ? QM : QW;
   a.probe_G = probe_G; a.probe_E = probe_E; a.pair_off = pair_off; a.pair_ids = pair_ids; a.tau = tau;
   a.nprobe = nprobe; a.k = k;
