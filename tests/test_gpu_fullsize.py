@@ -21,7 +21,8 @@ def test_l2_128_full_size_sampled_parity():
     k, nprobe = w.k, 16
     X, Q = synth.make_base(w), synth.make_queries(w)
     workers = min(16, len(os.sched_getaffinity(0)))
-    ix = build.build_index(X, w.nlist, w.total_bits, train_size=w.n // 10, kmeans_iters=5, workers=workers)
+    ix = build.build_index(X, w.nlist, w.total_bits, train_size=w.n // 10, kmeans_iters=5, workers=workers,
+                           center=True)   # as bench.py builds it: vectors minus their mean
     gi = upload(ix)
     Qd = torch.from_numpy(Q).cuda()
     ids, dist = gi.search(Qd, k, nprobe)
