@@ -194,6 +194,23 @@ class Index:
                                        p(out["long_factors"]), p(out["ids"]), p(out["mean"])))
         return out
 
+    def save(self, path: str):
+        """Writes the exported arrays to an .npz file (plain arrays, no pickled objects)."""
+        out = self.export()
+        np.savez(path, **{k: (np.asarray(v) if v is not None else np.zeros(0, np.uint32)) for k, v in out.items()})
+
+    @classmethod
+    def load(cls, path: str) -> "Index":
+        """Uploads an index written by save()."""
+        with np.load(path, allow_pickle=False) as z:
+            d = {k: z[k] for k in z.files}
+        scal = {k: int(d.pop(k)) for k in ("dim", "nlist", "n", "total_bits")}
+        metric = str(d.pop("metric"))
+        for k in ("long_codes", "long_factors"):
+            if d[k].size == 0:
+                d[k] = None
+        return cls(metric=metric, **scal, **d)
+
     def close(self):
         if getattr(self, "_h", None):
             _check(load_library().rabitq_index_free(self._h))

@@ -63,6 +63,14 @@ def test_centred_device_build():
     # (the upload recomputes the centroid norms on the host; the coarse term is a difference of large squares)
     atol = 2e-6 * float(((Q - out["mean"]).astype(np.float64) ** 2).sum(1).max())
     assert torch.equal(ids, ids2) and torch.allclose(d, d2, rtol=1e-5, atol=atol)
+    # save -> load (plain .npz) answers identically too
+    import os, tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        gi.save(os.path.join(tmp, "ix.npz"))
+        gk = rabitq.Index.load(os.path.join(tmp, "ix.npz"))
+    ids3, d3 = gk.search(torch.from_numpy(Q).cuda(), 10, 8)
+    assert torch.equal(ids, ids3) and torch.allclose(d, d3, rtol=1e-5, atol=atol)
+    gk.close()
     # an inner-product index cannot be centred
     with pytest.raises(rabitq.RabitqError):
         rabitq.Index.build(torch.from_numpy(X).cuda(), 40, 4, P, metric="ip", center=True)
