@@ -31,13 +31,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
   const float* a_ptr = A + (m0 + a_row) * (int64_t)K + a_half * 8;
   const bool n_vec = ((N & 3) == 0) && (n0 + b_n + 3 < N);
 
-  for (int k0 = 0; k0 < K; k0 += BK) {
-    float4 a0 = make_float4(0, 0, 0, 0), a1 = a0;
+  // operands of one k step as this thread loads them
+  float4 a0, a1, b;
+  auto fetch = [&](int k0) {
+    a0 = make_float4(0, 0, 0, 0);
+    a1 = a0;
     if (a_ok) {
       a0 = *reinterpret_cast<const float4*>(a_ptr + k0);
       a1 = *reinterpret_cast<const float4*>(a_ptr + k0 + 4);
     }
-    float4 b = make_float4(0, 0, 0, 0);
+    b = make_float4(0, 0, 0, 0);
     const float* b_ptr = B + (int64_t)(k0 + b_k) * N + n0 + b_n;
     if (n_vec) {
       b = *reinterpret_cast<const float4*>(b_ptr);
@@ -47,12 +50,16 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
       if (n0 + b_n + 2 < N) b.z = b_ptr[2];
       if (n0 + b_n + 3 < N) b.w = b_ptr[3];
     }
+  };
+  fetch(0);
+  for (int k0 = 0; k0 < K; k0 += BK) {
     __syncthreads();  // previous tile fully consumed
     const int kk = a_half * 8;
     As[kk + 0][a_row] = a0.x; As[kk + 1][a_row] = a0.y; As[kk + 2][a_row] = a0.z; As[kk + 3][a_row] = a0.w;
     As[kk + 4][a_row] = a1.x; As[kk + 5][a_row] = a1.y; As[kk + 6][a_row] = a1.z; As[kk + 7][a_row] = a1.w;
     *reinterpret_cast<float4*>(&Bs[b_k][b_n]) = b;
     __syncthreads();
+    if (k0 + BK < K) fetch(k0 + BK);  // the next step's operands travel while this step's products run
 #pragma unroll
     for (int k = 0; k < BK; k += 2) {
       const int kr = k + (lane >> 5);
