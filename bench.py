@@ -150,6 +150,19 @@ def stream_scan(args):
     distinct = int(torch.unique(probes).numel())
     scan_ms = stage_ms["scan"]
     achieved = alg_bytes / (scan_ms * 1e-3) / 1e9
+    # what a plain device-to-device copy of 1 GiB reaches on this device (read + write bytes), for scale
+    src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 10 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del src, dst
     res = {
         "metric": "code-scan HBM GB/s vs peak, streaming regime (1 GPU)", "value": achieved, "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": sec * 1e3, "higher_is_better": True,
@@ -161,7 +174,7 @@ def stream_scan(args):
                    "stage_ms": {k_: round(v, 4) for k_, v in stage_ms.items()}, "stage_ms_calls": calls,
                    "query_vector_evaluations": qv},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None, "device_copy_gbs": copy_gbs,
                      "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)",
                                 "scan_kernel")[args.scan_impl],  # D = 128: the default choice is the popcount kernel
                      "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms},

@@ -38,6 +38,7 @@ struct ScanArgs {
   const int32_t* pair_ids;
   const int32_t* item_off;
   int nprobe, k, pool, cand_stride;
+  int streaming;     // few pairs per list: every list is read from memory about once (prefetching scan variant)
   int tseg, segmax;  // a cluster of more than tseg tiles is scanned in up to segmax segments (separate work items)
   // outputs
   uint64_t* cand_keys;

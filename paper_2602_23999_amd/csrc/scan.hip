@@ -312,7 +312,9 @@ __device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   return min(cnt, k);
 }
 
-template <int W, int F, bool DBG, int M>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
+// PFD > 0 (streaming regime, few pairs per list): the codes and factors of the next tiles are requested ahead, because
+// there the kernel waits for memory, not for the vector ALUs.
+template <int W, int F, bool DBG, int M, int PFD = 0>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
 __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF;
   constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
@@ -344,6 +346,21 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int ts = t0 + sidx * seglen, te = min(tc1, ts + seglen);
   const int pbeg = a.pair_off[c] + grp * QW;
   const int np = min(QW, a.pair_off[c + 1] - pbeg);
+
+  constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead
+  uint32_t pw[PD > 0 ? PD : 1][W];
+  float pf[PD > 0 ? PD : 1][3];
+  auto fetch = [&](uint32_t (&w_)[W], float (&f_)[3], int tile) {
+#pragma unroll
+    for (int w = 0; w < W; ++w) w_[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
+#pragma unroll
+    for (int f = 0; f < 3; ++f) f_[f] = a.short_factors[((int64_t)tile * 3 + f) * TILE + lane];
+  };
+  // (requested here, before the scalars of the pairs are fetched, so that the two waits overlap)
+  if (PD > 0 && ts < te) {
+#pragma unroll
+    for (int d = 0; d < PD; ++d) fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(ts + d, te - 1));
+  }
 
   int pj[QW], Sj[QW], cnt[QW];
   float Gj[QW], Ej[QW], dlj[QW], bej[QW], tauj[QW], hsqj[QW];
@@ -419,11 +436,24 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 
   for (int tile = ts; tile < te; ++tile) {
     uint32_t cw[W];
+    float fq[3];
+    if (PD > 0) {
 #pragma unroll
-    for (int w = 0; w < W; ++w) cw[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
-    const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
-    const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
-    const float fe = a.short_factors[((int64_t)tile * 3 + 2) * TILE + lane];
+      for (int w = 0; w < W; ++w) cw[w] = pw[0][w];
+#pragma unroll
+      for (int f = 0; f < 3; ++f) fq[f] = pf[0][f];
+#pragma unroll
+      for (int d = 0; d + 1 < PD; ++d) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) pw[d][w] = pw[PD > 1 ? d + 1 : 0][w];
+#pragma unroll
+        for (int f = 0; f < 3; ++f) pf[d][f] = pf[PD > 1 ? d + 1 : 0][f];
+      }
+      fetch(pw[PD > 0 ? PD - 1 : 0], pf[PD > 0 ? PD - 1 : 0], min(tile + PD, te - 1));  // past the end: a harmless re-read
+    } else {
+      fetch(cw, fq, tile);
+    }
+    const float fa = fq[0], fr = fq[1], fe = fq[2];
     // The plane words are re-read through the scalar cache for every (tile, query): an
     // opaque zero keeps the compiler from hoisting QW*4*W scalar registers out of the loop.
     int opaque0;
@@ -824,6 +854,8 @@ static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream
                       (M == 1 ? (size_t)QW * W * 256 : 0);
   if (dbg)
     hipLaunchKernelGGL((scan_kernel<W, F, true, M>), dim3(grid), dim3(64), smem, st, a);
+  else if (M == 0 && a.streaming)
+    hipLaunchKernelGGL((scan_kernel<W, F, false, M, (M == 0 ? 1 : 0)>), dim3(grid), dim3(64), smem, st, a);
   else
     hipLaunchKernelGGL((scan_kernel<W, F, false, M>), dim3(grid), dim3(64), smem, st, a);
 }

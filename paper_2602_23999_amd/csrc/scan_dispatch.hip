@@ -143,6 +143,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     a.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
   }
   a.segmax = std::max(1, a.cand_stride / k);
+  a.streaming = (nq * nprobe <= 4 * (int64_t)ix->nlist) ? 1 : 0;
   if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
   hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
                      a.segmax, item_off);
