@@ -13,10 +13,10 @@ pytestmark = pytest.mark.gpu
 
 CASES = {
     # name: (workload, n, nq, n_centres, nlist, B, k, nprobe)
-    "tiny_b1": ("tiny", 10_000, 100, 64, 64, 1, 10, 8),          # BASELINE config 1 as stated
-    "l2_128_b4": ("l2_128", 30_000, 96, 64, 48, 4, 10, 6),       # config 2 shape, reduced
-    "l2_96_b3_k100": ("l2_96", 20_000, 64, 64, 40, 3, 100, 8),   # config 4 shape (W = 3, K = 100)
-    "l2_960_b5": ("l2_960", 4_000, 24, 16, 12, 5, 10, 4),        # config 3 shape (W = 30)
+    "tiny_b1": ("tiny", 10_000, 100, 64, 64, 1, 10, 8),          # the small 1-bit configuration at its full size
+    "l2_128_b4": ("l2_128", 30_000, 96, 64, 48, 4, 10, 6),       # the benchmark shape (D = 128, B = 4), reduced
+    "l2_96_b3_k100": ("l2_96", 20_000, 64, 64, 40, 3, 100, 8),   # D = 96 (W = 3), K = 100
+    "l2_960_b5": ("l2_960", 4_000, 24, 16, 12, 5, 10, 4),        # D = 960 (W = 30)
     "ragged_b2": ("tiny", 1_500, 40, 50, 50, 2, 10, 50),          # many small / empty lists, nprobe = nlist
     "centred_b4": ("l2_128", 20_000, 64, 64, 32, 4, 10, 6),      # index built on the vectors minus their mean
     "many_probes_b2": ("tiny", 12_000, 48, 64, 160, 2, 10, 100),  # nprobe > 64: workgroup-wide probe selection
