@@ -189,16 +189,21 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
       }
     }
   }
-  for (int tb = R * 64; tb < nlist; tb += 256) {
-    uint64_t kk[4];
+  // the rest of the row, eight tiles of scores in flight; a tile is only looked at closely when its smallest
+  // score beats the current nprobe-th key
+  for (int tb = R * 64; tb < nlist; tb += 512) {
+    float sc[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < 8; ++u) {
       const int i = tb + u * 64 + lane;
-      kk[u] = (i < nlist) ? make_key(row[i], (uint32_t)i) : KEY_NONE;
+      sc[u] = (i < nlist) ? row[i] : INFINITY;
     }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      if (tb + u * 64 < nlist) top.push_tile(kk[u], nprobe, lane);
+    for (int u = 0; u < 8; ++u) {
+      if (tb + u * 64 < nlist) {
+        const int i = tb + u * 64 + lane;
+        top.push_tile((i < nlist) ? make_key(sc[u], (uint32_t)i) : KEY_NONE, nprobe, lane);
+      }
     }
   }
   if (lane < nprobe) {
