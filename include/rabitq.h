@@ -14,7 +14,9 @@
  * stream).  Unless stated otherwise a call only enqueues work on `stream` and
  * returns; outputs are valid once the caller has synchronised the stream.
  * A handle supports one in-flight rabitq_search at a time (the workspace it owns
- * is reused); the stage-level calls use only caller-provided buffers.
+ * is reused); the stage-level calls use only caller-provided buffers.  A handle belongs
+ * to the device that was current when it was created; calls made with another current
+ * device are rejected (RABITQ_EINVAL).
  */
 #ifndef RABITQ_H
 #define RABITQ_H

@@ -382,6 +382,11 @@ int rabitq_stage_ms(rabitq_index_t ix, float* out_ms, int32_t* out_calls) {
 static int check_common(rabitq_index_t ix, int64_t nq, const char* who) {
   if (!ix) { set_error(std::string(who) + ": null index"); return RABITQ_EINVAL; }
   if (nq < 0) { set_error(std::string(who) + ": nq < 0"); return RABITQ_EINVAL; }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev != ix->device) {  // the handle's arrays live on one device
+    set_error(std::string(who) + ": the current device is not the one the index was created on");
+    return RABITQ_EINVAL;
+  }
   return RABITQ_OK;
 }
 
