@@ -57,7 +57,7 @@ def scan_algorithmic_bytes(gi, Qd, nprobe, cluster_sizes, dim):
     return qv * (dim // 8 + 12), qv
 
 
-def cpu_baseline(w, nprobe, sample_n=100_000, sample_q=200):
+def cpu_baseline(w, nprobe, sample_n=100_000, sample_q=1000):
     """The CPU oracle as it stands, timed on this host: it builds its own index over a
     bounded sample of the same workload (same mean list size, same k and nprobe, so the
     work per query matches) and answers `sample_q` queries."""
