@@ -230,6 +230,9 @@ def main():
     ap.add_argument("--workload", default="l2_128")
     ap.add_argument("--nprobe", type=int, default=0, help="fix the operating point instead of choosing it by recall")
     ap.add_argument("--n", type=int, default=0, help="override the number of base vectors (for quick runs)")
+    ap.add_argument("--bits", type=int, default=0,
+                    help="override the workload's total bits per dimension (1..8): shows where the recall ceiling of "
+                         "the code size lies; the default run keeps the size the workload states")
     ap.add_argument("--scan-impl", type=int, default=3,
                     help="0: popcount scan, 1: matrix-core scan, 2: lookup-table scan, 3 (default): the library's choice "
                          "by code width (popcount below D = 960)")
@@ -260,6 +263,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.n:
         w = w.scaled(n=args.n, nlist=max(64, int(round(w.nlist * args.n / w.n))))
+    if args.bits:
+        w = w.scaled(total_bits=args.bits)
     t0 = time.perf_counter()
     X, Q = synth.make_base(w), synth.make_queries(w)
     Xd, Qd = torch.from_numpy(X).cuda(), torch.from_numpy(Q).cuda()
