@@ -246,7 +246,7 @@ def main():
     ap.add_argument("--stream-scan", action="store_true",
                     help="measure the code scan in the streaming regime instead (index far larger than the caches, "
                          "one query per list); prints its own JSON line")
-    ap.add_argument("--stream-n", type=int, default=32 * 1024 * 1024)
+    ap.add_argument("--stream-n", type=int, default=64 * 1024 * 1024)
     ap.add_argument("--stream-bits", type=int, default=1)
     ap.add_argument("--stream-list", type=int, default=1024, help="mean inverted-list length of the streaming index")
     args = ap.parse_args()

@@ -100,6 +100,7 @@ struct EncodeArgs {
   const int32_t* members;   // [N] vector ids in cluster order
   const int32_t* tile_off;  // [nlist+1]
   int64_t n;
+  int64_t p0;               // first position of this launch
   int D, B, F, LW, nlist, metric;
   float eps0;
   uint32_t* short_codes;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256) void encode_kernel(EncodeArgs a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   float* ybuf = reinterpret_cast<float*>(smem_raw) + (size_t)wave * a.D;                          // [D] |o'|
   unsigned char* ubuf = smem_raw + 4 * (size_t)a.D * sizeof(float) + (size_t)wave * a.D;         // [D] codes
-  const int64_t p = (int64_t)blockIdx.x * 4 + wave;  // position in cluster order
+  const int64_t p = a.p0 + (int64_t)blockIdx.x * 4 + wave;  // position in cluster order
   if (p >= a.n) return;
   // cluster of this position: largest c with off[c] <= p
   int lo = 0, hi = a.nlist;
@@ -317,6 +318,120 @@ static unsigned grid_for(int64_t n, int block = 256, int64_t cap = 65535) {
   return (unsigned)std::max<int64_t>(1, std::min<int64_t>((n + block - 1) / block, cap));
 }
 
+// ---- rows grouped by cluster -------------------------------------------------------------------
+// A stable counting sort of row ids by cluster id whose memory grows with rows + blocks * nlist (the
+// search path's builder keeps one bit per (cluster, query), which is right for 10^4 queries and far
+// too much for 10^7 vectors).  The rows are cut into `nb` contiguous blocks; a workgroup counts its
+// block per cluster, the counts are scanned block-major per cluster, and the same workgroup then places
+// its rows tile by tile in row order, so every list holds its rows in ascending order whatever the
+// scheduling.
+constexpr int GROUP_TILE = 256;
+struct GroupPlan {
+  int nb;       // workgroups = row blocks
+  int64_t ch;   // rows per block, a multiple of GROUP_TILE
+};
+static GroupPlan group_plan(int64_t rows) {
+  GroupPlan g;
+  const int64_t want = std::max<int64_t>(1, std::min<int64_t>((rows + 4095) / 4096, 1024));
+  g.ch = ((rows + want - 1) / want + GROUP_TILE - 1) / GROUP_TILE * GROUP_TILE;
+  if (g.ch < GROUP_TILE) g.ch = GROUP_TILE;
+  g.nb = (int)std::max<int64_t>(1, (rows + g.ch - 1) / g.ch);
+  return g;
+}
+
+__global__ __launch_bounds__(GROUP_TILE) void group_count_kernel(const int32_t* __restrict__ asg, int64_t rows, int64_t ch,
+                                                                 int nlist, int32_t* __restrict__ hist) {
+  const int64_t r0 = (int64_t)blockIdx.x * ch, r1 = r0 + ch < rows ? r0 + ch : rows;
+  int32_t* h = hist + (int64_t)blockIdx.x * nlist;
+  for (int64_t i = r0 + threadIdx.x; i < r1; i += GROUP_TILE) atomicAdd(&h[asg[i]], 1);
+}
+
+// per cluster: counts of the row blocks -> exclusive prefix over the blocks (in place) and the list length
+__global__ void group_block_prefix_kernel(int32_t* __restrict__ hist, int nb, int nlist, int32_t* __restrict__ total) {
+  const int c = blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= nlist) return;
+  int32_t run = 0;
+  for (int b = 0; b < nb; ++b) {
+    const int32_t v = hist[(int64_t)b * nlist + c];
+    hist[(int64_t)b * nlist + c] = run;
+    run += v;
+  }
+  total[c] = run;
+}
+
+// off[c] = sum of total[0..c), off[nlist] = rows; one workgroup walks the lists in order
+__global__ __launch_bounds__(1024) void group_offsets_kernel(const int32_t* __restrict__ total, int nlist,
+                                                             int32_t* __restrict__ off) {
+  __shared__ int32_t s_part[1024];
+  __shared__ int32_t s_base;
+  if (threadIdx.x == 0) s_base = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < nlist; c0 += 1024) {
+    const int c = c0 + threadIdx.x;
+    const int32_t v = c < nlist ? total[c] : 0;
+    s_part[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < 1024; d <<= 1) {  // inclusive scan of the 1024 values
+      const int32_t add = threadIdx.x >= d ? s_part[threadIdx.x - d] : 0;
+      __syncthreads();
+      s_part[threadIdx.x] += add;
+      __syncthreads();
+    }
+    if (c < nlist) off[c] = s_base + s_part[threadIdx.x] - v;
+    __syncthreads();
+    if (threadIdx.x == 1023) s_base += s_part[1023];
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) off[nlist] = s_base;
+}
+
+__global__ __launch_bounds__(GROUP_TILE) void group_scatter_kernel(const int32_t* __restrict__ asg, int64_t rows, int64_t ch,
+                                                                   int nlist, int32_t* __restrict__ hist,
+                                                                   const int32_t* __restrict__ off,
+                                                                   int32_t* __restrict__ members) {
+  __shared__ int32_t s_key[GROUP_TILE];
+  const int64_t r0 = (int64_t)blockIdx.x * ch, r1 = r0 + ch < rows ? r0 + ch : rows;
+  int32_t* h = hist + (int64_t)blockIdx.x * nlist;  // rows of this cluster placed so far, by earlier blocks and tiles
+  const int tid = threadIdx.x;
+  for (int64_t t0 = r0; t0 < r1; t0 += GROUP_TILE) {
+    const int64_t i = t0 + tid;
+    const bool valid = i < r1;
+    const int32_t key = valid ? asg[i] : -1;
+    s_key[tid] = key;
+    __syncthreads();
+    int before = 0, same = 0;  // rows of the tile in the same list: ahead of this one, and in all
+    for (int j = 0; j < GROUP_TILE; ++j) {
+      const bool eq = s_key[j] == key;
+      same += eq;
+      before += eq && j < tid;
+    }
+    if (valid) {
+      // the counter is only ever changed by atomics of this workgroup; read it where they are performed
+      const int32_t base = __hip_atomic_load(&h[key], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      members[off[key] + base + before] = (int32_t)i;
+    }
+    __syncthreads();  // every row of the tile has read its counter
+    if (valid && before == same - 1) atomicAdd(&h[key], same);
+    __syncthreads();  // and the next tile sees the advanced counters
+  }
+}
+
+// rows [0, rows) grouped by asg[] into off[nlist + 1] / members[rows]; hist holds group_plan(rows).nb * nlist words
+static int launch_group_rows(const int32_t* asg, int64_t rows, int nlist, int32_t* off, int32_t* members, int32_t* hist,
+                             int32_t* total, hipStream_t st) {
+  const GroupPlan g = group_plan(rows);
+  const int64_t hw = (int64_t)g.nb * nlist;
+  hipLaunchKernelGGL(fill_i32_kernel, dim3(grid_for(hw)), dim3(256), 0, st, hist, hw, 0);
+  if (rows > 0)
+    hipLaunchKernelGGL(group_count_kernel, dim3(g.nb), dim3(GROUP_TILE), 0, st, asg, rows, g.ch, nlist, hist);
+  hipLaunchKernelGGL(group_block_prefix_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, hist, g.nb, nlist, total);
+  hipLaunchKernelGGL(group_offsets_kernel, dim3(1), dim3(1024), 0, st, total, nlist, off);
+  if (rows > 0)
+    hipLaunchKernelGGL(group_scatter_kernel, dim3(g.nb), dim3(GROUP_TILE), 0, st, asg, rows, g.ch, nlist, hist, off, members);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
 // nearest rotated centroid of every row of `x` [rows][D]; `scores` holds chunk x nlist floats
 static int assign_rows(const float* x, int64_t rows, int D, int nlist, const float* ct, const float* csq, float* scores,
                        int64_t chunk, int32_t* out, hipStream_t st) {
@@ -341,8 +456,7 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
   RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->rotation), (size_t)D * D * sizeof(float)));
   RQ_HIP(hipMemcpyAsync(ix->rotation, rotation_host, (size_t)D * D * sizeof(float), hipMemcpyHostToDevice, st));
   DevBuf<float> xr, tr, c_rows, scores;
-  DevBuf<int32_t> asg, off, members;
-  DevBuf<uint32_t> scratch;
+  DevBuf<int32_t> asg, off, members, hist, total;
   RQ_TRY(xr.alloc(N * D));
   if (center && N > 0) {
     // mean of the raw vectors; every later step sees (x - mean) P = x P - mean P
@@ -371,18 +485,19 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
   RQ_TRY(asg.alloc(std::max(N, nt)));
   RQ_TRY(off.alloc(nlist + 1));
   RQ_TRY(members.alloc(std::max(N, nt)));
-  RQ_TRY(scratch.alloc(probe_list_scratch_words(nlist, std::max(N, nt))));
+  RQ_TRY(hist.alloc((int64_t)std::max(group_plan(N).nb, group_plan(nt).nb) * nlist));
+  RQ_TRY(total.alloc(nlist));
   for (int it = 0; it < kmeans_iters; ++it) {
     hipLaunchKernelGGL(transpose_centroids_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, c_rows.p, nlist, D,
                        ix->centroids_t, ix->centroid_sq);
     RQ_TRY(assign_rows(tr.p, nt, D, nlist, ix->centroids_t, ix->centroid_sq, scores.p, chunk, asg.p, st));
-    RQ_TRY(launch_build_lists(asg.p, nt, 1, nlist, off.p, members.p, scratch.p, st));
+    RQ_TRY(launch_group_rows(asg.p, nt, nlist, off.p, members.p, hist.p, total.p, st));
     hipLaunchKernelGGL(centroid_update_kernel, dim3(nlist), dim3(256), 0, st, tr.p, off.p, members.p, D, c_rows.p);
   }
   hipLaunchKernelGGL(transpose_centroids_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, c_rows.p, nlist, D,
                      ix->centroids_t, ix->centroid_sq);
   RQ_TRY(assign_rows(xr.p, N, D, nlist, ix->centroids_t, ix->centroid_sq, scores.p, chunk, asg.p, st));
-  RQ_TRY(launch_build_lists(asg.p, N, 1, nlist, off.p, members.p, scratch.p, st));
+  RQ_TRY(launch_group_rows(asg.p, N, nlist, off.p, members.p, hist.p, total.p, st));
   // layout: cluster sizes, tile offsets (the total is needed on the host to size the arrays)
   RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->cluster_size), (size_t)nlist * sizeof(int32_t)));
   RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->tile_off), (size_t)2 * (nlist + 1) * sizeof(int32_t)));
@@ -423,8 +538,11 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
   a.n = N; a.D = D; a.B = B; a.F = ix->F; a.LW = LW; a.nlist = nlist; a.metric = ix->metric; a.eps0 = eps0;
   a.short_codes = ix->short_codes; a.short_factors = ix->short_factors; a.long_codes = ix->long_codes;
   a.long_factors = ix->long_factors; a.ids = ix->ids;
-  if (N > 0) {
-    const unsigned grid = (unsigned)((N + 3) / 4);
+  // (a launch may hold fewer than 2^32 work-items: the positions are encoded in slices)
+  constexpr int64_t SLICE = (int64_t)1 << 24;
+  for (int64_t p0 = 0; p0 < N; p0 += SLICE) {
+    a.p0 = p0;
+    const unsigned grid = (unsigned)((std::min(SLICE, N - p0) + 3) / 4);
     const size_t smem = 4 * (size_t)D * (sizeof(float) + 1);
     const int dpl = (D + 63) / 64;
     if (dpl <= 2) hipLaunchKernelGGL(encode_kernel<2>, dim3(grid), dim3(256), smem, st, a);

@@ -39,6 +39,14 @@ def check_built_index(out: dict, X: np.ndarray, B: int, metric: str = "l2", eps0
     cid = np.repeat(np.arange(nlist), counts)
     rows = ids[real]
     Xr = X[rows].astype(np.float64) @ P
+    # every list holds its vectors in ascending id order (the grouping is stable) ...
+    for c in range(nlist):
+        assert np.all(np.diff(rows[off[c]:off[c + 1]]) > 0), c
+    # ... and every vector sits in the list of its nearest centroid (scores are fp32 on the device: a near-tie may
+    # fall either way)
+    d2 = (Xr * Xr).sum(1)[:, None] + (C_rot * C_rot).sum(1)[None, :] - 2.0 * Xr @ C_rot.T
+    best = d2.min(axis=1)
+    assert np.all(d2[np.arange(n), cid] <= best + 1e-5 * (np.abs(best) + (Xr * Xr).sum(1))), "assignment"
     res = Xr - C_rot[cid]
     r = np.linalg.norm(res, axis=1)
     o_rot = res / np.maximum(r, 1e-300)[:, None]
