@@ -1,5 +1,5 @@
 """Checks of a built index (arrays in the layout of rabitq_index_desc) against the oracle's
-exact encoder and factor formulas.  Shared by the CPU and GPU builder tests."""
+exact encoder and factor formulas, for the device builder's tests."""
 import numpy as np
 
 from oracle import build
