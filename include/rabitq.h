@@ -140,7 +140,9 @@ int rabitq_index_free(rabitq_index_t index);
  *   out_dists device, [nq*k] fp32: L2 -> estimated squared distance ascending (not
  *             clamped at 0); IP -> estimated inner product descending; +inf / -inf
  *             beside id -1
- * The handle's workspace grows on demand (growth synchronises the device).
+ * The handle's workspace grows on demand (growth synchronises the device).  A batch whose
+ * workspace would exceed 16 GiB (or the "max_batch" option) is searched in consecutive
+ * sub-batches on `stream` through one workspace; results do not depend on the split.
  * Errors: RABITQ_EINVAL (null pointer with nq > 0, nq < 0, k < 1 or k > RABITQ_MAX_K,
  * nprobe < 1 or > min(nlist, RABITQ_MAX_NPROBE)), RABITQ_ENOMEM, RABITQ_EHIP.
  * nq == 0 succeeds and does nothing.
@@ -157,6 +159,8 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *   "overlap" 1 (default): inside a search the pair lists and the scan's work-item table are built on a second
  *             stream owned by the handle (default priority), beside the threshold seeding; the scan kernel waits
  *             for both and everything joins the caller's stream again before the call returns to it.  0: one stream.
+ *   "max_batch" n: rabitq_search passes at most n queries through the pipeline at a time (0, the default:
+ *             as many as keep the workspace under 16 GiB, at least 256).
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per
  *             wavefront; 1: the same integer inner products on the matrix cores (the sign
  *             bits of a tile are expanded to int8 once and contracted against 16 queries'

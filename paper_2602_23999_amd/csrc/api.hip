@@ -115,6 +115,20 @@ static int ensure_workspace(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   return RABITQ_OK;
 }
 
+// Largest number of queries one pass may take: the "max_batch" option, else as many as keep the per-query part
+// of the workspace (coarse scores, pair arrays, candidate keys, query representation) under WORKSPACE_BUDGET
+// bytes, and never so many that the pair index leaves 31 bits.
+constexpr int64_t WORKSPACE_BUDGET = (int64_t)16 << 30;
+static int64_t search_batch_limit(const rabitq_index* ix, int k, int nprobe) {
+  int cap = 1;
+  while (cap < k + TILE) cap <<= 1;
+  const int64_t per_query = (int64_t)ix->nlist * 4 + (int64_t)nprobe * ((int64_t)cap * 8 + 20) +
+                            (int64_t)ix->dim * 10 + (int64_t)ix->nlist / 4 + 64;
+  int64_t lim = std::max<int64_t>(256, WORKSPACE_BUDGET / per_query);
+  if (ix->max_batch > 0) lim = ix->max_batch;
+  return std::max<int64_t>(1, std::min<int64_t>(lim, 0x7fffffff / nprobe));
+}
+
 
 // second stream (default priority) and fork / join events of a handle; called once when the handle is made
 static int init_streams(rabitq_index* ix) {
@@ -321,6 +335,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!std::strcmp(name, "prune") && (value == 0 || value == 1)) { ix->prune = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 3) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "max_batch") && value >= 0 && value <= 0x7fffffff) { ix->max_batch = value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
     ix->prof_mask = (unsigned)value;
     ix->prof_used = 0;
@@ -499,17 +514,13 @@ int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* ca
   return launch_merge(cand_keys, cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, (hipStream_t)stream);
 }
 
-int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
-                  float* out_dists, void* stream) {
-  int rc = check_common(ix, nq, "search");
-  if (rc) return rc;
-  if ((rc = check_k_nprobe(ix, k, nprobe, "search"))) return rc;
-  if (nq == 0) return RABITQ_OK;
-  if (!queries || !out_ids || !out_dists) { set_error("search: null pointer"); return RABITQ_EINVAL; }
-  if (nq * nprobe > 0x7fffffff) { set_error("search: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
-  if ((rc = ensure_workspace(ix, nq, nprobe, k))) return rc;
+}  // extern "C"
+
+// One pass of the whole path over at most ix->ws.cap_nq queries (the workspace is already large enough).
+static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
+                        float* out_dists, hipStream_t st) {
+  int rc;
   Workspace& w = ix->ws;
-  hipStream_t st = (hipStream_t)stream;
   rabitq_index::EventSet* ev = nullptr;  // event set of this call when it is being recorded
   if (ix->prof_used < ix->prof_limit) ev = &ix->prof_sets[ix->prof_used++];
   // stage s runs between its begin and end events, both recorded on the stream the stage is put on
@@ -551,6 +562,28 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
     return rc;
   RQ_STAGE(8, st, launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
 #undef RQ_STAGE
+  return RABITQ_OK;
+}
+
+extern "C" {
+
+int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
+                  float* out_dists, void* stream) {
+  int rc = check_common(ix, nq, "search");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "search"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!queries || !out_ids || !out_dists) { set_error("search: null pointer"); return RABITQ_EINVAL; }
+  // Queries are independent of one another, so a batch whose workspace would be large is searched in
+  // consecutive sub-batches through one workspace; the results do not depend on the split.
+  const int64_t step = std::min(nq, search_batch_limit(ix, k, nprobe));
+  if ((rc = ensure_workspace(ix, step, nprobe, k))) return rc;
+  for (int64_t s0 = 0; s0 < nq; s0 += step) {
+    const int64_t m = std::min(step, nq - s0);
+    if ((rc = search_batch(ix, queries + s0 * ix->dim, m, k, nprobe, out_ids + s0 * k, out_dists + s0 * k,
+                           (hipStream_t)stream)))
+      return rc;
+  }
   return RABITQ_OK;
 }
 

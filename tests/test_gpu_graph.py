@@ -64,3 +64,23 @@ def test_second_stream_does_not_change_results(name):
     ms, calls = gi.stage_ms()
     gi.set_option("profile", 0)
     assert calls == 2 and len(ms) == 9 and all(v > 0 for v in ms.values())
+
+
+@pytest.mark.parametrize("name,limit", [("l2_128_b4", 7), ("l2_128_b4", 64), ("l2_96_b3_k100", 33), ("ragged_b2", 1)])
+def test_sub_batches_do_not_change_results(name, limit):
+    # "max_batch": a large batch goes through the pipeline in consecutive sub-batches of one workspace
+    c = case(name)
+    gi, k, nprobe = c["gi"], c["k"], c["nprobe"]
+    Q = torch.from_numpy(c["Q"]).cuda()
+    ref_ids, ref_d = gi.search(Q, k, nprobe)
+    torch.cuda.synchronize()
+    gi.set_option("max_batch", limit)
+    try:
+        for rep in range(2):
+            ids, d = gi.search(Q, k, nprobe)
+            torch.cuda.synchronize()
+            assert torch.equal(ids, ref_ids) and torch.equal(d, ref_d)
+    finally:
+        gi.set_option("max_batch", 0)
+    ids, d = gi.search(Q, k, nprobe)
+    assert torch.equal(ids, ref_ids) and torch.equal(d, ref_d)
