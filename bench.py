@@ -23,6 +23,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # integer vector rate of the chip: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-operations per second
+MFMA_I8_PEAK_TOPS = 5000.0   # dense int8 matrix-core peak of MI355X, TOP/s
 ALU_PEAK_TOPS = 256 * 4 * 16 * 2.4e9 / 1e12
 
 
@@ -350,6 +351,16 @@ def main():
                              "frac": achieved / HBM_PEAK_GBS,
                              "note": "above 1 because the launch is cache-served; the HBM-bound regime is measured by "
                                      "bench.py --stream-scan"}}
+    if impl == 1:
+        # the matrix-core scan contracts sign bytes with the int8 query: 2 D integer operations per evaluation on
+        # v_mfma_i32_16x16x64_i8, priced against the dense int8 peak
+        mfma_ops = qv * 2 * w.dim
+        mfma_achieved = mfma_ops / (scan_ms * 1e-3) / 1e12
+        roofline.update({"bound": "mfma", "achieved": mfma_achieved, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s (int8)",
+                         "frac": mfma_achieved / MFMA_I8_PEAK_TOPS, "algorithmic_ops_per_launch": mfma_ops,
+                         "alu_view": {"lane_ops_per_launch": alu_ops, "achieved_tops": alu_achieved,
+                                      "peak_tops": ALU_PEAK_TOPS,
+                                      "note": "what the popcount formulation of the same evaluations would need"}})
     res = {
         "metric": "queries/sec at recall@10~0.95 (1 GPU); code-scan HBM GB/s vs peak",
         "value": qps, "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
