@@ -102,8 +102,11 @@ int rabitq_index_upload(const rabitq_index_desc* desc, rabitq_index_t* out, void
  * Lloyd) runs in the rotated space on a training subset, every vector is assigned to its
  * nearest centroid, normalised with respect to it, and quantised by the two-phase grid
  * search over the rescaling factor (N_coarse = 64 samples over [0, m_B*2^(B-1)/max|o'|] with
- * m_B = 6, 4.5, 2.5 for B = 2, 3, 4 and 1.5 above, then N_fine = 32 around the best); codes, factors and ids are written in the layout above.
- * Deterministic: no order-dependent atomics anywhere.
+ * m_B = 6, 4.5, 2.5 for B = 2, 3, 4 and 1.5 above, then N_fine = 32 around the best); codes,
+ * factors and ids are written in the layout above, every list in ascending id order.
+ * Deterministic: no order-dependent atomics anywhere.  Temporary device memory, freed before
+ * the call returns: a rotated copy of the data (n*D floats), the training subset, 3n words
+ * of assignments and list members and at most 1024*nlist counters.
  *   data: device, [n*D] fp32 row-major raw vectors (not modified)
  * The training subset is taken at a fixed stride through the data and the initial centroids
  * at a fixed stride through the training subset (shuffle the data first if its order is not
