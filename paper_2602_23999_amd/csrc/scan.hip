@@ -64,18 +64,40 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
   float* qf = reinterpret_cast<float*>(out + kpad);
   _Float16* lut_s = reinterpret_cast<_Float16*>(qf + a.D);
   __shared__ SelectScratch sh;
-  __shared__ int s_rank;
+  __shared__ int s_rank, s_t0, s_t1;
+  __shared__ float s_G;
   __shared__ uint32_t s_max;
 
   const int64_t q = blockIdx.x;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  if (tid == 0) {
-    int r = -1;
-    for (int j = 0; j < a.nprobe; ++j) {
-      if (a.cluster_size[a.probe_ids[q * a.nprobe + j]] >= a.k) { r = j; break; }
+  if (wave == 0) {
+    // lane j looks at probe j: size, coarse term and tile range of all probes are fetched at once and the first
+    // probe with at least k vectors is taken from its lane
+    int r = -1, to0_ = 0, to1_ = 0;
+    float g_ = 0.f;
+    for (int b = 0; b < a.nprobe && r < 0; b += 64) {
+      const int j = b + lane;
+      const bool in = j < a.nprobe;
+      const int pid = in ? a.probe_ids[q * a.nprobe + j] : 0;
+      const float g = in ? a.probe_G[q * a.nprobe + j] : 0.f;
+      const int sz = in ? a.cluster_size[pid] : 0;
+      const int to0 = in ? a.tile_off[pid] : 0, to1 = in ? a.tile_off[pid + 1] : 0;
+      const uint64_t mk = __ballot(in && sz >= a.k);
+      if (mk != 0ull) {
+        const int l = __ffsll((unsigned long long)mk) - 1;
+        r = b + l;
+        g_ = __shfl(g, l, 64);
+        to0_ = __shfl(to0, l, 64);
+        to1_ = __shfl(to1, l, 64);
+      }
     }
-    s_rank = r;
-    s_max = 0u;
+    if (lane == 0) {
+      s_rank = r;
+      s_G = g_;
+      s_t0 = to0_;
+      s_t1 = to1_;
+      s_max = 0u;
+    }
   }
   for (int i = tid; i < kpad; i += 256) best[i] = KEY_NONE;
   if (F > 0) stage_query(qf, a.q_stage + q * a.D, a.D, tid, 256);
@@ -86,14 +108,12 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
     if (tid == 0) a.tau_out[q] = 3.402823466e+38f;
     return;
   }
-  const int64_t p = q * a.nprobe + rank;
-  const int c = a.probe_ids[p];
-  const float G = a.probe_G[p];
+  const float G = s_G;
   const float dl = a.delta[q];
   const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const float hsq = 0.5f * a.sum_q[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
-  const int t0 = a.tile_off[c], t1 = a.tile_off[c + 1];
+  const int t0 = s_t0, t1 = s_t1;
 
   for (int tb = t0; tb < t1; tb += SEED_CHUNK_TILES) {
     const int nt = min(SEED_CHUNK_TILES, t1 - tb);
@@ -158,25 +178,34 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int64_t q = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
   if (q >= nq) return;
-  int rank = -1;
+  // Lane j looks at probe j: everything the chosen probe contributes (cluster, coarse term, tile range) is fetched
+  // for all probes at once and read from the chosen lane, so the walk to the first tile is two dependent loads deep.
+  int rank = -1, t0 = 0, t1 = 0;
+  float G = 0.f;
   for (int b = 0; b < a.nprobe && rank < 0; b += 64) {
     const int j = b + lane;
-    const bool ok = j < a.nprobe && a.cluster_size[a.probe_ids[q * a.nprobe + j]] >= a.k;
-    const uint64_t m = __ballot(ok);
-    if (m != 0ull) rank = b + __ffsll((unsigned long long)m) - 1;
+    const bool in = j < a.nprobe;
+    const int pid = in ? a.probe_ids[q * a.nprobe + j] : 0;
+    const float g = in ? a.probe_G[q * a.nprobe + j] : 0.f;
+    const int sz = in ? a.cluster_size[pid] : 0;
+    const int to0 = in ? a.tile_off[pid] : 0, to1 = in ? a.tile_off[pid + 1] : 0;
+    const uint64_t m = __ballot(in && sz >= a.k);
+    if (m != 0ull) {
+      const int l = __ffsll((unsigned long long)m) - 1;
+      rank = b + l;
+      G = __shfl(g, l, 64);
+      t0 = __shfl(to0, l, 64);  // positions in the keys are relative to the cluster's first tile
+      t1 = __shfl(to1, l, 64);
+    }
   }
   if (rank < 0) {
     if (lane == 0) a.tau_out[q] = 3.402823466e+38f;
     return;
   }
-  const int64_t p = q * a.nprobe + rank;
-  const int c = a.probe_ids[p];
-  const float G = a.probe_G[p];
   const float dl = a.delta[q];
   const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
-  const int t0 = a.tile_off[c];  // positions in the keys are relative to the cluster's first tile
-  int tw0 = t0, t1 = a.tile_off[c + 1];
+  int tw0 = t0;
   if (SPLIT) {  // this wavefront's quarter of the tiles (possibly empty)
     const int per = (t1 - t0 + 3) >> 2;
     tw0 = min(t0 + wave * per, t1);
