@@ -175,12 +175,19 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 template <int W, int F, bool SPLIT>
 __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) {
   __shared__ uint64_t s_lists[SPLIT ? 3 * 64 : 1];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int64_t q = SPLIT ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave;
+  // (the wavefront index is the same in all lanes: saying so lets everything indexed by the query be fetched
+  // through the scalar cache)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of queries, so that
+  // neighbouring queries (which the caller may have grouped by nearest list) share one L2
+  // (the grid is the number of workgroups rounded up to a multiple of 8)
+  const int per = (int)(gridDim.x >> 3);
+  const int blk = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  const int64_t q = SPLIT ? (int64_t)blk : (int64_t)blk * 4 + wave;
   if (q >= nq) return;
   // Lane j looks at probe j: everything the chosen probe contributes (cluster, coarse term, tile range) is fetched
   // for all probes at once and read from the chosen lane, so the walk to the first tile is two dependent loads deep.
-  int rank = -1, t0 = 0, t1 = 0;
+  int rank = -1, t0 = 0, t1 = 0, n_c = 0;
   float G = 0.f;
   for (int b = 0; b < a.nprobe && rank < 0; b += 64) {
     const int j = b + lane;
@@ -196,12 +203,18 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
       G = __shfl(g, l, 64);
       t0 = __shfl(to0, l, 64);  // positions in the keys are relative to the cluster's first tile
       t1 = __shfl(to1, l, 64);
+      n_c = __shfl(sz, l, 64);
     }
   }
   if (rank < 0) {
     if (lane == 0) a.tau_out[q] = 3.402823466e+38f;
     return;
   }
+  // (the same in all lanes)
+  t0 = __builtin_amdgcn_readfirstlane(t0);
+  t1 = __builtin_amdgcn_readfirstlane(t1);
+  n_c = __builtin_amdgcn_readfirstlane(n_c);
+  G = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(G)));
   const float dl = a.delta[q];
   const float be = 0.5f * dl * (float)a.sum_qhat[q];
   const_u32_ptr pl = (const_u32_ptr)(a.planes + q * 4 * W);
@@ -229,7 +242,7 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
       for (int w = 0; w < W; ++w) cw[u][w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
       fa[u] = a.short_factors[((int64_t)tile * 3 + 0) * TILE + lane];
       fr[u] = a.short_factors[((int64_t)tile * 3 + 1) * TILE + lane];
-      real[u] = tb + u < t1 && a.ids[(int64_t)tile * TILE + lane] >= 0;
+      real[u] = tb + u < t1 && (tile - t0) * TILE + lane < n_c;  // slots past the cluster's last vector are padding
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -858,9 +871,10 @@ static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t 
   if (impl == 2)
     hipLaunchKernelGGL((seed_kernel<W, F, 1>), dim3((unsigned)nq), dim3(256), smem + (size_t)W * 256, st, a);
   else if (a.k <= 64 && nq <= 2048)  // few queries: four wavefronts per query
-    hipLaunchKernelGGL((seed_wave_kernel<W, F, true>), dim3((unsigned)nq), dim3(256), 0, st, a, nq);
+    hipLaunchKernelGGL((seed_wave_kernel<W, F, true>), dim3((unsigned)((nq + 7) / 8 * 8)), dim3(256), 0, st, a, nq);
   else if (a.k <= 64)
-    hipLaunchKernelGGL((seed_wave_kernel<W, F, false>), dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, a, nq);
+    hipLaunchKernelGGL((seed_wave_kernel<W, F, false>), dim3((unsigned)(((nq + 3) / 4 + 7) / 8 * 8)), dim3(256), 0, st, a,
+                       nq);
   else
     hipLaunchKernelGGL((seed_kernel<W, F, 0>), dim3((unsigned)nq), dim3(256), smem, st, a);
 }
