@@ -4,6 +4,19 @@
 
 namespace rq {
 
+// Keeps a loaded value where it is: without it the compiler moves a load whose value is only used under a
+// condition back under that condition, into a block of its own, and then waits for every such load before it
+// issues the next one.
+__device__ inline float pinned(float v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+__device__ inline uint64_t pinned(uint64_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
+
 // ---------------------------------------------------------------------------------
 // Section 3.3.3 / 3.4.1(2): 4-bit signed quantisation of q' and its bit-planes, once
 // per query.  One wavefront per query.  delta = max|q'|/7 and q'/delta use IEEE fp32
@@ -132,10 +145,15 @@ __global__ __launch_bounds__(64) void select_probes_wave_kernel(const float* __r
   const int64_t q = blockIdx.x;
   const float* row = scores + q * nlist;
   uint64_t key[R];
+  float sv[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) sv[r] = row[min(r * 64 + lane, nlist - 1)];  // unconditional: R requests in flight together
+#pragma unroll
+  for (int r = 0; r < R; ++r) sv[r] = pinned(sv[r]);
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     const int i = r * 64 + lane;
-    key[r] = (i < nlist) ? make_key(row[i], (uint32_t)i) : KEY_NONE;
+    key[r] = (i < nlist) ? make_key(sv[r], (uint32_t)i) : KEY_NONE;
   }
   const uint64_t bound = wave_kth_bound<R>(key, nprobe);
   wave_gather_selected<R>(key, bound, sel_out, npad);
@@ -169,12 +187,16 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
   // its nprobe-th key is small from the outset and few of the remaining scores have to be inserted.
   constexpr int R = 16;
   {
+    // (unconditional loads of clamped indices, all requested before the first value is touched: a load whose value
+    // is only used under a condition would otherwise be waited for before the next one is issued)
+    float sv[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) sv[r] = row[min(r * 64 + lane, nlist - 1)];
+#pragma unroll
+    for (int r = 0; r < R; ++r) sv[r] = pinned(sv[r]);
     uint32_t ord[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const int i = r * 64 + lane;
-      ord[r] = (i < nlist) ? f2ord(row[i]) : 0xffffffffu;
-    }
+    for (int r = 0; r < R; ++r) ord[r] = (r * 64 + lane < nlist) ? f2ord(sv[r]) : 0xffffffffu;
     uint32_t mo = ord[0];
     int mr = 0;
 #pragma unroll
@@ -194,10 +216,11 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
   for (int tb = R * 64; tb < nlist; tb += 512) {
     float sc[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      const int i = tb + u * 64 + lane;
-      sc[u] = (i < nlist) ? row[i] : INFINITY;
-    }
+    for (int u = 0; u < 8; ++u) sc[u] = row[min(tb + u * 64 + lane, nlist - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sc[u] = pinned(sc[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) sc[u] = (tb + u * 64 + lane < nlist) ? sc[u] : INFINITY;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       if (tb + u * 64 < nlist) {
@@ -451,10 +474,11 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(const uint64_t* __restr
     for (int e0 = 0; e0 < nmax; e0 += 4 * G) {
       uint64_t kk[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const int e = e0 + u * G + g;
-        kk[u] = (e < n) ? row[e] : KEY_NONE;
-      }
+      for (int u = 0; u < 4; ++u) kk[u] = row[min(e0 + u * G + g, cap - 1)];  // unconditional, inside the pair's region
+#pragma unroll
+      for (int u = 0; u < 4; ++u) kk[u] = pinned(kk[u]);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) kk[u] = (e0 + u * G + g < n) ? kk[u] : KEY_NONE;
       if (first) {
         // the lanes' smallest keys start the sorted list; the other keys are then offered to it
         uint64_t mn = kk[0];
