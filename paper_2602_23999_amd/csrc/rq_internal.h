@@ -115,8 +115,9 @@ int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st);
 int64_t probe_list_scratch_words(int32_t nlist, int64_t nq);
+int launch_clear_list_bitmap(int64_t nq, int nlist, uint32_t* scratch, hipStream_t st);
 int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,
-                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st);
+                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st, bool bitmap_is_clear = false);
 int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st);
 // Streams and events of one scan launch: the set-up kernels (work-item offsets, counter clearing) run on `setup`
@@ -126,7 +127,9 @@ struct ScanStreams {
   hipStream_t main = nullptr, setup = nullptr;
   hipEvent_t join = nullptr;
   hipEvent_t setup_b = nullptr, setup_e = nullptr, scan_b = nullptr, scan_e = nullptr;
+  bool counters_clear = false;  // cand_cnt was already zeroed by launch_clear_counters
 };
+int launch_clear_counters(int32_t* cand_cnt, int64_t n, hipStream_t st);
 int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
                 uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, const ScanStreams& ss);

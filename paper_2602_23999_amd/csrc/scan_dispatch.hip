@@ -94,6 +94,13 @@ static int need_lut(const rabitq_index* ix, const rabitq_query_repr& r) {
   return RABITQ_OK;
 }
 
+int launch_clear_counters(int32_t* cand_cnt, int64_t n, hipStream_t st) {
+  if (n <= 0) return RABITQ_OK;
+  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((n + 255) / 256, 4096)), dim3(256), 0, st, cand_cnt, n);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
 int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int32_t* probe_ids, const float* probe_G,
                 const float* probe_E, int64_t nq, int k, int nprobe, float* tau, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
@@ -147,8 +154,9 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
   hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
                      a.segmax, item_off);
-  hipLaunchKernelGGL(zero_i32_kernel, dim3((unsigned)std::min<int64_t>((nq * nprobe + 255) / 256, 4096)), dim3(256), 0, sst,
-                     cand_cnt, nq * nprobe);
+  if (!ss.counters_clear) {
+    if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
+  }
   if (ss.setup_e) RQ_HIP(hipEventRecord(ss.setup_e, sst));
   if (sst != st) {
     RQ_HIP(hipEventRecord(ss.join, sst));

@@ -351,17 +351,27 @@ int64_t probe_list_scratch_words(int32_t nlist, int64_t nq) {
   return 2 * (int64_t)nlist * qwords + nlist;
 }
 
+// step 1 on its own: it needs no probes, so a search can clear the bitmap while the probes are still being computed
+int launch_clear_list_bitmap(int64_t nq, int nlist, uint32_t* scratch, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const int64_t bm_words = (int64_t)nlist * ((nq + 31) / 32);
+  const unsigned g1 = (unsigned)std::min<int64_t>((bm_words + 255) / 256, 4096);
+  hipLaunchKernelGGL(fill_u32_kernel, dim3(g1), dim3(256), 0, st, scratch, bm_words, 0u);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
 int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,
-                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st) {
+                       int32_t* pair_ids, uint32_t* scratch, hipStream_t st, bool bitmap_is_clear) {
   if (nq <= 0) return RABITQ_OK;
   const int qwords = (int)((nq + 31) / 32);
   const int64_t npairs = nq * nprobe;
   uint32_t* bitmap = scratch;
   uint32_t* word_rank = scratch + (int64_t)nlist * qwords;
   uint32_t* total = word_rank + (int64_t)nlist * qwords;
-  const int64_t bm_words = (int64_t)nlist * qwords;
-  const unsigned g1 = (unsigned)std::min<int64_t>((bm_words + 255) / 256, 4096);
-  hipLaunchKernelGGL(fill_u32_kernel, dim3(g1), dim3(256), 0, st, bitmap, bm_words, 0u);
+  if (!bitmap_is_clear) {
+    if (int rc = launch_clear_list_bitmap(nq, nlist, scratch, st)) return rc;
+  }
   const unsigned g2 = (unsigned)std::min<int64_t>((npairs + 255) / 256, 8192);
   hipLaunchKernelGGL(bitmap_set_kernel, dim3(g2), dim3(256), 0, st, probe_ids, npairs, nprobe, qwords, bitmap);
   hipLaunchKernelGGL(row_rank_kernel, dim3(nlist), dim3(64), 0, st, bitmap, qwords, word_rank, total);
