@@ -307,15 +307,13 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
     const int sidx = base + grp;
     const uint64_t skey = shfl_u64(top.v, min(sidx, 63));
     const bool valid = sidx < m && skey != KEY_NONE;
-    float part = 0.f;
-    int64_t slot = 0;
-    if (valid) {
-      slot = (int64_t)t0 * TILE + (uint32_t)skey;
-      part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + q * a.D, t);
-    }
+    // nothing here is fetched under a condition (an absent seed reads the cluster's first slot instead), so the
+    // code words and the factors of a round are requested together
+    const int64_t slot = (int64_t)t0 * TILE + (valid ? (uint32_t)skey : 0u);
+    const float2 lf = *reinterpret_cast<const float2*>(a.long_factors + 2 * slot);
+    const float part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + q * a.D, t);
     const float ip = group_sum<GL>(part);
-    float eB = 0.f;
-    if (valid) eB = G + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - csq);
+    const float eB = G + lf.x + lf.y * (ip - csq);
     // seed base + g was refined by lanes g*GL ..; hand its estimate to lane base + g
     const int g = (lane - base) & (NS - 1);
     const float mine = __shfl(eB, g * GL, 64);
