@@ -484,11 +484,10 @@ __global__ __launch_bounds__(256) void merge_wave_kernel(const uint64_t* __restr
     for (int e0 = 0; e0 < nmax; e0 += 4 * G) {
       uint64_t kk[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) kk[u] = row[min(e0 + u * G + g, cap - 1)];  // unconditional, inside the pair's region
-#pragma unroll
-      for (int u = 0; u < 4; ++u) kk[u] = pinned(kk[u]);
-#pragma unroll
-      for (int u = 0; u < 4; ++u) kk[u] = (e0 + u * G + g < n) ? kk[u] : KEY_NONE;
+      for (int u = 0; u < 4; ++u) {
+        const int e = e0 + u * G + g;
+        kk[u] = (e < n) ? row[e] : KEY_NONE;  // (lists differ in length: reading past a short one would only add traffic)
+      }
       if (first) {
         // the lanes' smallest keys start the sorted list; the other keys are then offered to it
         uint64_t mn = kk[0];
