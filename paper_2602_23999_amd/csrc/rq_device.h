@@ -296,6 +296,18 @@ __device__ inline uint64_t readlane_u64(uint64_t v, int src) {  // src must be w
   return ((uint64_t)hi << 32) | lo;
 }
 
+// Keeps a loaded value where it is: without it the compiler moves a load whose value is only used under a
+// condition back under that condition, into a block of its own, and then waits for every such load before it
+// issues the next one.
+__device__ inline float pinned(float v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+__device__ inline uint64_t pinned(uint64_t v) {
+  asm volatile("" : "+v"(v));
+  return v;
+}
+
 struct WaveTopK {
   uint64_t v;  // lane l: l-th smallest key so far (KEY_NONE where there is none yet)
 

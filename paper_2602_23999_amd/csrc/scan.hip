@@ -777,6 +777,16 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
     }
     const int tile = tb + wave;
     if (tile < t1) {
+      // the factors of the lane's four vectors are requested with the code words, ahead of the matrix
+      // instructions (fetched where they are used, each column block would wait for its own three loads)
+      float fa4[4], fr4[4], fe4[4];
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
+        const int v = 16 * cb + lj;
+        fa4[cb] = a.short_factors[((int64_t)tile * 3 + 0) * TILE + v];
+        fr4[cb] = a.short_factors[((int64_t)tile * 3 + 1) * TILE + v];
+        fe4[cb] = a.short_factors[((int64_t)tile * 3 + 2) * TILE + v];
+      }
       // inner products: 4 column blocks of 16 vectors x 16 queries
       v4i acc[4];
 #pragma unroll
@@ -793,10 +803,14 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
       }
 #pragma unroll
       for (int cb = 0; cb < 4; ++cb) {
+        fa4[cb] = pinned(fa4[cb]);
+        fr4[cb] = pinned(fr4[cb]);
+        fe4[cb] = pinned(fe4[cb]);
+      }
+#pragma unroll
+      for (int cb = 0; cb < 4; ++cb) {
         const int v = 16 * cb + lj;
-        const float fa = a.short_factors[((int64_t)tile * 3 + 0) * TILE + v];
-        const float fr = a.short_factors[((int64_t)tile * 3 + 1) * TILE + v];
-        const float fe = a.short_factors[((int64_t)tile * 3 + 2) * TILE + v];
+        const float fa = fa4[cb], fr = fr4[cb], fe = fe4[cb];
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
           const int I = acc[cb][r];

@@ -4,18 +4,6 @@
 
 namespace rq {
 
-// Keeps a loaded value where it is: without it the compiler moves a load whose value is only used under a
-// condition back under that condition, into a block of its own, and then waits for every such load before it
-// issues the next one.
-__device__ inline float pinned(float v) {
-  asm volatile("" : "+v"(v));
-  return v;
-}
-__device__ inline uint64_t pinned(uint64_t v) {
-  asm volatile("" : "+v"(v));
-  return v;
-}
-
 
 // ---------------------------------------------------------------------------------
 // Section 3.3.3 / 3.4.1(2): 4-bit signed quantisation of q' and its bit-planes, once
