@@ -12,7 +12,7 @@ Conventions
 * ``B`` = total bits per dimension, code ``u in {0..2^B-1}^D``, grid point
   ``x = u - c_B`` with ``c_B = (2^B-1)/2`` (Eq. (1)).
 * 1-bit code ``u_b`` = most significant bit of ``u``; ex-code = remaining bits
-  (Section 3.1, "Index build").
+  (Section 3.1, paragraph on the index build).
 
 Parity status
 -------------
@@ -146,9 +146,10 @@ def code_cosine(u: np.ndarray, o_rot: np.ndarray, B: int) -> np.ndarray:
 
 
 # --------------------------------------------------------------------------
-# Per-vector factors (Section 2.2 last paragraph names "the dot product between
-# the code and q'" and "some factors"; Section 3.4.3 splits them into short and
-# long factors.  The formulas below are derived from Eq. (1)-(3).)
+# Per-vector factors (the last paragraph of Section 2.2 says that the estimate
+# needs the code's inner product with q' and a few stored factors, without
+# giving them; Section 3.4.3 splits them into short and long factors.  The
+# formulas below are derived from Eq. (1)-(3).)
 # --------------------------------------------------------------------------
 def vector_factors(x: np.ndarray, o_rot: np.ndarray, c_rot: np.ndarray,
                    r: np.ndarray, metric: str, eps0: float,
@@ -195,7 +196,7 @@ def vector_factors(x: np.ndarray, o_rot: np.ndarray, c_rot: np.ndarray,
 
 
 # --------------------------------------------------------------------------
-# Whole index (Section 3.1 "Index build", Section 3.4.3 layout)
+# Whole index (Section 3.1 on the index build, Section 3.4.3 layout)
 # --------------------------------------------------------------------------
 def build_index(X: np.ndarray, nlist: int, total_bits: int, metric: str = "l2",
                 seed_rotation: int = 7, seed_kmeans: int = 99, kmeans_iters: int = 10,

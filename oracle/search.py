@@ -19,9 +19,9 @@ Readings taken where the paper is silent
   example); ``<x_b, q'>`` is the fp32 sum of the looked-up entries in ascending
   block order.  Both are precision decisions of the variant, so they are part of
   its definition here.  The query is not quantised in this variant.
-* Refinement uses the unquantised fp32 ``q'`` (Section 3.4.2 says only "the
-  query").
-* Threshold (Section 3.3.4 "current K-th best distance"): the running value is
+* Refinement uses the unquantised fp32 ``q'`` (Section 3.4.2 does not say in
+  which precision the query enters).
+* Threshold (Section 3.3.4: the K-th best distance found so far): the running value is
   order dependent on a parallel machine, so it is fixed per query before the
   scan, as the K-th best distance after a first look at the nearest cluster.  In
   the query's nearest probed cluster holding at least K vectors, the
