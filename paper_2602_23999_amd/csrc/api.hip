@@ -531,8 +531,10 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
     if ((rc = (call)) != RABITQ_OK) return rc;                                  \
     if (on_) RQ_HIP(hipEventRecord(ev->e[s], (stream_)));                       \
   } while (0)
-  // What needs no probes is cleared on the second stream while the probes are being computed.
-  if (ix->overlap) {
+  // What needs no probes is cleared on the second stream while the probes are being computed (a large batch only:
+  // for a small one the clears take no time and the extra dependency between the streams would only add latency).
+  const bool early_clear = ix->overlap && nq >= 2048;
+  if (early_clear) {
     RQ_HIP(hipEventRecord(ix->ev_fork, st));
     RQ_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
     if ((rc = launch_clear_list_bitmap(nq, ix->nlist, w.list_scratch, ix->side)) != RABITQ_OK) return rc;
@@ -555,7 +557,7 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
     RQ_HIP(hipStreamWaitEvent(lst, ix->ev_fork, 0));
   }
   RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst,
-                                      ix->overlap != 0));
+                                      early_clear));
   if (ix->prune) {
     RQ_STAGE(5, st, launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
   } else {
@@ -563,7 +565,7 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
   }
   ScanStreams ss;
   ss.main = st; ss.setup = lst; ss.join = ix->ev_join;
-  ss.counters_clear = ix->overlap != 0;
+  ss.counters_clear = early_clear;
   if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; }
   if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; }
   if ((rc = launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids, w.tau, nq, k, nprobe, w.cand_keys,
