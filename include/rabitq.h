@@ -159,9 +159,10 @@ int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_
  *   "profile" n: see rabitq_stage_ms.
  *   "profile_stages" m: bit s of m (1..511, default all) selects whether stage s of rabitq_stage_ms is
  *             recorded; unrecorded stages report 0.  Recording costs two event records per stage and search.
- *   "overlap" 1 (default): inside a search the pair lists and the scan's work-item table are built on a second
- *             stream owned by the handle (default priority), beside the threshold seeding; the scan kernel waits
- *             for both and everything joins the caller's stream again before the call returns to it.  0: one stream.
+ *   "overlap" 1 (default): inside a search of 256 or more queries the pair lists and the scan's work-item table
+ *             are built on a second stream owned by the handle (default priority), beside the threshold seeding;
+ *             the scan kernel waits for both and everything joins the caller's stream again before the call
+ *             returns to it.  Smaller batches stay on one stream.  0: always one stream.
  *   "max_batch" n: rabitq_search passes at most n queries through the pipeline at a time (0, the default:
  *             as many as keep the workspace under 16 GiB, at least 256).
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per

@@ -533,7 +533,10 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
   } while (0)
   // What needs no probes is cleared on the second stream while the probes are being computed (a large batch only:
   // for a small one the clears take no time and the extra dependency between the streams would only add latency).
-  const bool early_clear = ix->overlap && nq >= 2048;
+  // The second stream pays off when the kernels are long enough: its events cost the host about 0.08 ms per search,
+  // more than a whole search of a few queries takes on the GPU.
+  const bool side_stream = ix->overlap && nq >= 256;
+  const bool early_clear = side_stream && nq >= 2048;
   if (early_clear) {
     RQ_HIP(hipEventRecord(ix->ev_fork, st));
     RQ_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
@@ -551,7 +554,7 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
   // The pair lists and the scan's work-item table depend on the probes only, and so does the threshold seeding:
   // the former run on the handle's second stream beside the latter, and the scan kernel waits for both.
   hipStream_t lst = st;
-  if (ix->overlap) {
+  if (side_stream) {
     lst = ix->side;
     RQ_HIP(hipEventRecord(ix->ev_fork, st));
     RQ_HIP(hipStreamWaitEvent(lst, ix->ev_fork, 0));

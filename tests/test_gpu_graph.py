@@ -12,11 +12,19 @@ from test_gpu_parity import case
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name,nq", [("l2_128_b4", 1), ("l2_128_b4", 96), ("tiny_b1", 100), ("l2_96_b3_k100", 16)])
+def tiled(Q: np.ndarray, nq: int) -> np.ndarray:
+    """nq queries: the case's own, repeated as often as needed (batches of 256 queries and more use the handle's
+    second stream, batches of 2048 and more also clear their scratch on it ahead of time)."""
+    reps = -(-nq // len(Q))
+    return np.tile(Q, (reps, 1))[:nq].copy()
+
+
+@pytest.mark.parametrize("name,nq", [("l2_128_b4", 1), ("l2_128_b4", 96), ("tiny_b1", 100), ("l2_96_b3_k100", 16),
+                                     ("l2_128_b4", 300), ("tiny_b1", 2500), ("l2_96_b3_k100", 2100)])
 def test_captured_search_replays_like_eager(name, nq):
     c = case(name)
     gi, k, nprobe = c["gi"], c["k"], c["nprobe"]
-    Q = torch.from_numpy(c["Q"][:nq].copy()).cuda()
+    Q = torch.from_numpy(tiled(c["Q"], nq)).cuda()
     q_in = Q.clone()
     ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
     dist = torch.empty((nq, k), dtype=torch.float32, device="cuda")
@@ -46,7 +54,8 @@ def test_second_stream_does_not_change_results(name):
     # "overlap": list building and scan set-up on the handle's second stream beside the seeding
     c = case(name)
     gi, k, nprobe = c["gi"], c["k"], c["nprobe"]
-    Q = torch.from_numpy(c["Q"]).cuda()
+    base = len(c["Q"])
+    Q = torch.from_numpy(tiled(c["Q"], 2048 + base)).cuda()   # large enough for the second stream and the early clears
     out = {}
     for mode in (1, 0, 1):
         gi.set_option("overlap", mode)
@@ -58,6 +67,10 @@ def test_second_stream_does_not_change_results(name):
     ref = out[0][0]
     for ids, d in out[1]:
         assert torch.equal(ids, ref[0]) and torch.equal(d, ref[1])
+    # the repeated queries give the answers of the small batch (which stays on one stream)
+    s_ids, s_d = gi.search(Q[:base].contiguous(), k, nprobe)
+    for r0 in range(0, Q.shape[0] - base + 1, base):
+        assert torch.equal(ref[0][r0:r0 + base], s_ids) and torch.equal(ref[1][r0:r0 + base], s_d)
     # per-stage timings are still reported for every stage
     gi.set_option("profile", 2)
     gi.search(Q, k, nprobe); gi.search(Q, k, nprobe)
