@@ -234,6 +234,9 @@ def main():
     ap.add_argument("--bits", type=int, default=0,
                     help="override the workload's total bits per dimension (1..8): shows where the recall ceiling of "
                          "the code size lies; the default run keeps the size the workload states")
+    ap.add_argument("--eps0", type=float, default=1.9,
+                    help="multiplier of the 1-bit error bound the index is built with (the filter keeps a vector when "
+                         "its estimate minus eps0 standard errors is below the threshold)")
     ap.add_argument("--scan-impl", type=int, default=3,
                     help="0: popcount scan, 1: matrix-core scan, 2: lookup-table scan, 3 (default): the library's choice "
                          "by code width (popcount below D = 960)")
@@ -277,7 +280,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     gi = rabitq.Index.build(Xd, w.nlist, w.total_bits, P, metric=w.metric, kmeans_iters=10,
-                            train_size=max(w.nlist * 40, w.n // 10), center=(w.metric == "l2"))
+                            train_size=max(w.nlist * 40, w.n // 10), center=(w.metric == "l2"), epsilon0=args.eps0)
     torch.cuda.synchronize()
     build_s = time.perf_counter() - t0
     log(f"[bench] index build on the device: {build_s:.3f}s")
