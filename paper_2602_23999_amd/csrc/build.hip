@@ -53,9 +53,19 @@ __global__ __launch_bounds__(256) void argmin_rows_kernel(const float* __restric
   if (r >= rows) return;
   const float* row = scores + r * nlist;
   uint64_t best = KEY_NONE;
-  for (int c = lane; c < nlist; c += 64) {
-    const uint64_t key = make_key(row[c], (uint32_t)c);
-    best = key < best ? key : best;
+  // eight requests in flight (clamped indices, so that no load sits under a condition)
+  for (int c0 = lane; c0 < nlist; c0 += 8 * 64) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = row[min(c0 + u * 64, nlist - 1)];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = pinned(v[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int c = c0 + u * 64;
+      const uint64_t key = c < nlist ? make_key(v[u], (uint32_t)c) : KEY_NONE;
+      best = key < best ? key : best;
+    }
   }
   best = wave_reduce_u64(best, [](uint64_t a, uint64_t b) { return a < b ? a : b; });
   if (lane == 0) out[r] = (int32_t)(uint32_t)best;
