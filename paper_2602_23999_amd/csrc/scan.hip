@@ -426,7 +426,28 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       qs[2 * j] = Gj[j];
       qs[2 * j + 1] = a.cB * a.sum_q[q];
     }
-    if (F > 0) stage_query(qf + j * a.D, a.q_stage + q * a.D, a.D, lane, 64);
+  }
+  if (F > 0) {
+    // the rotated queries go to LDS for the refinement: every word is requested before the first one is stored
+    // (copied one after the other, each word would wait for its own round trip, 2 QW of them for D = 128)
+    constexpr int DD = 32 * W, PER = (DD + 63) / 64, JB = (PER * QW <= 16) ? QW : 1;
+#pragma unroll
+    for (int j0 = 0; j0 < QW; j0 += JB) {
+      float sv[JB][PER];
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int u = 0; u < PER; ++u) sv[jj][u] = a.q_stage[qj[j0 + jj] * DD + min(u * 64 + lane, DD - 1)];
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int u = 0; u < PER; ++u) sv[jj][u] = pinned(sv[jj][u]);
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int u = 0; u < PER; ++u)
+          if (u * 64 + lane < DD) qf[(j0 + jj) * DD + u * 64 + lane] = sv[jj][u];
+    }
   }
   __syncthreads();
 
