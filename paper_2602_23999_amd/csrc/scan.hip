@@ -417,7 +417,6 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     Sj[j] = a.sum_qhat[q];
     bej[j] = 0.5f * dlj[j] * (float)Sj[j];
     hsqj[j] = 0.5f * a.sum_q[q];
-    if (M == 1) stage_lut(lut_s + j * W * 128, a.lut + q * (int64_t)W * 128, W, lane, 64);
     tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
     cnt[j] = 0;
     if (lane == 0) {
@@ -425,6 +424,26 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       pool_cnt[j] = 0;
       qs[2 * j] = Gj[j];
       qs[2 * j + 1] = a.cB * a.sum_q[q];
+    }
+  }
+  if (M == 1) {
+    // the lookup tables of the QW queries (W * 64 dwords each) go to LDS, all words of a batch requested before the
+    // first one is stored
+    constexpr int JB = (W * QW <= 16) ? QW : 1;
+    uint32_t* d32 = reinterpret_cast<uint32_t*>(lut_s);
+#pragma unroll
+    for (int j0 = 0; j0 < QW; j0 += JB) {
+      uint32_t tv[JB][W];
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj) {
+        const uint32_t* s32 = reinterpret_cast<const uint32_t*>(a.lut + qj[j0 + jj] * (int64_t)W * 128);
+#pragma unroll
+        for (int u = 0; u < W; ++u) tv[jj][u] = s32[u * 64 + lane];
+      }
+#pragma unroll
+      for (int jj = 0; jj < JB; ++jj)
+#pragma unroll
+        for (int u = 0; u < W; ++u) d32[(j0 + jj) * W * 64 + u * 64 + lane] = tv[jj][u];
     }
   }
   if (F > 0) {
