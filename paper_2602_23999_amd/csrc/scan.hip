@@ -624,9 +624,13 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 // the popcount kernel; integer results are identical.
 // ---------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
-constexpr int MWAVES = 4;                     // wavefronts per work item (they split its tiles)
+// wavefronts per work item (they split its tiles and own QM / n of its queries each): four for short codes, two for
+// wide ones, where a tile keeps a wavefront busy for longer and the barrier after every round of tiles weighs more
+// (D = 960: 0.97 ms with four, 0.86 ms with two, 0.86 ms with one; D = 128: 0.32 / 0.38 / 0.45 ms)
+__host__ __device__ constexpr int mfma_waves(int W) { return W >= 16 ? 2 : 4; }
 constexpr int MLIST_FLUSH = 128;              // an owner list longer than this is refined before the next tiles
-constexpr int MLIST_CAP = MLIST_FLUSH + MWAVES * TILE * (QM / MWAVES);  // + what one round of tiles can add
+// + what one round of tiles can add: every wavefront a tile, 64 vectors x QM / n queries per owner
+__host__ __device__ constexpr int mlist_cap(int n) { return MLIST_FLUSH + n * TILE * (QM / n); }
 
 __device__ inline v4i expand16(uint32_t bits16) {  // 16 sign bits -> 16 bytes of 0/1
   v4i v;
@@ -677,13 +681,14 @@ __device__ inline int block_pool_compact(uint64_t* pool, int pool_n, int cnt, in
   return min(cnt, k);
 }
 
-// Work split inside the workgroup: every wavefront scans a quarter of the tiles for all 16
-// queries, but survivors are filed by OWNER: query j belongs to wavefront j % 4, which alone
+// Work split inside the workgroup of n = mfma_waves(W) wavefronts: every wavefront scans every n-th tile for all 16
+// queries, but survivors are filed by OWNER: query j belongs to wavefront j % n, which alone
 // refines them and keeps that query's pool.  Refinement therefore needs no workgroup
 // barrier; the wavefronts only meet once per round of tiles.
 template <int W, int F, bool DBG>
-__global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
+__global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs a) {
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF, KC = (W + 1) / 2;
+  constexpr int MWAVES = mfma_waves(W), MLIST_CAP = mlist_cap(MWAVES);
   constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
   extern __shared__ unsigned char smem_raw[];
   uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);          // [QM][pool]
@@ -763,7 +768,7 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
     }
   };
 
-  // F > 0: this wavefront refines its own list (queries j with j % 4 == wave) into its own pools
+  // F > 0: this wavefront refines its own list (queries j with j % MWAVES == wave) into its own pools
   auto flush_own = [&]() {
     uint32_t* list = lists + (size_t)wave * MLIST_CAP;
     const int list_cnt = s_list_cnt[wave];
@@ -786,7 +791,7 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
       }
       wave_sync();
 #pragma unroll
-      for (int rr = 0; rr < QM / MWAVES; ++rr) {  // the four pools this wavefront owns
+      for (int rr = 0; rr < QM / MWAVES; ++rr) {  // the pools this wavefront owns
         const int jj = MWAVES * rr + wave;
         const int cj = pool_cnt[jj];
         if (cj + NS > a.pool) {
@@ -807,7 +812,8 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
   for (int tb = ts; tb < t1; tb += MWAVES) {
     if (F > 0) {
       // workgroup-uniform decision (the counts were last written before the barrier below)
-      const int longest = max(max(s_list_cnt[0], s_list_cnt[1]), max(s_list_cnt[2], s_list_cnt[3]));
+      int longest = 0;
+      for (int ww = 0; ww < MWAVES; ++ww) longest = max(longest, s_list_cnt[ww]);
       if (longest > MLIST_FLUSH) {
         flush_own();
         __syncthreads();
@@ -865,9 +871,9 @@ __global__ __launch_bounds__(64 * MWAVES) void scan_mfma_kernel(ScanArgs a) {
             if (F == 0) {  // B == 1: the 1-bit estimate is the final key
               const uint64_t key = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + v]);
               if (key <= pool_kth[j]) pools[(size_t)j * a.pool + atomicAdd(&pool_cnt[j], 1)] = key;
-            } else {       // file the survivor with the owner of query j (= wavefront r)
-              const int pos = atomicAdd(&s_list_cnt[r], 1);
-              lists[(size_t)r * MLIST_CAP + pos] = ((uint32_t)j << 28) | (uint32_t)((tile - t0) * TILE + v);
+            } else {       // file the survivor with the owner of query j (= wavefront r % MWAVES)
+              const int pos = atomicAdd(&s_list_cnt[r % MWAVES], 1);
+              lists[(size_t)(r % MWAVES) * MLIST_CAP + pos] = ((uint32_t)j << 28) | (uint32_t)((tile - t0) * TILE + v);
             }
           }
         }
@@ -933,6 +939,7 @@ static void launch_seed_wf(const ScanArgs& a, int impl, int64_t nq, hipStream_t 
 
 template <int W, int F>
 static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
+  constexpr int MWAVES = mfma_waves(W), MLIST_CAP = mlist_cap(MWAVES);
   const size_t smem = (size_t)QM * a.pool * sizeof(uint64_t) +
                       QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + QM) * sizeof(int) +
                       (F > 0 ? (size_t)MWAVES * MLIST_CAP * sizeof(uint32_t) : 0);
