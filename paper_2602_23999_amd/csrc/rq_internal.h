@@ -82,8 +82,9 @@ struct rabitq_index {
 namespace rq {
 
 // The scan the handle's option selects: "by code width" takes the matrix-core kernel from D = 960 on, where it was
-// measured 2.8x faster than the popcount kernel (0.98 against 2.79 ms), and the popcount kernel below (D = 768: 22 against
-// 31 ms, D = 128: 0.30 against 0.41 ms).
+// measured 3.2x faster than the popcount kernel (0.86 against 2.79 ms), and the popcount kernel below (D = 128: 0.28
+// against 0.32 ms; at D = 768 the matrix-core kernel wins where the filter works, 4.2 against 5.8 ms, and loses where
+// nearly every vector has to be refined, 32 against 22 ms).
 inline int effective_impl(const rabitq_index* ix) { return ix->scan_impl == 3 ? (ix->W >= 30 ? 1 : 0) : ix->scan_impl; }
 
 void set_error(const std::string& s);
