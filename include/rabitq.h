@@ -235,6 +235,12 @@ int rabitq_query_prep(rabitq_index_t index, const float* q_rot, int64_t nq, cons
 int rabitq_coarse_probe(rabitq_index_t index, const float* q_rot, const float* sq_norm, int64_t nq,
                         int32_t nprobe, float* scores, int32_t* probe_ids, float* probe_G, float* probe_E,
                         void* stream);
+/* The top-nprobe selection of Section 3.3.2 has several kernels; this names the one rabitq_coarse_probe and
+ * rabitq_search launch for an index of nlist lists (so that tests can show each of them was exercised):
+ * 0 = one wavefront per query streams the score row through a register-resident sorted list (nprobe <= 64);
+ * 1, 2, 3 = one wavefront per query, whole row in registers, nlist <= 512 / 1024 / 2048 (nprobe > 64);
+ * 4 = one workgroup per query, radix select in LDS (nprobe > 64, nlist > 2048).  Negative status if out of range. */
+int32_t rabitq_probe_select_variant(int32_t nlist, int32_t nprobe);
 
 /* Section 3.3.3: regroup the (query, cluster) pairs by cluster (stable in query id).
  *   pair_off [nlist+1] i32: pairs of cluster c are pair_ids[pair_off[c] .. pair_off[c+1])

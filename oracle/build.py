@@ -179,7 +179,11 @@ def vector_factors(x: np.ndarray, o_rot: np.ndarray, c_rot: np.ndarray,
     xo_s = np.where(ok, xo, 1.0)
     a = np.clip(xo_s / xn, 0.0, 1.0)
     a_s = np.where(ok, a, 1.0)
-    spread = np.sqrt(np.maximum(1.0 - a_s * a_s, 0.0)) / (a_s * np.sqrt(D - 1.0))
+    # a code at right angles to (or pointing away from) its vector carries no information about it: the error
+    # scale is unbounded there, stated as +inf rather than obtained from a division by zero
+    pos = a_s > 0.0
+    spread = np.full(n, np.inf)
+    spread[pos] = np.sqrt(np.maximum(1.0 - a_s[pos] * a_s[pos], 0.0)) / (a_s[pos] * np.sqrt(D - 1.0))
     f = np.zeros((n, 3), dtype=np.float64)
     if metric == "l2":
         f[:, 0] = r * r + 2.0 * r * xc / xo_s

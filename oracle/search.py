@@ -250,17 +250,24 @@ class Searcher:
             return float(np.sort(self.refined(s, e, G, qr, sel))[k - 1])
         return FLT_MAX
 
-    def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False, tau=None):
+    def search(self, Q, k, nprobe, prune=True, Qr=None, detail=False, tau=None, probes=None):
         """Returns (ids [nq,k] i64, dists [nq,k] f64, info).  ``prune=False`` is
         the unpruned definition (every vector of every probed cluster is ranked by
         its final key).  ``info`` holds per-query tau, survivor counts, the probe
         lists, and the count of unpruned top-k members the filter would drop.
-        ``tau`` (optional [nq]) replaces the seeded thresholds (used by stage tests)."""
+        Stage tests may replace the outcome of an earlier step by given values: ``Qr``
+        (rotated queries), ``probes`` = (ids [nq,nprobe], G, E) in place of the cluster
+        selection, ``tau`` [nq] in place of the seeded thresholds."""
         ix = self.ix
         if Qr is None:
             Qr = rotate_queries(Q, ix["P"], ix.get("mean"))
         nq = Qr.shape[0]
-        probes, G, E = coarse_probe(Qr, ix["centroids_rot"], nprobe, self.metric)
+        if probes is None:
+            probes, G, E = coarse_probe(Qr, ix["centroids_rot"], nprobe, self.metric)
+        else:
+            probes, G, E = (np.asarray(probes[0], np.int32), np.asarray(probes[1], np.float64),
+                            np.asarray(probes[2], np.float64))
+            assert probes.shape == (nq, nprobe)
         out_ids = np.full((nq, k), -1, dtype=np.int64)
         out_d = np.full((nq, k), np.inf, dtype=np.float64)
         taus = np.full(nq, FLT_MAX)

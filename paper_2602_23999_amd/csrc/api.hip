@@ -130,11 +130,13 @@ static int64_t search_batch_limit(const rabitq_index* ix, int k, int nprobe) {
 }
 
 
-// second stream (default priority) and fork / join events of a handle; called once when the handle is made
+// second stream (default priority) and fork / join events of a handle; called once when the handle is made,
+// with the handle's device current
 static int init_streams(rabitq_index* ix) {
   RQ_HIP(hipStreamCreateWithFlags(&ix->side, hipStreamNonBlocking));
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
+  ix->seg_sorted.reserve(ix->host_tiles.size());  // so that a search never grows a host vector either
   return RABITQ_OK;
 }
 
@@ -451,6 +453,11 @@ int rabitq_coarse_probe(rabitq_index_t ix, const float* q_rot, const float* sq_n
                               probe_E, st);
 }
 
+int32_t rabitq_probe_select_variant(int32_t nlist, int32_t nprobe) {
+  if (nlist < 1 || nprobe < 1 || nprobe > nlist || nprobe > RABITQ_MAX_NPROBE) return RABITQ_EINVAL;
+  return probe_select_variant(nlist, nprobe);
+}
+
 int32_t rabitq_cand_capacity(int32_t k) {
   if (k < 1 || k > RABITQ_MAX_K) return RABITQ_EINVAL;
   int cap = 1;
@@ -516,11 +523,11 @@ int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* ca
 
 }  // extern "C"
 
-// One pass of the whole path over at most ix->ws.cap_nq queries (the workspace is already large enough).
-static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
-                        float* out_dists, hipStream_t st) {
+// One pass of the whole path over the queries `w` was sized for.  `forked` tells the caller whether the handle's
+// second stream has work that the caller's stream has not waited for yet (only possible when an error is returned).
+static int search_batch_body(rabitq_index* ix, Workspace& w, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
+                             int64_t* out_ids, float* out_dists, hipStream_t st, bool* forked) {
   int rc;
-  Workspace& w = ix->ws;
   rabitq_index::EventSet* ev = nullptr;  // event set of this call when it is being recorded
   if (ix->prof_used < ix->prof_limit) ev = &ix->prof_sets[ix->prof_used++];
   // stage s runs between its begin and end events, both recorded on the stream the stage is put on
@@ -540,6 +547,7 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
   if (early_clear) {
     RQ_HIP(hipEventRecord(ix->ev_fork, st));
     RQ_HIP(hipStreamWaitEvent(ix->side, ix->ev_fork, 0));
+    *forked = true;
     if ((rc = launch_clear_list_bitmap(nq, ix->nlist, w.list_scratch, ix->side)) != RABITQ_OK) return rc;
     if ((rc = launch_clear_counters(w.cand_cnt, nq * nprobe, ix->side)) != RABITQ_OK) return rc;
   }
@@ -558,6 +566,7 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
     lst = ix->side;
     RQ_HIP(hipEventRecord(ix->ev_fork, st));
     RQ_HIP(hipStreamWaitEvent(lst, ix->ev_fork, 0));
+    *forked = true;
   }
   RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst,
                                       early_clear));
@@ -579,6 +588,21 @@ static int search_batch(rabitq_index* ix, const float* queries, int64_t nq, int3
   return RABITQ_OK;
 }
 
+static int search_batch(rabitq_index* ix, Workspace& w, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
+                        int64_t* out_ids, float* out_dists, hipStream_t st) {
+  bool forked = false;
+  const int rc = search_batch_body(ix, w, queries, nq, k, nprobe, out_ids, out_dists, st, &forked);
+  if (rc != RABITQ_OK && forked) {
+    // An error left the second stream forked from the caller's: join it again, so that the caller's stream (and a
+    // stream capture it may be part of) ends with no work outstanding elsewhere.  The first error is the one reported.
+    const std::string first = g_err;
+    if (hipEventRecord(ix->ev_join, ix->side) == hipSuccess) (void)hipStreamWaitEvent(st, ix->ev_join, 0);
+    (void)hipGetLastError();
+    g_err = first;
+  }
+  return rc;
+}
+
 extern "C" {
 
 int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe, int64_t* out_ids,
@@ -594,7 +618,7 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   if ((rc = ensure_workspace(ix, step, nprobe, k))) return rc;
   for (int64_t s0 = 0; s0 < nq; s0 += step) {
     const int64_t m = std::min(step, nq - s0);
-    if ((rc = search_batch(ix, queries + s0 * ix->dim, m, k, nprobe, out_ids + s0 * k, out_dists + s0 * k,
+    if ((rc = search_batch(ix, ix->ws, queries + s0 * ix->dim, m, k, nprobe, out_ids + s0 * k, out_dists + s0 * k,
                            (hipStream_t)stream)))
       return rc;
   }

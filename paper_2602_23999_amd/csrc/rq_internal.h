@@ -115,6 +115,7 @@ int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int 
 int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st);
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st);
+int probe_select_variant(int nlist, int nprobe);  // which selection kernel launch_select_probes takes (see stages.hip)
 int64_t probe_list_scratch_words(int32_t nlist, int64_t nq);
 int launch_clear_list_bitmap(int64_t nq, int nlist, uint32_t* scratch, hipStream_t st);
 int launch_build_lists(const int32_t* probe_ids, int64_t nq, int nprobe, int nlist, int32_t* pair_off,

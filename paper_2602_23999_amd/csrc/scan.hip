@@ -674,6 +674,20 @@ __device__ inline int wave_pool_compact(uint64_t* pool, int pool_n, int cnt, int
   return min(cnt, k);
 }
 
+// A decision every wavefront of the workgroup must take alike, although each of them computes it from LDS counters
+// that faster wavefronts may already be advancing: the first wavefront to arrive fixes the value in `slot` (which
+// holds AGREE_UNSET) and the others adopt it.  Whoever advances a counter has taken the decision first, so the
+// value that wins was computed before any counter moved.  `mine` is wave-uniform and never AGREE_UNSET.
+constexpr uint32_t AGREE_UNSET = 0xffffffffu;
+__device__ inline uint32_t wave_agree(uint32_t* slot, uint32_t mine, int lane) {
+  uint32_t v = 0;
+  if (lane == 0) {
+    const uint32_t old = atomicCAS(slot, AGREE_UNSET, mine);
+    v = (old == AGREE_UNSET) ? mine : old;
+  }
+  return (uint32_t)__builtin_amdgcn_readfirstlane((int)v);
+}
+
 __device__ inline int block_pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
   __syncthreads();
   for (int i = cnt + (int)threadIdx.x; i < pool_n; i += (int)blockDim.x) pool[i] = KEY_NONE;
@@ -698,7 +712,8 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   int* qidx = pool_cnt + QM;                                        // [QM] query of each pair
   int* s_list_cnt = qidx + QM;                                      // [MWAVES] entries in each owner list
   int* s_out = s_list_cnt + MWAVES;                                 // [QM] first output slot of each pair
-  uint32_t* lists = reinterpret_cast<uint32_t*>(s_out + QM);        // [MWAVES][MLIST_CAP] (F > 0)
+  uint32_t* s_agree = reinterpret_cast<uint32_t*>(s_out + QM);      // [2] per-round decisions (wave_agree), by round parity
+  uint32_t* lists = s_agree + 2;                                    // [MWAVES][MLIST_CAP] (F > 0)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, lj = lane & 15, g = lane >> 4;
 
   const int n_items = a.item_off[a.nlist];
@@ -734,6 +749,7 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
       pool_cnt[lj] = 0;
     }
     if (tid < MWAVES) s_list_cnt[tid] = 0;
+    if (tid < 2) s_agree[tid] = AGREE_UNSET;
   }
   // scalars of this lane's four queries (rows 4g .. 4g+3; query 4g+r is owned by wavefront r)
   float al[4], be[4], Gr[4], Er[4], tr[4];
@@ -751,12 +767,13 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   }
   __syncthreads();
 
-  // F == 0 only: the pools are filled by all wavefronts straight from the tiles
-  auto block_compact_if_full = [&](int room) {
+  // Cuts the pools named by `mask` (bit jj = pool jj; the same in every wavefront) back to their k best.
+  // No wavefront may be adding to those pools meanwhile.
+  auto block_compact = [&](uint32_t mask) {
 #pragma unroll 1
     for (int jj = 0; jj < QM; ++jj) {
-      const int cj = pool_cnt[jj];
-      if (cj + room > a.pool) {  // workgroup-uniform: pool_cnt is read after a barrier
+      if ((mask >> jj) & 1u) {
+        const int cj = pool_cnt[jj];
         uint64_t* pool = pools + (size_t)jj * a.pool;
         const int nc = block_pool_compact(pool, a.pool, cj, a.k);
         if (tid == 0) {
@@ -809,17 +826,27 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
     if (lane == 0) s_list_cnt[wave] = 0;
   };
 
-  for (int tb = ts; tb < t1; tb += MWAVES) {
+  // pools that could not take `room` more keys (lane jj looks at pool jj); wave-uniform
+  auto full_pools = [&](int room) -> uint32_t {
+    return (uint32_t)__ballot(lane < QM && pool_cnt[min(lane, QM - 1)] + room > a.pool);
+  };
+  int round = 0;
+  for (int tb = ts; tb < t1; tb += MWAVES, round ^= 1) {
+    // Every wavefront is past the previous round's barrier here, but a faster one may already be filing this
+    // round's survivors, so the counters a slower one reads can be ahead of what its siblings saw: the decision to
+    // flush / compact (which contains barriers) is therefore agreed upon, not taken by each wavefront for itself.
+    // The slot of the other parity was last read before the previous barrier and is reset for the next round.
+    if (tid == 0) s_agree[round ^ 1] = AGREE_UNSET;
     if (F > 0) {
-      // workgroup-uniform decision (the counts were last written before the barrier below)
       int longest = 0;
       for (int ww = 0; ww < MWAVES; ++ww) longest = max(longest, s_list_cnt[ww]);
-      if (longest > MLIST_FLUSH) {
+      if (wave_agree(&s_agree[round], longest > MLIST_FLUSH ? 1u : 0u, lane)) {
         flush_own();
         __syncthreads();
       }
     } else {
-      block_compact_if_full(MWAVES * TILE);
+      const uint32_t mask = wave_agree(&s_agree[round], full_pools(MWAVES * TILE), lane);
+      if (mask) block_compact(mask);
     }
     const int tile = tb + wave;
     if (tile < t1) {
@@ -886,7 +913,8 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
     __syncthreads();
   }
   // a pool larger than the output region, or any pool of a split cluster, is cut to its k best
-  block_compact_if_full(nseg > 1 ? a.pool - a.k : a.pool - a.cand_stride);
+  // (every wavefront is past a barrier and nothing is being added any more: all see the same counters)
+  block_compact(full_pools(nseg > 1 ? a.pool - a.k : a.pool - a.cand_stride));
   // every pair reserves its part of the candidate region at once (one atomic per pair, all in flight together);
   // the wavefronts then copy the pools out, a pair each
   if (tid < np) {
@@ -941,7 +969,7 @@ template <int W, int F>
 static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   constexpr int MWAVES = mfma_waves(W), MLIST_CAP = mlist_cap(MWAVES);
   const size_t smem = (size_t)QM * a.pool * sizeof(uint64_t) +
-                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + QM) * sizeof(int) +
+                      QM * (sizeof(uint64_t) + 2 * sizeof(float) + 2 * sizeof(int)) + (MWAVES + QM + 2) * sizeof(int) +
                       (F > 0 ? (size_t)MWAVES * MLIST_CAP * sizeof(uint32_t) : 0);
   if (dbg)
     hipLaunchKernelGGL((scan_mfma_kernel<W, F, true>), dim3(grid), dim3(64 * MWAVES), smem, st, a);

@@ -228,26 +228,44 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
   }
 }
 
+// Which selection kernel a given (nlist, nprobe) takes: 0 = one wavefront per query streaming the score row through
+// a register-resident sorted list (nprobe <= 64, any nlist); 1, 2, 3 = one wavefront per query with the whole row
+// in registers, 8 / 16 / 32 scores per lane (nprobe > 64, nlist <= 512 / 1024 / 2048); 4 = one workgroup per
+// query, radix select in LDS (nprobe > 64, nlist > 2048).
+int probe_select_variant(int nlist, int nprobe) {
+  if (nprobe <= 64) return 0;
+  if (nlist <= 64 * 8) return 1;
+  if (nlist <= 64 * 16) return 2;
+  if (nlist <= 64 * 32) return 3;
+  return 4;
+}
+
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st) {
   if (nq <= 0) return RABITQ_OK;
   const int npad = next_pow2(nprobe);
   const size_t smem = npad * sizeof(uint64_t);
-  if (nprobe <= 64)
-    hipLaunchKernelGGL(select_probes_stream_kernel, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, scores, sq_norm,
-                       centroid_sq, nq, nlist, nprobe, metric, probe_ids, probe_G, probe_E);
-  else if (nlist <= 64 * 8)
-    hipLaunchKernelGGL(select_probes_wave_kernel<8>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm, centroid_sq,
-                       nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
-  else if (nlist <= 64 * 16)
-    hipLaunchKernelGGL(select_probes_wave_kernel<16>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
-                       centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
-  else if (nlist <= 64 * 32)
-    hipLaunchKernelGGL(select_probes_wave_kernel<32>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
-                       centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
-  else
-    hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)nq), dim3(256), smem, st, scores, sq_norm, centroid_sq,
-                       nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  switch (probe_select_variant(nlist, nprobe)) {
+    case 0:
+      hipLaunchKernelGGL(select_probes_stream_kernel, dim3((unsigned)((nq + 3) / 4)), dim3(256), 0, st, scores, sq_norm,
+                         centroid_sq, nq, nlist, nprobe, metric, probe_ids, probe_G, probe_E);
+      break;
+    case 1:
+      hipLaunchKernelGGL(select_probes_wave_kernel<8>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
+                         centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+      break;
+    case 2:
+      hipLaunchKernelGGL(select_probes_wave_kernel<16>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
+                         centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+      break;
+    case 3:
+      hipLaunchKernelGGL(select_probes_wave_kernel<32>, dim3((unsigned)nq), dim3(64), smem, st, scores, sq_norm,
+                         centroid_sq, nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+      break;
+    default:
+      hipLaunchKernelGGL(select_probes_kernel, dim3((unsigned)nq), dim3(256), smem, st, scores, sq_norm, centroid_sq,
+                         nlist, nprobe, npad, metric, probe_ids, probe_G, probe_E);
+  }
   RQ_HIP(hipGetLastError());
   return RABITQ_OK;
 }

@@ -24,7 +24,7 @@ TILE = 64
 EXPORTS = [
     "rabitq_index_upload", "rabitq_index_build", "rabitq_index_export", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
     "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_qhat_stride", "rabitq_coarse_probe",
-    "rabitq_probe_list_scratch_words", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
+    "rabitq_probe_list_scratch_words", "rabitq_probe_select_variant", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
 ]
 
@@ -84,6 +84,8 @@ def load_library() -> C.CDLL:
     lib.rabitq_probe_list_scratch_words.argtypes = [i32, i64]
     lib.rabitq_probe_list_scratch_words.restype = i64
     lib.rabitq_cand_capacity.argtypes = [i32]
+    lib.rabitq_probe_select_variant.argtypes = [i32, i32]
+    lib.rabitq_probe_select_variant.restype = i32
     lib.rabitq_cand_capacity.restype = i32
     lib.rabitq_build_probe_lists.argtypes = [vp, vp, i64, i32, vp, vp, vp, vp]
     lib.rabitq_seed_threshold.argtypes = [vp, C.POINTER(_QueryRepr), vp, vp, vp, i64, i32, i32, vp, vp]
@@ -91,7 +93,7 @@ def load_library() -> C.CDLL:
     lib.rabitq_merge.argtypes = [vp, vp, vp, i64, i32, i32, vp, vp, vp]
     for name in EXPORTS:
         if name not in ("rabitq_last_error", "rabitq_index_info", "rabitq_probe_list_scratch_words",
-                        "rabitq_cand_capacity", "rabitq_qhat_stride"):
+                        "rabitq_cand_capacity", "rabitq_qhat_stride", "rabitq_probe_select_variant"):
             getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
