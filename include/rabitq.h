@@ -88,7 +88,10 @@ typedef struct {
  * document; these follow from Eq. (1)-(3)).  With G the coarse term of the probed
  * cluster (L2: ||q'-c'||^2, IP: -<q',c'>), E = ||q'-c'||, the 4-bit query qhat with
  * scale delta and S = sum(qhat), and I = <x_b, qhat> by AND+popcount:
- *   est1 = G + f_add1 + f_rescale1 * delta * (2I - S)/2,   lb1 = est1 - f_err1 * E
+ *   est1 = G + f_add1 + f_rescale1 * delta * (2I - S)/2,
+ *   lb1 = est1 - f_err1 * sqrt(E^2 + (D-1) delta^2 / (12 (1 - 2/pi)))   (the second term under the root is the
+ *         variance the 4-bit query's rounding adds, in the units of the code's own error; the lookup-table
+ *         scheme rounds no query and uses lb1 = est1 - f_err1 * E)
  *   estB = G + f_addB + f_rescaleB * (<u, q'> - (2^B-1)/2 * sum(q'))
  * Keys are "smaller is better" for both metrics (IP keys are negated products). */
 

@@ -30,7 +30,8 @@ Readings taken where the paper is silent
   the K-th smallest of their refined estimates (for B = 1: the K-th smallest
   1-bit estimate).  Every probed cluster is then filtered with that one ``tau``:
   a vector survives when its 1-bit lower bound (B = 1: its 1-bit estimate) is
-  <= tau.  ``tau`` is always >= the final K-th best key of the unpruned search,
+  <= tau.  The bound of the bitwise scheme also covers the rounding error of the
+  4-bit query (bound_radius below); the lookup-table scheme has no such error.  ``tau`` is always >= the final K-th best key of the unpruned search,
   because K scanned vectors have keys <= tau.
 * Result: the K smallest (key, id) among survivors; L2 keys are estimated squared
   distances, IP keys are negated estimated inner products.
@@ -178,8 +179,26 @@ def estimate_1bit_lut(G, E, short_factors, ip, sum_q):
     return est, lb
 
 
+# The 4-bit query's rounding errors (Section 3.4.1(2)) are a second, independent error of the 1-bit estimate: dimension
+# i contributes f_rescale * x_bar_i * e_i with x_bar_i = +-1/2 and e_i = q'_i - delta*qhat_i in [-delta/2, delta/2]
+# (no clamping error, since delta = max|q'|/7), variance delta^2/12.  Their sum has standard deviation
+# |f_rescale| * delta * sqrt(D/48); in units of the code's own error scale f_err * ||q'-c'|| / eps0 (oracle.build.
+# vector_factors) that is sqrt((D-1) delta^2 / (12 (1-a^2))) / ||q'-c'||, a = the code's alignment <x,o'>/||x||.  Both
+# errors are zero-mean and independent, so the lower bound of Section 3.3.4 keeps its confidence when ||q'-c'|| is
+# replaced by sqrt(||q'-c'||^2 + (D-1) delta^2 / (12 (1-a^2))).  For 1-bit codes a^2 concentrates at 2/pi (pinned in
+# tests/test_oracle_encode.py), which makes the widening a per-(query, cluster) scalar.
+QUANT_ERR_VAR = 1.0 / 12.0            # variance of one rounding error in units of delta^2 (uniform on [-1/2, 1/2])
+ONE_BIT_MISALIGN = 1.0 - 2.0 / np.pi  # 1 - a^2 of a 1-bit code in the large-D limit
+
+
+def bound_radius(E, delta, D):
+    """``||q'-c'||`` widened by the 4-bit query's rounding error (see above); ``E`` may be an array."""
+    return np.sqrt(np.asarray(E, np.float64) ** 2 + (D - 1.0) * float(delta) ** 2 * QUANT_ERR_VAR / ONE_BIT_MISALIGN)
+
+
 def estimate_1bit(G, E, short_factors, delta, I, S):
-    """1-bit estimate and its lower bound for one (query, cluster) pair.
+    """1-bit estimate and its lower bound for one (query, cluster) pair; ``E`` is the radius the error factor
+    multiplies (bound_radius for a quantised query).
     ``<x_bar, q'> ~= delta * (I - S/2)`` with ``x_bar = u_b - 1/2``."""
     f = short_factors.astype(np.float64)
     ipq = float(delta) * (2.0 * I.astype(np.float64) - float(S)) / 2.0
@@ -227,7 +246,7 @@ class Searcher:
             est1, lb1 = estimate_1bit_lut(G, E, ix["short_factors"][s:e], I, np.asarray(qr, np.float64).sum())
             return s, e, I, est1, lb1
         I = ip_bitplane(self.words[s:e], planes)
-        est1, lb1 = estimate_1bit(G, E, ix["short_factors"][s:e], delta, I, S)
+        est1, lb1 = estimate_1bit(G, bound_radius(E, delta, ix["dim"]), ix["short_factors"][s:e], delta, I, S)
         return s, e, I, est1, lb1
 
     def refined(self, s, e, G, qr, sel=None):

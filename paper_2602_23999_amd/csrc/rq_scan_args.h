@@ -20,6 +20,10 @@ struct ScanArgs {
   const int32_t* cluster_size;
   int D, B, LW, nlist;
   float cB;  // (2^B - 1) / 2
+  // The 1-bit bound of a 4-bit query multiplies f_err by sqrt(E^2 + qerr * delta^2) instead of E = ||q'-c'||: the
+  // query's rounding errors add variance (D-1) delta^2 / (12 (1-a^2)) in the units of the code's own error, with
+  // a^2 = 2/pi for 1-bit codes; qerr = (D-1) / (12 (1 - 2/pi)), 0 for the lookup-table scheme (no rounded query).
+  float qerr;
   // per query
   const float* q_stage;   // [nq][D] rotated query in refinement order
   const int8_t* qhat8;    // [nq][Dp] 4-bit query as bytes (matrix-core scan)

@@ -412,8 +412,11 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     pj[j] = pp;
     qj[j] = q;
     Gj[j] = a.probe_G[pp];
-    Ej[j] = a.probe_E[pp];
     dlj[j] = a.delta[q];
+    {  // radius of the bound: ||q'-c'|| widened by the rounding error of the 4-bit query
+      const float e = a.probe_E[pp];
+      Ej[j] = sqrtf(fmaf(a.qerr, dlj[j] * dlj[j], e * e));
+    }
     Sj[j] = a.sum_qhat[q];
     bej[j] = 0.5f * dlj[j] * (float)Sj[j];
     hsqj[j] = 0.5f * a.sum_q[q];
@@ -762,7 +765,10 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
     al[r] = dl;
     be[r] = 0.5f * dl * (float)a.sum_qhat[q];
     Gr[r] = a.probe_G[pp];
-    Er[r] = a.probe_E[pp];
+    {  // radius of the bound: ||q'-c'|| widened by the rounding error of the 4-bit query
+      const float e = a.probe_E[pp];
+      Er[r] = sqrtf(fmaf(a.qerr, dl * dl, e * e));
+    }
     tr[r] = (qi < np) ? a.tau[q] : -3.402823466e+38f;
   }
   __syncthreads();

@@ -73,6 +73,7 @@ static ScanArgs base_args(const rabitq_index* ix) {
   a.LW = ix->LW;
   a.nlist = ix->nlist;
   a.cB = (float)(((1 << ix->total_bits) - 1) * 0.5);
+  a.qerr = effective_impl(ix) == 2 ? 0.f : (float)((ix->dim - 1.0) / (12.0 * (1.0 - 2.0 / 3.14159265358979323846)));
   return a;
 }
 

@@ -7,7 +7,7 @@ import torch
 from oracle import exact, search
 from paper_2602_23999_amd import rabitq
 
-from gpu_helpers import compare_topk
+from gpu_helpers import check_against_own_run, compare_topk, search_explained
 from test_gpu_parity import case
 
 pytestmark = pytest.mark.gpu
@@ -109,20 +109,15 @@ def test_search_end_to_end_lut(name):
     s, k, nprobe = c["s_lut"], c["k"], c["nprobe"]
     c["gi"].set_option("scan_impl", 2)
     try:
-        ids, dist = c["gi"].search(torch.from_numpy(c["Q"]).cuda(), k, nprobe)
+        ids, dist, why = search_explained(c["gi"], s, c["Q"], k, nprobe)
     finally:
         c["gi"].set_option("scan_impl", 0)
-    ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
-    o_ids, o_d, info = s.search(c["Q"], k, nprobe)
+    # the GPU's q' differs from the oracle's in the last place, which may move a binary16 table entry by one
+    # step for some queries (recorded in why["caused"]); everything else must be identical
+    own = s.search(c["Q"], k, nprobe, detail=True)
+    check_against_own_run(s, own, ids, dist, k, why)
     gt, _ = exact.exact_knn(c["X"], c["Q"], k, c["ix"]["metric"])
-    same = np.array([np.array_equal(a, b) for a, b in zip(ids, o_ids)])
-    # the GPU's q' differs from the oracle's in the last ulp, which may move a binary16 table
-    # entry by one step for a few queries; everything else must be identical
-    assert same.mean() >= 0.9, same.mean()
-    assert abs(exact.recall_at_k(ids, gt) - exact.recall_at_k(o_ids, gt)) <= 0.01
-    atol = 1e-4 * (info["G"].max(axis=1) + 1e-6)
-    ok = np.abs(dist[same] - o_d[same]) <= atol[same, None] + 1e-4 * np.abs(o_d[same])
-    assert ok[np.isfinite(o_d[same])].all()
+    assert abs(exact.recall_at_k(ids, gt) - exact.recall_at_k(own[0], gt)) <= 0.01
 
 
 def test_lut_scan_without_tables_is_rejected():

@@ -7,7 +7,8 @@ import torch
 from oracle import build, exact, search
 from paper_2602_23999_amd import rabitq, synth
 
-from gpu_helpers import compare_topk, oracle_stages, to_dev, upload
+from gpu_helpers import (check_against_own_run, compare_topk, key_scale, oracle_stages, search_explained, to_dev,
+                         upload)
 
 pytestmark = pytest.mark.gpu
 
@@ -20,6 +21,8 @@ CASES = {
     "ragged_b2": ("tiny", 1_500, 40, 50, 50, 2, 10, 50),          # many small / empty lists, nprobe = nlist
     "centred_b4": ("l2_128", 20_000, 64, 64, 32, 4, 10, 6),      # index built on the vectors minus their mean
     "many_probes_b2": ("tiny", 12_000, 48, 64, 160, 2, 10, 100),  # nprobe > 64: workgroup-wide probe selection
+    "ip_768_b8": ("ip_768_tight", 1_500, 24, 12, 10, 8, 10, 4),   # inner product, D = 768 (W = 24), 8-bit codes
+    "l2_960_b1": ("l2_960", 4_000, 24, 16, 12, 1, 10, 4),         # D = 960 with 1-bit codes only (no refinement)
 }
 _cache = {}
 
@@ -118,10 +121,20 @@ def test_seed_threshold(name):
     st, d = c["st"], c["dev"]
     tau = c["gi"].seed_threshold(d["prep"], d["probes"], c["k"]).cpu().numpy().astype(np.float64)
     want = np.minimum(st["tau"], rabitq.FLT_MAX)
-    scale = st["G"].max(axis=1) + 1e-6
-    bad = np.abs(tau - want) > 1e-4 * (np.abs(want) + scale)
-    # a mismatch can only come from a near-tie at rank k among the 1-bit estimates
-    assert bad.mean() <= 0.02, (tau[bad], want[bad])
+    scale = key_scale(st["G"], st["E"], c["s"].metric)
+    bad = np.nonzero(np.abs(tau - want) > 1e-4 * (np.abs(want) + scale))[0]
+    # a mismatch can only come from a near-tie among the 1-bit estimates at the rank that bounds the seeds
+    s, ix, k = c["s"], c["ix"], c["k"]
+    m = k if s.B == 1 else max(k, s.seed_m)
+    for i in bad:
+        for cl, G, E in zip(st["probes"][i], st["G"][i], st["E"][i]):
+            a, b = int(ix["offsets"][cl]), int(ix["offsets"][cl + 1])
+            if b - a < k:
+                continue
+            e = np.sort(s.pair(cl, G, E, st["Qr"][i], st["delta"][i], st["planes"][i], int(st["S"][i]))[3])
+            assert b - a > m and abs(e[m] - e[m - 1]) <= 1e-5 * (abs(e[m]) + scale[i]), (i, tau[i], want[i])
+            break
+    assert len(bad) <= 0.02 * len(tau)
 
 
 @pytest.mark.parametrize("impl", [0, 1])
@@ -134,8 +147,9 @@ def test_scan_and_merge_with_injected_threshold(name, prune, impl):
     nq, k, nprobe = len(c["Q"]), c["k"], c["nprobe"]
     # The injected threshold is the oracle's, moved up by a hair (as an fp32 value that both
     # sides then share) so that the k-th seed itself does not sit on the fp32/fp64 boundary.
+    scale = key_scale(st["G"], st["E"], s.metric)
     tau_np = np.minimum(st["tau"], rabitq.FLT_MAX)
-    tau_np = (tau_np + 1e-5 * (np.abs(tau_np) + st["G"].max(axis=1))).astype(np.float32)
+    tau_np = (tau_np + 1e-5 * (np.abs(tau_np) + scale)).astype(np.float32)
     tau_np[st["tau"] >= rabitq.FLT_MAX] = rabitq.FLT_MAX
     if not prune:
         tau_np[:] = rabitq.FLT_MAX
@@ -144,32 +158,51 @@ def test_scan_and_merge_with_injected_threshold(name, prune, impl):
     c["gi"].set_option("scan_impl", 0)
     ids, dist = c["gi"].merge(keys, cnt, nq, k, nprobe)
     o_ids, o_d, info = s.search(c["Q"], k, nprobe, prune=prune, Qr=st["Qr"], tau=tau_np.astype(np.float64))
-    atol = 1e-4 * (st["G"].max(axis=1) + 1e-6)
-    n_exact = compare_topk(ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64), o_ids, o_d, atol)
+    n_exact = compare_topk(ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64), o_ids, o_d, 1e-4 * scale)
     assert n_exact >= 0.97 * nq
     assert int(cnt.max()) <= keys.shape[1]
 
 
+def oracle_own(c, prune):
+    """The oracle's search on its own fp64 path (cached per case)."""
+    key = ("own", prune)
+    if key not in c:
+        c[key] = c["s"].search(c["Q"], c["k"], c["nprobe"], prune=prune, detail=True)
+    return c[key]
+
+
 @pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("prune", [True, False])
 @pytest.mark.parametrize("name", ALL)
-def test_search_end_to_end(name, impl):
+def test_search_end_to_end(name, prune, impl):
     c = case(name)
     s, k, nprobe = c["s"], c["k"], c["nprobe"]
     c["gi"].set_option("scan_impl", impl)
-    ids, dist = c["gi"].search(torch.from_numpy(c["Q"]).cuda(), k, nprobe)
-    c["gi"].set_option("scan_impl", 0)
-    ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
-    o_ids, o_d, info = s.search(c["Q"], k, nprobe)
+    try:
+        # every difference from the oracle is accounted for stage by stage (a digit on a rounding boundary, a
+        # probe or seed near-tie, a vector on the threshold, keys that tie); anything else fails inside
+        ids, dist, why = search_explained(c["gi"], s, c["Q"], k, nprobe, prune=prune, cache=c.setdefault("e2e", {}))
+    finally:
+        c["gi"].set_option("scan_impl", 0)
+    # and the outcome is the oracle's own: same recall against exact kNN
+    o_ids, o_d, info = oracle_own(c, prune)
     gt, _ = exact.exact_knn(c["X"], c["Q"], k, c["ix"]["metric"])
     r_gpu, r_ora = exact.recall_at_k(ids, gt), exact.recall_at_k(o_ids, gt)
-    same = np.array([np.array_equal(a, b) for a, b in zip(ids, o_ids)])
-    # GPU q' differs from the oracle's in the last ulp, which may flip a 4-bit code or a
-    # probe near-tie for a few queries; everything else must be identical
-    assert same.mean() >= 0.95, same.mean()
-    assert abs(r_gpu - r_ora) <= 0.005, (r_gpu, r_ora)
-    atol = 1e-4 * (info["G"].max(axis=1) + 1e-6)
-    ok = np.abs(dist[same] - o_d[same]) <= atol[same, None] + 1e-4 * np.abs(o_d[same])
-    assert ok[np.isfinite(o_d[same])].all()
+    assert abs(r_gpu - r_ora) <= 0.005, (r_gpu, r_ora, why)
+    # a query that differs from the oracle's own run needs a recorded cause in the stages, else it may only differ by
+    # tied keys or a vector on the threshold
+    n_same = check_against_own_run(s, (o_ids, o_d, info), ids, dist, k, why)
+    assert n_same >= 0.9 * len(ids), (n_same, why)
+    if prune:
+        # What the filter costs: members of the oracle's unpruned top-k (the paper's definition) that the filtered GPU
+        # search lost.  A member is lost only if its 1-bit lower bound exceeds tau >= its own refined key, i.e. if the
+        # 1-bit estimate errs by more than eps0 = 1.9 standard errors to one side: probability <= 1 - Phi(1.9) = 0.0287
+        # per member (a little more with the query's 4-bit quantisation error, which the bound does not cover), plus
+        # three standard deviations of sampling noise over the members counted.
+        u_ids, _, _ = oracle_own(c, False)
+        members = int((u_ids >= 0).sum())
+        lost = sum(int((~np.isin(u[u >= 0], g)).sum()) for u, g in zip(u_ids, ids)) / max(members, 1)
+        assert lost <= 1.15 * 0.0287 + 3.0 * np.sqrt(0.0287 / max(members, 1)), (lost, members)
 
 
 def test_edge_cases():
@@ -204,10 +237,9 @@ def test_ip_metric_end_to_end():
     ix = build.build_index(X, 24, 6, metric="ip", kmeans_iters=3)
     s = search.Searcher(ix)
     gi = upload(ix)
-    ids, dist = gi.search(torch.from_numpy(Q).cuda(), 10, 6)
-    o_ids, o_d, info = s.search(Q, 10, 6)
-    ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
-    same = np.array([np.array_equal(a, b) for a, b in zip(ids, o_ids)])
-    assert same.mean() >= 0.9
-    assert np.all(np.abs(dist[same] - o_d[same]) <= 2e-4)
-    assert np.all(np.diff(dist, axis=1) <= 1e-6)
+    ids, dist, why = search_explained(gi, s, Q, 10, 6)
+    assert np.all(np.diff(dist, axis=1) <= 1e-6)          # inner products, best (largest) first
+    o_ids, _, _ = s.search(Q, 10, 6)
+    gt, _ = exact.exact_knn(X, Q, 10, "ip")
+    assert abs(exact.recall_at_k(ids, gt) - exact.recall_at_k(o_ids, gt)) <= 0.005
+    gi.close()

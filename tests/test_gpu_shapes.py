@@ -9,7 +9,7 @@ import torch
 from oracle import build, exact, search
 from paper_2602_23999_amd import synth
 
-from gpu_helpers import upload
+from gpu_helpers import check_against_own_run, search_explained, upload
 
 pytestmark = pytest.mark.gpu
 
@@ -34,17 +34,12 @@ def test_shape_end_to_end(D, B, n, nlist, k, nprobe, nq, impl):
     s = search.Searcher(ix)
     gi = upload(ix)
     gi.set_option("scan_impl", impl)
-    ids, dist = gi.search(torch.from_numpy(Q).cuda(), k, nprobe)
-    ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
-    o_ids, o_d, info = s.search(Q, k, nprobe)
-    # padding (fewer than k survivors) must agree exactly; distances within the estimator tolerance
+    ids, dist, why = search_explained(gi, s, Q, k, nprobe)   # every difference from the oracle accounted for
+    own = s.search(Q, k, nprobe, detail=True)
+    o_ids = own[0]
+    # padding (fewer than k survivors) must agree exactly
     assert np.array_equal(ids < 0, o_ids < 0)
-    same = np.array([np.array_equal(a, b) for a, b in zip(ids, o_ids)])
-    assert same.mean() >= 0.85, same.mean()
-    atol = 1e-4 * (info["G"].max(axis=1) + 1e-6)
-    fin = np.isfinite(o_d)
-    ok = np.abs(np.where(fin, dist - o_d, 0.0)) <= atol[:, None] + 1e-4 * np.abs(np.where(fin, o_d, 0.0))
-    assert ok[same].all()
+    check_against_own_run(s, own, ids, dist, k, why)
     gt, _ = exact.exact_knn(X, Q, k)
     assert abs(exact.recall_at_k(ids, gt) - exact.recall_at_k(o_ids, gt)) <= 0.03
     gi.close()

@@ -107,3 +107,52 @@ def test_degenerate_vector_equal_to_centroid():
     q = np.full((1, 32), 0.5, np.float32)
     ids, d, _ = s.search(q, 3, 2)
     assert np.allclose(d[0], 32 * 0.25, atol=1e-4) and ids[0].tolist() == [0, 1, 2]
+
+
+def test_bound_covers_the_query_rounding_error():
+    """The 1-bit estimate from the 4-bit query has two independent errors: the code's and the query's rounding.
+    In a regime where the two are of the same size (a query far from the origin but close to the centroid), the
+    error's spread matches the combined prediction, search.bound_radius reproduces it from the expected alignment
+    of 1-bit codes, and the lower bound built on it fails as often as a 1.9-sigma bound should, which the bound on
+    ||q'-c'|| alone does not."""
+    rng = np.random.default_rng(5)
+    D, T, eps0 = 256, 800, 1.9
+    c = 2.5 * rng.standard_normal(D)
+    o_raw = c + rng.standard_normal(D)
+    q = c + 0.5 * rng.standard_normal(D)
+    true = np.sum((q - o_raw) ** 2)
+    z_exact, z_radius, over_new, over_old, ratio = [], [], 0, 0, []
+    for t in range(T):
+        P = build.random_rotation(D, 1000 + t).astype(np.float64)
+        res = o_raw - c
+        r = np.linalg.norm(res)
+        o_rot = (res / r) @ P
+        xb = (o_rot >= 0).astype(np.float64)[None] - 0.5
+        c_rot, q_rot = (c @ P)[None], (q @ P).astype(np.float32)
+        f = build.vector_factors(xb, o_rot[None], c_rot, np.array([r]), "l2", eps0)[0]
+        delta, qhat, S = search.quantize_query(q_rot)
+        I = int(((xb[0] + 0.5) * qhat).sum())
+        G = np.sum((q_rot.astype(np.float64) - c_rot[0]) ** 2)
+        E = np.sqrt(G)
+        est1, lb = search.estimate_1bit(G, search.bound_radius(E, delta, D), f[None].astype(np.float32), delta,
+                                        np.array([I]), S)
+        err = est1[0] - true
+        s_code = f[2] * E / eps0
+        s_query = abs(f[1]) * float(delta) * np.sqrt(D / 48.0)
+        ratio.append(s_query / s_code)
+        z_exact.append(err / np.hypot(s_code, s_query))
+        z_radius.append(err / (f[2] * search.bound_radius(E, delta, D) / eps0))
+        over_new += lb[0] > true
+        over_old += est1[0] - f[2] * E > true
+    assert 0.7 < np.median(ratio) < 1.5                      # the regime: both errors matter
+    assert abs(np.std(z_exact) - 1.0) < 0.12 and abs(np.mean(z_exact)) < 0.12
+    assert abs(np.std(z_radius) - 1.0) < 0.12               # the expected alignment stands in for the code's own
+    tail = 0.0287                                            # 1 - Phi(1.9)
+    assert abs(over_new / T - tail) < 3.5 * np.sqrt(tail / T)
+    assert over_old / T > tail + 5 * np.sqrt(tail / T)       # the bound on the code's error alone is not one
+
+
+def test_bound_radius_is_negligible_where_the_query_grid_is_fine():
+    # benchmark-like sizes: delta ~ 10, ||q'-c'|| ~ 250, D = 128
+    assert search.bound_radius(250.0, 10.0, 128) / 250.0 < 1.03
+    assert search.bound_radius(0.0, 0.0, 128) == 0.0
