@@ -31,6 +31,7 @@ extern "C" {
 #define RABITQ_MAX_K 128      /* largest supported K                                    */
 #define RABITQ_QUERY_BITS 4   /* B_q of the bitwise scheme (Section 3.4.1(2))           */
 #define RABITQ_MAX_NPROBE 1024
+#define RABITQ_NOALLOC_SCRATCH_BYTES (64u << 20) /* static workspace of rabitq_search_noalloc, per device */
 
 typedef enum {
   RABITQ_OK = 0,
@@ -155,6 +156,24 @@ int rabitq_index_free(rabitq_index_t index);
  */
 int rabitq_search(rabitq_index_t index, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
                   int64_t* out_ids, float* out_dists, void* stream);
+
+/*
+ * The same search for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Arguments, results and kernels are those of rabitq_search;
+ * the workspace (rotated queries and their representation, coarse scores [nq][nlist], probes, pair lists,
+ * list-builder bitmap, candidate keys [nq*nprobe][cap] and counters) is laid out in a static device array of
+ * RABITQ_NOALLOC_SCRATCH_BYTES (64 MiB) that every device the library runs on holds until the process ends.
+ * The call allocates and frees nothing, on the device or through any library, and never splits the batch:
+ * a (nq, k, nprobe) whose workspace does not fit is rejected with RABITQ_EINVAL and a message that names the
+ * bytes needed.  Roughly nq * (4 nlist + nprobe * (8 cap + 20) + 10 D + nlist / 4) bytes, cap = rabitq_cand_capacity(k):
+ * about 7000 queries at nlist 1024, D 128, k 10, nprobe 16.
+ * All calls on one device share that device's array, which keeps the previous call's contents; the call clears
+ * what must start at zero itself (with kernels).  Calls that overlap in time on one device (other streams, other
+ * handles, other threads) race on the array: the caller must order them.  rabitq_search is not affected: it
+ * uses the handle's own workspace.
+ */
+int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
+                          int64_t* out_ids, float* out_dists, void* stream);
 
 /* Options (host call, takes effect for later searches):
  *   "prune"   1 (default): filter with the per-query seeded threshold (Section 3.3.4);

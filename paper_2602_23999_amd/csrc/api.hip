@@ -2,6 +2,7 @@
 // chaining of the stage kernels on the caller's stream.
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -10,6 +11,14 @@
 namespace rq {
 
 static thread_local std::string g_err;
+
+// Search workspace of rabitq_search_noalloc: one array per device, held until the process ends.  The name is a
+// host-side stand-in; the device address is looked up once per device (noalloc_scratch) and only that address is
+// ever handed to kernels.
+static __device__ __align__(256) unsigned char scratch[RABITQ_NOALLOC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+static unsigned char* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+static std::mutex g_scratch_mu;
 
 void set_error(const std::string& s) { g_err = s; }
 
@@ -130,6 +139,57 @@ static int64_t search_batch_limit(const rabitq_index* ix, int k, int nprobe) {
 }
 
 
+// Address of the current device's copy of `scratch`; `dev` must be the current device.  Looked up once per device.
+static int noalloc_scratch(int dev, unsigned char** out) {
+  if (dev < 0 || dev >= MAX_DEVICES) { set_error("device index out of range"); return RABITQ_EINVAL; }
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!p) { set_error("hipGetSymbolAddress(scratch) returned a null address"); return RABITQ_EHIP; }
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return RABITQ_OK;
+}
+
+// Lays the buffers of one search of (nq, nprobe, k) out behind `base`, each at a multiple of 256 bytes, and
+// returns the bytes they take; base == nullptr only measures.  Nothing is allocated.
+static size_t carve_workspace(const rabitq_index* ix, int64_t nq, int nprobe, int k, unsigned char* base, Workspace* w) {
+  size_t off = 0;
+  auto take = [&](auto** p, int64_t count) {
+    using T = std::remove_pointer_t<std::remove_pointer_t<decltype(p)>>;
+    if (base && p) *p = reinterpret_cast<T*>(base + off);
+    off += (((size_t)std::max<int64_t>(count, 1) * sizeof(T)) + 255) / 256 * 256;
+  };
+  const int64_t pairs = nq * nprobe;
+  int cap = 1;
+  while (cap < k + TILE) cap <<= 1;
+  Workspace dummy;
+  Workspace& x = w ? *w : dummy;
+  take(&x.q_rot, nq * ix->dim);
+  take(&x.repr.planes, nq * 4 * ix->W);
+  take(&x.repr.delta, nq);
+  take(&x.repr.sum_qhat, nq);
+  take(&x.repr.sum_q, nq);
+  take(&x.repr.sq_norm, nq);
+  take(&x.repr.qhat8, nq * qhat_stride(ix->dim));
+  take(&x.repr.q_stage, nq * ix->dim);
+  if (ix->scan_impl == 2) take(&x.repr.lut, nq * ix->dim * 4);
+  take(&x.tau, nq);
+  take(&x.scores, nq * ix->nlist);
+  take(&x.probe_ids, pairs);
+  take(&x.probe_G, pairs);
+  take(&x.probe_E, pairs);
+  take(&x.pair_off, (int64_t)ix->nlist + 1);
+  take(&x.pair_ids, pairs);
+  take(&x.list_scratch, probe_list_scratch_words(ix->nlist, nq));
+  take(&x.cand_keys, pairs * cap);
+  take(&x.cand_cnt, pairs);
+  return off;
+}
+
 // second stream (default priority) and fork / join events of a handle; called once when the handle is made,
 // with the handle's device current
 static int init_streams(rabitq_index* ix) {
@@ -137,7 +197,8 @@ static int init_streams(rabitq_index* ix) {
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
   ix->seg_sorted.reserve(ix->host_tiles.size());  // so that a search never grows a host vector either
-  return RABITQ_OK;
+  unsigned char* sp = nullptr;  // the allocation-free search's workspace on this device
+  return noalloc_scratch(ix->device, &sp);
 }
 
 int set_index_mean(rabitq_index* ix, const float* mean, const float* rotation_host, hipStream_t st) {
@@ -623,6 +684,27 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
       return rc;
   }
   return RABITQ_OK;
+}
+
+int rabitq_search_noalloc(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k, int32_t nprobe,
+                          int64_t* out_ids, float* out_dists, void* stream) {
+  int rc = check_common(ix, nq, "search_noalloc");
+  if (rc) return rc;
+  if ((rc = check_k_nprobe(ix, k, nprobe, "search_noalloc"))) return rc;
+  if (nq == 0) return RABITQ_OK;
+  if (!queries || !out_ids || !out_dists) { set_error("search_noalloc: null pointer"); return RABITQ_EINVAL; }
+  if (nq > 0x7fffffff / nprobe) { set_error("search_noalloc: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
+  const size_t need = carve_workspace(ix, nq, nprobe, k, nullptr, nullptr);
+  if (need > (size_t)RABITQ_NOALLOC_SCRATCH_BYTES) {
+    set_error("search_noalloc: this (nq, k, nprobe) needs " + std::to_string(need) + " bytes of workspace, the static "
+              "scratch holds " + std::to_string((size_t)RABITQ_NOALLOC_SCRATCH_BYTES) + "; use rabitq_search or a smaller batch");
+    return RABITQ_EINVAL;
+  }
+  unsigned char* base = nullptr;
+  if ((rc = noalloc_scratch(ix->device, &base))) return rc;
+  Workspace w;
+  carve_workspace(ix, nq, nprobe, k, base, &w);
+  return search_batch(ix, w, queries, nq, k, nprobe, out_ids, out_dists, (hipStream_t)stream);
 }
 
 }  // extern "C"

@@ -22,7 +22,7 @@ QUERY_BITS = 4
 TILE = 64
 
 EXPORTS = [
-    "rabitq_index_upload", "rabitq_index_build", "rabitq_index_export", "rabitq_index_free", "rabitq_search", "rabitq_set_option", "rabitq_index_info",
+    "rabitq_index_upload", "rabitq_index_build", "rabitq_index_export", "rabitq_index_free", "rabitq_search", "rabitq_search_noalloc", "rabitq_set_option", "rabitq_index_info",
     "rabitq_stage_ms", "rabitq_rotate", "rabitq_query_prep", "rabitq_qhat_stride", "rabitq_coarse_probe",
     "rabitq_probe_list_scratch_words", "rabitq_probe_select_variant", "rabitq_cand_capacity", "rabitq_build_probe_lists", "rabitq_seed_threshold", "rabitq_scan",
     "rabitq_merge", "rabitq_last_error",
@@ -72,6 +72,7 @@ def load_library() -> C.CDLL:
     lib.rabitq_index_export.argtypes = [vp] * 10
     lib.rabitq_index_free.argtypes = [vp]
     lib.rabitq_search.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
+    lib.rabitq_search_noalloc.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     lib.rabitq_set_option.argtypes = [vp, C.c_char_p, i64]
     lib.rabitq_index_info.argtypes = [vp, C.c_char_p]
     lib.rabitq_index_info.restype = i64
@@ -234,6 +235,12 @@ class Index:
             out_dists = torch.empty((nq, k), dtype=torch.float32, device=dev)
         _check(load_library().rabitq_search(self._h, _dev(queries, torch.float32), nq, k, nprobe,
                                             _dev(out_ids, torch.int64), _dev(out_dists, torch.float32), _stream()))
+        return out_ids, out_dists
+
+    def search_noalloc(self, queries: torch.Tensor, k: int, nprobe: int, out_ids: torch.Tensor, out_dists: torch.Tensor):
+        """rabitq_search_noalloc: the caller supplies the outputs; nothing is allocated here or in the library."""
+        _check(load_library().rabitq_search_noalloc(self._h, _dev(queries, torch.float32), queries.shape[0], k, nprobe,
+                                                    _dev(out_ids, torch.int64), _dev(out_dists, torch.float32), _stream()))
         return out_ids, out_dists
 
     def set_option(self, name: str, value: int):
