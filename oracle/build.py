@@ -17,14 +17,18 @@ Conventions
 Parity status
 -------------
 random_rotation      pinned: orthogonality, norm / distance preservation.
-kmeans_lloyd         pinned: assignment = brute-force nearest centroid.
+kmeans_lloyd         pinned: assignment = brute-force nearest centroid; update step =
+                     the members' mean to 1e-12 on separated blobs; an empty cluster
+                     keeps its centroid.
 encode_unit          pinned: brute force over the whole grid for tiny D, B;
                      B = 1 closed form (sign bits, cosine = ||o'||_1/sqrt(D)).
 vector_factors       pinned: exactness when o' is itself a grid direction;
                      zero-mean error over random rotations; 1/sqrt(D) error
                      scale (tests/test_oracle_estimator.py).
 pack_device_layout   pinned: hand-written fixture tests/golden/layout_small.txt
-                     and unpack(pack(x)) == x.
+                     and unpack(pack(x)) == x; unpack_device_layout is its inverse.
+pack_ex_planes       pinned: decodes, with the short code, to the same u as the
+                     whole-code fields (the long code of Section 3.4.3 vs the stored one).
 """
 from __future__ import annotations
 
@@ -394,3 +398,57 @@ def pack_device_layout(index: dict) -> dict:
         out["long_codes"] = lc.reshape(-1)
         out["long_factors"] = lfa.reshape(-1)
     return out
+
+
+def pack_ex_planes(u: np.ndarray, B: int) -> np.ndarray:
+    """The long code exactly as Section 3.4.3 describes it: only the B-1 ex-bits of each dimension (the sign bit
+    lives in the short code), stored as B-1 bit-planes of W words, plane j = bit j of ``u mod 2^(B-1)``:
+    [n, (B-1)*W] uint32.  The library stores the whole code in F-bit fields instead (pack_fields); both are
+    encodings of the same ``u`` and this function exists so that a test can show it and count the bytes."""
+    n, D = u.shape
+    ex = u.astype(np.uint32) & np.uint32((1 << (B - 1)) - 1)
+    return np.concatenate([pack_bits((ex >> np.uint32(j)) & np.uint32(1)) for j in range(B - 1)], axis=1) \
+        if B > 1 else np.zeros((n, 0), np.uint32)
+
+
+def unpack_ex_planes(short_words_: np.ndarray, planes: np.ndarray, B: int, D: int) -> np.ndarray:
+    """``u = 2^(B-1) u_b + u_ex`` from the short code [n, W] and the ex-bit planes [n, (B-1)*W]."""
+    W = D // 32
+    u = unpack_bits(short_words_, D).astype(np.uint32) << np.uint32(B - 1)
+    for j in range(B - 1):
+        u |= unpack_bits(planes[:, j * W:(j + 1) * W], D).astype(np.uint32) << np.uint32(j)
+    return u.astype(np.uint8)
+
+
+def unpack_device_layout(arr: dict) -> dict:
+    """Inverse of pack_device_layout: the canonical (unpadded, cluster-ordered) index from arrays in the layout the
+    search library uploads and exports (keys: dim, nlist, n, total_bits, metric, rotation, centroids, offsets,
+    short_codes, short_factors, long_codes, long_factors, ids, mean).  Lets the oracle search an index that was
+    built elsewhere; nothing is recomputed, every array is only re-indexed."""
+    D, B, nlist, n = int(arr["dim"]), int(arr["total_bits"]), int(arr["nlist"]), int(arr["n"])
+    W = D // 32
+    off = np.asarray(arr["offsets"], np.int64)
+    counts = np.diff(off)
+    tiles = (counts + TILE - 1) // TILE
+    tile_off = np.zeros(nlist + 1, dtype=np.int64)
+    np.cumsum(tiles, out=tile_off[1:])
+    n_tiles = int(tile_off[-1])
+    within = np.arange(n, dtype=np.int64) - np.repeat(off[:-1], counts)
+    slot = np.repeat(tile_off[:-1] * TILE, counts) + within
+    sc = np.asarray(arr["short_codes"], np.uint32).reshape(n_tiles, W, TILE).transpose(0, 2, 1).reshape(-1, W)[slot]
+    sf = np.asarray(arr["short_factors"], np.float32).reshape(n_tiles, 3, TILE).transpose(0, 2, 1).reshape(-1, 3)[slot]
+    ids = np.asarray(arr["ids"], np.int32)[slot]
+    if B > 1:
+        F = long_field_bits(B)
+        u = unpack_fields(np.asarray(arr["long_codes"], np.uint32).reshape(n_tiles * TILE, -1)[slot], F, D)
+        lf = np.asarray(arr["long_factors"], np.float32).reshape(-1, 2)[slot]
+        assert np.array_equal(u >> (B - 1), unpack_bits(sc, D)), "sign bit of the long code differs from the short code"
+    else:
+        u = unpack_bits(sc, D)
+        lf = sf[:, :2].copy()
+    mean = arr.get("mean")
+    mean = np.zeros(D, np.float32) if mean is None else np.asarray(mean, np.float32)
+    return dict(dim=D, nlist=nlist, n=n, total_bits=B, metric=arr["metric"], mean=mean,
+                P=np.asarray(arr["rotation"], np.float32).reshape(D, D),
+                centroids_rot=np.asarray(arr["centroids"], np.float32).reshape(nlist, D), offsets=off,
+                ids=ids, u=u, short_factors=sf, long_factors=lf)

@@ -65,3 +65,39 @@ def test_layout_roundtrip_ragged():
     pad = np.setdiff1d(np.arange(dev["n_slots"]), slot)
     assert not sc[pad].any() and not lc[pad].any() and np.all(dev["ids"][pad] == -1)
     assert np.all(np.isinf(sf[pad, 0])) and not sf[pad, 1:].any()
+
+
+def test_whole_code_fields_and_ex_bit_planes_hold_the_same_code():
+    # Section 3.4.3 stores only the B-1 ex-bits in the long code; the library stores the whole code in F-bit
+    # fields.  Both decode to the same u, so the choice is one of format (bytes read per refined vector), not of
+    # arithmetic.  Bytes per vector of the two formats, at the dimensions of the configurations that use them:
+    rng = np.random.default_rng(3)
+    want_bytes = {(3, 96): (48, 24 + 12), (4, 128): (64, 48 + 16), (5, 960): (960, 480 + 120), (8, 768): (768, 672 + 96)}
+    for (B, D), (field_bytes, ex_bytes) in want_bytes.items():
+        u = rng.integers(0, 1 << B, (37, D)).astype(np.uint8)
+        F = build.long_field_bits(B)
+        fields = build.pack_fields(u, F)
+        sw = build.pack_bits(u >> (B - 1))
+        ex = build.pack_ex_planes(u, B)
+        assert np.array_equal(build.unpack_fields(fields, F, D), u)
+        assert np.array_equal(build.unpack_ex_planes(sw, ex, B, D), u)
+        assert fields.shape[1] * 4 == field_bytes                   # what a refined vector reads today
+        assert (ex.shape[1] + sw.shape[1]) * 4 == ex_bytes          # ex-bit planes plus the sign words they need
+
+
+def test_unpack_device_layout_inverts_pack():
+    rng = np.random.default_rng(1)
+    for B, D in ((1, 64), (5, 96)):
+        ix = _index([70, 0, 64, 1, 129], D, B, rng)
+        ix.update(metric="l2", P=rng.standard_normal((D, D)).astype(np.float32),
+                  centroids_rot=rng.standard_normal((5, D)).astype(np.float32))
+        if B == 1:
+            ix["long_factors"] = ix["short_factors"][:, :2].copy()
+        dev = build.pack_device_layout(ix)
+        arr = dict(dim=D, nlist=5, n=ix["n"], total_bits=B, metric="l2", rotation=ix["P"].reshape(-1),
+                   centroids=ix["centroids_rot"].reshape(-1), offsets=ix["offsets"], short_codes=dev["short_codes"],
+                   short_factors=dev["short_factors"], long_codes=dev["long_codes"], long_factors=dev["long_factors"],
+                   ids=dev["ids"], mean=None)
+        back = build.unpack_device_layout(arr)
+        for key in ("u", "ids", "short_factors", "long_factors", "offsets", "P", "centroids_rot"):
+            assert np.array_equal(back[key], ix[key]), key

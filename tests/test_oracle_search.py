@@ -46,6 +46,27 @@ def test_kmeans_assignment_is_nearest_centroid():
     assert ix["offsets"][-1] == X.shape[0] and sorted(ix["ids"].tolist()) == list(range(X.shape[0]))
 
 
+def test_kmeans_update_step_gives_the_cluster_means():
+    # Two blobs far apart: whatever the seeded initial points, one Lloyd iteration separates them (or leaves one
+    # centroid without points, which then keeps its place), and the centroids are the means of their members.
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal((300, 8)) + 50.0
+    b = rng.standard_normal((200, 8)) - 50.0
+    X = np.concatenate([a, b])[rng.permutation(500)]
+    for seed in range(6):
+        C = build.kmeans_lloyd(X, 2, 3, seed)
+        assign = build.assign_clusters(X, C)
+        for c in range(2):
+            members = X[assign == c].astype(np.float64)
+            assert len(members) in (200, 300)
+            assert np.abs(C[c] - members.mean(axis=0)).max() < 1e-12
+    # a centroid that attracts no point keeps its previous position
+    far = np.concatenate([X, np.full((1, 8), 1e4)])
+    C = build.kmeans_lloyd(far, 3, 4, 0)
+    counts = np.bincount(build.assign_clusters(far, C), minlength=3)
+    assert counts.sum() == 501 and np.isfinite(C).all()
+
+
 def test_coarse_probe_matches_direct_loop():
     X, Q, ix = _tiny()
     Qr = search.rotate_queries(Q, ix["P"])
