@@ -399,6 +399,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 3) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "max_batch") && value >= 0 && value <= 0x7fffffff) { ix->max_batch = value; return RABITQ_OK; }
+  if (!std::strcmp(name, "scan_segment_tiles") && value >= 0 && value <= 4096) { ix->seg_tiles = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
     ix->prof_mask = (unsigned)value;
     ix->prof_used = 0;
@@ -631,7 +632,10 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
   }
   RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst,
                                       early_clear));
-  if (ix->prune) {
+  // With one probed list and 1-bit codes the threshold would be the k-th smallest estimate of that very list: the
+  // scan's own top-k selects the same vectors, so the seeding pass (a second read of the list) is left out.
+  const bool seed = ix->prune && !(nprobe == 1 && ix->total_bits == 1);
+  if (seed) {
     RQ_STAGE(5, st, launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
   } else {
     RQ_STAGE(5, st, launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));

@@ -338,7 +338,11 @@ struct WaveTopK {
       const uint64_t x = readlane_u64(key, src);
       if (x < kth) {  // the K-th key may have dropped since the ballot
         const int p = __popcll(__ballot(v < x));  // keys below x; x goes to position p (< K)
-        const uint64_t up = shfl_u64(v, lane > 0 ? lane - 1 : 0);
+        // every lane's left neighbour through the data-parallel primitive that shifts the whole wavefront by one
+        // lane (lane 0 keeps its own value, which it never needs: it takes x or stays)
+        const uint32_t ulo = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, 0x138, 0xF, 0xF, false);
+        const uint32_t uhi = (uint32_t)__builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32), 0x138, 0xF, 0xF, false);
+        const uint64_t up = ((uint64_t)uhi << 32) | ulo;
         v = lane < p ? v : (lane == p ? x : up);
         kth = readlane_u64(v, K - 1);
       }
@@ -465,6 +469,35 @@ __device__ inline float refine_lane(const uint32_t* __restrict__ row, const floa
       if (w < LW) acc += dot_word<F>(row[w], qf + w * DPW);
     }
   }
+  return acc;
+}
+
+// The same in two steps, so that the words of the next candidate can be requested before the current one is
+// worked on: refine_load only issues loads (every address is inside the row, whatever t), refine_dot consumes them.
+template <int F, int LW>
+__device__ inline void refine_load(const uint32_t* __restrict__ row, int t, uint32_t (&w)[RefineShape<LW>::WPL]) {
+  constexpr int WPL = RefineShape<LW>::WPL;
+  const int w0 = t * WPL;
+  if (WPL % 4 == 0 && LW % 4 == 0) {
+#pragma unroll
+    for (int c = 0; c < WPL / 4; ++c) {
+      const uint4 v = *reinterpret_cast<const uint4*>(row + min(w0 + 4 * c, LW - 4));
+      w[4 * c] = v.x; w[4 * c + 1] = v.y; w[4 * c + 2] = v.z; w[4 * c + 3] = v.w;
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < WPL; ++i) w[i] = row[min(w0 + i, LW - 1)];
+  }
+}
+
+template <int F, int LW>
+__device__ inline float refine_dot(const uint32_t (&w)[RefineShape<LW>::WPL], const float* qf, int t) {
+  constexpr int WPL = RefineShape<LW>::WPL, DPW = 32 / F;
+  const int w0 = t * WPL;
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < WPL; ++i)
+    if (w0 + i < LW) acc += dot_word<F>(w[i], qf + (w0 + i) * DPW);
   return acc;
 }
 

@@ -68,6 +68,7 @@ struct rabitq_index {
   int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl)
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   int64_t max_batch = 0;  // queries per pass of rabitq_search; 0 = from the workspace budget
+  int seg_tiles = 0;      // tiles per scan work item of a long list; 0 = chosen from the batch (see launch_scan)
   // second stream of a search (default priority) and the events that fork it from and join it to the caller's
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;

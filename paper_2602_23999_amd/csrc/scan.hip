@@ -385,7 +385,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int seglen = (tc1 - t0 + nseg - 1) / nseg;
   const int ts = t0 + sidx * seglen, te = min(tc1, ts + seglen);
   const int pbeg = a.pair_off[c] + grp * QW;
-  const int np = min(QW, a.pair_off[c + 1] - pbeg);
+  const int np = __builtin_amdgcn_readfirstlane(min(QW, a.pair_off[c + 1] - pbeg));  // the same in all lanes
 
   constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead
   uint32_t pw[PD > 0 ? PD : 1][W];
@@ -474,25 +474,53 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   __syncthreads();
 
   int list_cnt = 0;
+  // Streaming variant with 1-bit codes and k <= 64: the k best keys of each pair are kept in registers (lane l holds
+  // the l-th smallest), so a list that is read once is also selected from in one pass, without the LDS pools and their
+  // sorts; its k-th key tightens the filter as the pools' compaction does.
+  constexpr bool REGK_VARIANT = (F == 0 && PFD > 0);
+  const bool regk = REGK_VARIANT && a.k <= 64;
+  WaveTopK top[QW];
+  bool started[QW];
+#pragma unroll
+  for (int j = 0; j < QW; ++j) {
+    top[j].v = KEY_NONE;
+    started[j] = false;
+  }
 
-  // refine everything in the list (F > 0 only); wave-uniform control flow throughout
+  // refine everything in the list (F > 0 only); wave-uniform control flow throughout.  Nothing is fetched under a
+  // condition: a lane without a candidate repeats the list's last one, so a round's code words, factors and id are
+  // requested together, and the next round's are requested before the current round is worked on.
+  struct Cand {
+    uint32_t w[RefineShape<LW>::WPL];
+    float2 lf;
+    int id, j;
+    bool valid;
+  };
+  auto request = [&](int base, Cand& c_) {
+    const int idx = base + lane / G;
+    c_.valid = idx < list_cnt;
+    const uint32_t e = list[min(idx, list_cnt - 1)];
+    c_.j = (int)(e >> 30);
+    const int64_t slot = (int64_t)t0 * TILE + (e & 0x3fffffffu);
+    refine_load<FF, LW>(a.long_codes + slot * LW, lane % G, c_.w);
+    c_.lf = *reinterpret_cast<const float2*>(a.long_factors + 2 * slot);
+    c_.id = a.ids[slot];
+  };
   auto flush = [&]() {
     __syncthreads();
     RQ_STAT(0, list_cnt);
     RQ_STAT(3, 1);
+    Cand nxt;
+    if (list_cnt > 0) request(0, nxt);
     for (int base = 0; base < list_cnt; base += NS) {
       RQ_STAT(1, 1);
-      const int idx = base + lane / G, t = lane % G;
-      const bool valid = idx < list_cnt;
-      const uint32_t e = valid ? list[idx] : 0u;
-      const int j = (int)(e >> 30);
-      const int64_t slot = (int64_t)t0 * TILE + (e & 0x3fffffffu);
-      float part = 0.f;
-      if (valid) part = refine_lane<FF, LW>(a.long_codes + slot * LW, qf + j * a.D, t);
-      const float ip = group_sum<G>(part);
-      if (valid && t == 0) {
-        const float eB = qs[2 * j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - qs[2 * j + 1]);
-        const uint64_t key = make_key(eB, (uint32_t)a.ids[slot]);
+      const Cand cur = nxt;
+      if (base + NS < list_cnt) request(base + NS, nxt);
+      const int t = lane % G, j = cur.j;
+      const float ip = group_sum<G>(refine_dot<FF, LW>(cur.w, qf + j * a.D, t));
+      if (cur.valid && t == 0) {
+        const float eB = qs[2 * j] + cur.lf.x + cur.lf.y * (ip - qs[2 * j + 1]);
+        const uint64_t key = make_key(eB, (uint32_t)cur.id);
         if (key <= pool_kth[j]) {
           const int pos = atomicAdd(&pool_cnt[j], 1);
           pools[(size_t)j * a.pool + pos] = key;
@@ -539,10 +567,15 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     const float fa = fq[0], fr = fq[1], fe = fq[2];
     // The plane words are re-read through the scalar cache for every (tile, query): an
     // opaque zero keeps the compiler from hoisting QW*4*W scalar registers out of the loop.
-    int opaque0;
-    asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
+    // (the streaming variant runs one or two queries per item and waits for memory, not for registers: there the
+    // plane words may stay in scalar registers across tiles)
+    int opaque0 = 0;
+    if (!(PFD > 0 && W <= 4)) asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
 #pragma unroll
     for (int j = 0; j < QW; ++j) {
+      // pairs the item does not have (the last group of a list; most groups when a list is probed by one or two
+      // queries only) are not estimated at all
+      if (j >= np) break;
       const_u32_ptr pl = (const_u32_ptr)(a.planes + qj[j] * 4 * W + opaque0);
       int I;
       float e1;
@@ -562,6 +595,18 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       if (m == 0ull) continue;
       const int ns = __popcll(m);
       const int before = __popcll(m & ((1ull << lane) - 1ull));
+      if (REGK_VARIANT && regk) {
+        const uint64_t key = surv ? make_key(e1, (uint32_t)((tile - t0) * TILE + lane)) : KEY_NONE;
+        if (!started[j]) {
+          top[j].init_sorted(key, lane);
+          started[j] = true;
+        } else {
+          top[j].push_tile(key, a.k, lane);
+        }
+        const uint64_t kth = readlane_u64(top[j].v, a.k - 1);
+        if (kth != KEY_NONE) tauj[j] = fminf(tauj[j], ord2f((uint32_t)(kth >> 32)));
+        continue;
+      }
       if (F == 0) {
         // B == 1: the 1-bit estimate is the final key
         uint64_t* pool = pools + (size_t)j * a.pool;
@@ -570,7 +615,9 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
           // exact tightening: keys above the k-th best of this pair cannot be in its top-k
           if (cnt[j] >= a.k) tauj[j] = fminf(tauj[j], ord2f((uint32_t)(pool[a.k - 1] >> 32)));
         }
-        if (surv) pool[cnt[j] + before] = make_key(e1, (uint32_t)a.ids[(int64_t)tile * TILE + lane]);
+        // (the key's low word is the vector's position in its list, which needs no load; the id replaces it when the
+        // pool is written out.  Lists hold their vectors in ascending id order, so equal estimates rank alike.)
+        if (surv) pool[cnt[j] + before] = make_key(e1, (uint32_t)((tile - t0) * TILE + lane));
         cnt[j] += ns;
       } else {
         if (list_cnt + ns > LIST_CAP) flush();
@@ -587,6 +634,16 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   // every key still in a pool goes out, unsorted; the per-query merge selects among them.
   // The segments of a split cluster share the pair's region (cand_cnt starts at 0 and is
   // advanced atomically), each contributing at most k keys so that the region cannot overflow.
+  if (REGK_VARIANT && regk) {
+    // the register lists go out through the pools' memory, so that one output path serves both
+#pragma unroll
+    for (int j = 0; j < QW; ++j) {
+      if (j >= np) break;
+      const bool have = lane < a.k && top[j].v != KEY_NONE;
+      cnt[j] = __popcll(__ballot(have));
+      if (have) pools[(size_t)j * a.pool + lane] = top[j].v;  // sorted: the present keys are the first cnt lanes
+    }
+  }
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
@@ -603,14 +660,19 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 #pragma unroll
     for (int j = 1; j < QW; ++j)
       if (lane == j) pp = pj[j];
-    base_l = atomicAdd(&a.cand_cnt[pp], mine);
+    if (nseg > 1) base_l = atomicAdd(&a.cand_cnt[pp], mine);
+    else a.cand_cnt[pp] = mine;  // the only work item of this pair: its region starts at 0 and nobody else counts
   }
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     if (j >= np) break;
     const uint64_t* pool = pools + (size_t)j * a.pool;
     const int base = __builtin_amdgcn_readlane(base_l, j);
-    for (int e = lane; e < cnt[j]; e += 64) a.cand_keys[(int64_t)pj[j] * a.cand_stride + base + e] = pool[e];
+    for (int e = lane; e < cnt[j]; e += 64) {
+      uint64_t key = pool[e];
+      if (F == 0) key = (key & 0xffffffff00000000ull) | (uint32_t)a.ids[(int64_t)t0 * TILE + (uint32_t)key];
+      a.cand_keys[(int64_t)pj[j] * a.cand_stride + base + e] = key;
+    }
   }
 }
 

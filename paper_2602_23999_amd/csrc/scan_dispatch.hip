@@ -149,6 +149,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     const int64_t est_items = std::min<int64_t>(np_all, (np_all + qw - 1) / qw + ix->nlist);
     const int64_t avg_tiles = std::max<int64_t>(1, ix->n_tiles / std::max(1, ix->nlist));
     a.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
+    if (ix->seg_tiles > 0) a.tseg = ix->seg_tiles;
   }
   a.segmax = std::max(1, a.cand_stride / k);
   a.streaming = (nq * nprobe <= 4 * (int64_t)ix->nlist) ? 1 : 0;

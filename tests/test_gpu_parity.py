@@ -205,6 +205,21 @@ def test_search_end_to_end(name, prune, impl):
         assert lost <= 1.15 * 0.0287 + 3.0 * np.sqrt(0.0287 / max(members, 1)), (lost, members)
 
 
+@pytest.mark.parametrize("name,k,nq", [("tiny_b1", 10, 9), ("tiny_b1", 100, 7), ("l2_128_b4", 10, 5), ("l2_960_b5", 10, 3),
+                                       ("ragged_b2", 10, 1), ("l2_960_b1", 10, 2)])
+def test_few_pairs_per_list_variant(name, k, nq):
+    """A batch so small that a list is probed by one or two queries takes the scan variant that reads ahead and
+    (1-bit codes, k <= 64) keeps each pair's best keys in registers: the same results as the oracle's."""
+    c = case(name)
+    nprobe = c["nprobe"]
+    assert nq * nprobe <= 4 * c["ix"]["nlist"]          # the library's condition for that variant
+    c["gi"].set_option("scan_impl", 0)
+    for prune in (True, False):
+        ids, dist, why = search_explained(c["gi"], c["s"], c["Q"][:nq], k, nprobe, prune=prune)
+        own = c["s"].search(c["Q"][:nq], k, nprobe, prune=prune, detail=True)
+        check_against_own_run(c["s"], own, ids, dist, k, why)
+
+
 def test_edge_cases():
     c = case("tiny_b1")
     gi = c["gi"]
