@@ -115,26 +115,33 @@ def stored_traffic(workload, nprobe):
 def cpu_baseline(gi, Q, k, nprobe, budget_q=200):
     """The CPU oracle as it stands, on the index the GPU leg searched (exported from the device and re-indexed into
     the oracle's arrays) and the first min(nq, 200) of the same queries, on all host cores the process may use: the
-    queries are dealt to one thread per core (numpy releases the interpreter lock inside its loops)."""
-    from concurrent.futures import ThreadPoolExecutor
-    from oracle import build as obuild, search as osearch
+    queries are dealt to one worker process per core, each running the oracle's search unchanged.  The workers are
+    started afresh (spawn), load the index from a file and never touch the GPU."""
+    import multiprocessing as mp
+    import tempfile
+    from oracle import build as obuild, parallel as opar
     t0 = time.perf_counter()
     ix = obuild.unpack_device_layout(gi.export())
-    s = osearch.Searcher(ix)
-    t_prep = time.perf_counter() - t0
     cores = len(os.sched_getaffinity(0))
     nq = min(budget_q, Q.shape[0])
     parts = [p for p in np.array_split(np.arange(nq), cores) if len(p)]
-    times = []
-    with ThreadPoolExecutor(max_workers=len(parts)) as ex:
-        for _ in range(3):
-            t0 = time.perf_counter()
-            list(ex.map(lambda p: s.search(Q[p], k, nprobe), parts))
-            times.append(time.perf_counter() - t0)
+    with tempfile.TemporaryDirectory() as tmp:
+        path = os.path.join(tmp, "index.npz")
+        opar.save_index(path, ix)
+        del ix
+        with mp.get_context("spawn").Pool(len(parts), initializer=opar.init, initargs=(path,)) as pool:
+            assert all(pool.map(opar.ready, range(4 * len(parts))))   # every worker has loaded the index
+            t_prep = time.perf_counter() - t0
+            jobs = [(Q[p], k, nprobe) for p in parts]
+            times = []
+            for _ in range(3):
+                t0 = time.perf_counter()
+                pool.map(opar.run, jobs, chunksize=1)
+                times.append(time.perf_counter() - t0)
     return dict(value=nq / float(np.median(times)), unit="queries/s", cores=len(parts), kind="oracle",
-                sample=f"the index of the GPU leg (rabitq_index_export -> oracle arrays, {t_prep:.1f}s, not timed), the "
-                       f"first {nq} of its queries, k={k}, nprobe={nprobe}, median of 3; numpy fp64, deliberately "
-                       f"unoptimised, {len(parts)} threads on {cores} host cores")
+                sample=f"the index of the GPU leg (rabitq_index_export -> oracle arrays -> {len(parts)} worker processes, "
+                       f"{t_prep:.1f}s, not timed), the first {nq} of its queries, k={k}, nprobe={nprobe}, median of 3; "
+                       f"numpy fp64, deliberately unoptimised, one process per host core ({cores} available)")
 
 
 def build_index(Xd, w, bits, eps0):

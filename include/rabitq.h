@@ -187,6 +187,11 @@ int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq
  *             returns to it.  Smaller batches stay on one stream.  0: always one stream.
  *   "max_batch" n: rabitq_search passes at most n queries through the pipeline at a time (0, the default:
  *             as many as keep the workspace under 16 GiB, at least 256).
+ *   "small_batch" 1 (default): a batch of at most 64 queries goes through fused kernels that do the same work in fewer
+ *             launches (Section 4.2.2: latency at small batch sizes is launch-bound): the pair lists, the scan's
+ *             work-item table and the cleared counters come from one single-workgroup kernel, probe selection and
+ *             threshold seeding run in one kernel.  Results are identical to those of the general kernels.
+ *             0: always the general kernels.
  *   "scan_segment_tiles" n: a list longer than n tiles of 64 vectors is scanned by several work items of about n tiles
  *             each (at most cand_capacity(k) / k of them); 0 (default): chosen from the batch size, 2..32.
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per

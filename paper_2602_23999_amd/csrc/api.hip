@@ -298,9 +298,11 @@ int rabitq_index_upload(const rabitq_index_desc* d, rabitq_index_t* out, void* s
   RQ_UP(ix->rotation, d->rotation, (int64_t)D * D, float);
   RQ_UP(ix->centroids_t, ct.data(), (int64_t)D * nlist, float);
   RQ_UP(ix->centroid_sq, csq.data(), nlist, float);
-  if (rc == RABITQ_OK) rc = dev_alloc(&ix->tile_off, 2 * (int64_t)(nlist + 1));  // second half: scan work-item offsets
+  if (rc == RABITQ_OK) rc = dev_alloc(&ix->tile_off, tile_off_words(nlist));  // + scan work-item offsets + ticket
   if (rc == RABITQ_OK) {
-    he = hipMemcpyAsync(ix->tile_off, tile_off.data(), (size_t)(nlist + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st);
+    he = hipMemsetAsync(ix->tile_off, 0, (size_t)tile_off_words(nlist) * sizeof(int32_t), st);
+    if (he == hipSuccess)
+      he = hipMemcpyAsync(ix->tile_off, tile_off.data(), (size_t)(nlist + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st);
     if (he != hipSuccess) rc = hip_fail(he, "hipMemcpyAsync");
   }
   RQ_UP(ix->cluster_size, csize.data(), nlist, int32_t);
@@ -399,6 +401,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!std::strcmp(name, "scan_impl") && value >= 0 && value <= 3) { ix->scan_impl = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "max_batch") && value >= 0 && value <= 0x7fffffff) { ix->max_batch = value; return RABITQ_OK; }
+  if (!std::strcmp(name, "small_batch") && (value == 0 || value == 1)) { ix->small_batch = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "scan_segment_tiles") && value >= 0 && value <= 4096) { ix->seg_tiles = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
     ix->prof_mask = (unsigned)value;
@@ -411,6 +414,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
       ix->prof_sets.resize((size_t)value);
       for (size_t i = have; i < (size_t)value; ++i)
         for (int s2 = 0; s2 < rabitq_index::N_STAGES; ++s2) ix->prof_sets[i].b[s2] = ix->prof_sets[i].e[s2] = nullptr;
+      for (size_t i = have; i < (size_t)value; ++i) ix->prof_sets[i].rec = 0;
       for (size_t i = have; i < (size_t)value; ++i)
         for (int s2 = 0; s2 < rabitq_index::N_STAGES; ++s2) {
           RQ_HIP(hipEventCreate(&ix->prof_sets[i].b[s2]));
@@ -446,8 +450,9 @@ int rabitq_stage_ms(rabitq_index_t ix, float* out_ms, int32_t* out_calls) {
   double acc[rabitq_index::N_STAGES] = {0};
   for (int s = 0; s < rabitq_index::N_STAGES; ++s) {
     if (!((ix->prof_mask >> s) & 1u)) continue;  // not recorded: reported as 0
-    RQ_HIP(hipEventSynchronize(ix->prof_sets[n - 1].e[s]));
     for (int i = 0; i < n; ++i) {
+      if (!((ix->prof_sets[i].rec >> s) & 1u)) continue;  // this search ran the stage inside another one's kernel
+      RQ_HIP(hipEventSynchronize(ix->prof_sets[i].e[s]));
       float ms = 0.f;
       RQ_HIP(hipEventElapsedTime(&ms, ix->prof_sets[i].b[s], ix->prof_sets[i].e[s]));
       acc[s] += ms;
@@ -591,12 +596,16 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
                              int64_t* out_ids, float* out_dists, hipStream_t st, bool* forked) {
   int rc;
   rabitq_index::EventSet* ev = nullptr;  // event set of this call when it is being recorded
-  if (ix->prof_used < ix->prof_limit) ev = &ix->prof_sets[ix->prof_used++];
+  if (ix->prof_used < ix->prof_limit) {
+    ev = &ix->prof_sets[ix->prof_used++];
+    ev->rec = 0;
+  }
   // stage s runs between its begin and end events, both recorded on the stream the stage is put on
 #define RQ_STAGE(s, stream_, call)                                              \
   do {                                                                          \
     const bool on_ = ev && ((ix->prof_mask >> (s)) & 1u);                       \
     if (on_) RQ_HIP(hipEventRecord(ev->b[s], (stream_)));                       \
+    if (on_) ev->rec |= 1u << (s);                                              \
     if ((rc = (call)) != RABITQ_OK) return rc;                                  \
     if (on_) RQ_HIP(hipEventRecord(ev->e[s], (stream_)));                       \
   } while (0)
@@ -613,14 +622,27 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
     if ((rc = launch_clear_list_bitmap(nq, ix->nlist, w.list_scratch, ix->side)) != RABITQ_OK) return rc;
     if ((rc = launch_clear_counters(w.cand_cnt, nq * nprobe, ix->side)) != RABITQ_OK) return rc;
   }
-  RQ_STAGE(0, st, launch_rotate(ix, queries, w.q_rot, nq, st));
   rabitq_query_repr repr = w.repr;
   if (ix->scan_impl != 2) repr.lut = nullptr;  // tables are only built for the scan that reads them
-  RQ_STAGE(1, st, launch_query_prep(w.q_rot, nq, ix->dim, ix->F, repr, st));
-  RQ_STAGE(2, st, launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim, ix->metric == RABITQ_L2 ? 1 : 2,
-                              w.repr.sq_norm, ix->centroid_sq, st));
-  RQ_STAGE(3, st, launch_select_probes(w.scores, w.repr.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric,
-                                       w.probe_ids, w.probe_G, w.probe_E, st));
+  // a small batch is bound by the number of dependent launches (Section 4.2.2): it takes fused kernels
+  const bool small = ix->small_batch && nq <= SMALL_BATCH_MAX;
+  if (small) {
+    RQ_STAGE(0, st, launch_small_front(ix, queries, nq, w.q_rot, repr, w.scores, st));
+  } else {
+    RQ_STAGE(0, st, launch_rotate(ix, queries, w.q_rot, nq, st));
+    RQ_STAGE(1, st, launch_query_prep(w.q_rot, nq, ix->dim, ix->F, repr, st));
+    RQ_STAGE(2, st, launch_gemm(w.q_rot, ix->centroids_t, w.scores, nq, ix->nlist, ix->dim,
+                                ix->metric == RABITQ_L2 ? 1 : 2, w.repr.sq_norm, ix->centroid_sq, st));
+  }
+  // ... and, when the per-query selections fit one wavefront, everything up to the scan from a second one
+  const bool small_fused = small && nprobe <= 64 && k <= 64 && effective_impl(ix) != 2;
+  if (small_fused) {
+    RQ_STAGE(3, st, launch_small_select_seed(ix, w.repr, w.scores, nq, k, nprobe, w.probe_ids, w.probe_G, w.probe_E, w.tau,
+                                             w.pair_off, w.pair_ids, w.list_scratch, w.cand_cnt, st));
+  } else {
+    RQ_STAGE(3, st, launch_select_probes(w.scores, w.repr.sq_norm, ix->centroid_sq, nq, ix->nlist, nprobe, ix->metric,
+                                         w.probe_ids, w.probe_G, w.probe_E, st));
+  }
   // The pair lists and the scan's work-item table depend on the probes only, and so does the threshold seeding:
   // the former run on the handle's second stream beside the latter, and the scan kernel waits for both.
   hipStream_t lst = st;
@@ -630,12 +652,21 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
     RQ_HIP(hipStreamWaitEvent(lst, ix->ev_fork, 0));
     *forked = true;
   }
-  RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst,
-                                      early_clear));
+  // a small batch takes its lists, work-item offsets and cleared counters from one single-workgroup kernel
+  if (small_fused) {
+    // lists, thresholds, work-item table and counters are already there
+  } else if (small) {
+    RQ_STAGE(4, lst, launch_small_batch_lists(ix, w.probe_ids, nq, nprobe, k, w.pair_off, w.pair_ids, w.list_scratch,
+                                              w.cand_cnt, lst));
+  } else {
+    RQ_STAGE(4, lst, launch_build_lists(w.probe_ids, nq, nprobe, ix->nlist, w.pair_off, w.pair_ids, w.list_scratch, lst,
+                                        early_clear));
+  }
   // With one probed list and 1-bit codes the threshold would be the k-th smallest estimate of that very list: the
   // scan's own top-k selects the same vectors, so the seeding pass (a second read of the list) is left out.
   const bool seed = ix->prune && !(nprobe == 1 && ix->total_bits == 1);
-  if (seed) {
+  if (small_fused) {
+  } else if (seed) {
     RQ_STAGE(5, st, launch_seed(ix, w.repr, w.probe_ids, w.probe_G, w.probe_E, nq, k, nprobe, w.tau, st));
   } else {
     RQ_STAGE(5, st, launch_fill_f32(w.tau, nq, 3.402823466e+38f, st));
@@ -643,8 +674,9 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
   ScanStreams ss;
   ss.main = st; ss.setup = lst; ss.join = ix->ev_join;
   ss.counters_clear = early_clear;
-  if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; }
-  if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; }
+  ss.setup_done = small;
+  if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; ev->rec |= 1u << 6; }
+  if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; ev->rec |= 1u << 7; }
   if ((rc = launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids, w.tau, nq, k, nprobe, w.cand_keys,
                         w.cand_cnt, nullptr, nullptr, ss)) != RABITQ_OK)
     return rc;

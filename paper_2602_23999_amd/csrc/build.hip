@@ -510,7 +510,8 @@ int build_index_device(rabitq_index* ix, const float* data, const float* rotatio
   RQ_TRY(launch_group_rows(asg.p, N, nlist, off.p, members.p, hist.p, total.p, st));
   // layout: cluster sizes, tile offsets (the total is needed on the host to size the arrays)
   RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->cluster_size), (size_t)nlist * sizeof(int32_t)));
-  RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->tile_off), (size_t)2 * (nlist + 1) * sizeof(int32_t)));
+  RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->tile_off), (size_t)tile_off_words(nlist) * sizeof(int32_t)));
+  RQ_HIP(hipMemsetAsync(ix->tile_off, 0, (size_t)tile_off_words(nlist) * sizeof(int32_t), st));
   hipLaunchKernelGGL(cluster_layout_kernel, dim3((nlist + 255) / 256), dim3(256), 0, st, off.p, nlist, ix->cluster_size);
   std::vector<int32_t> h_off(nlist + 1), h_tile(nlist + 1);
   RQ_HIP(hipMemcpyAsync(h_off.data(), off.p, (size_t)(nlist + 1) * sizeof(int32_t), hipMemcpyDeviceToHost, st));

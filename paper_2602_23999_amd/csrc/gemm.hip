@@ -3,7 +3,7 @@
 //   coarse scores   s_q 1^T + 1 s_c^T - 2 Q' C^T   (Section 3.3.2)
 // fp32 inputs are kept (v_mfma_f32_32x32x2_f32): the rotated query feeds an integer
 // quantisation and the estimator, so reduced-precision inputs are not an option.
-#include "rq_internal.h"
+#include "rq_device.h"
 
 namespace rq {
 
@@ -89,6 +89,159 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
       C[m * (int64_t)N + n] = v;
     }
   }
+}
+
+// ---------------------------------------------------------------------------------
+// Small batches (Section 4.2.2: latency at small batch sizes): rotation, per-query representation and coarse scores
+// in ONE launch.  A workgroup takes 32 queries and 128 lists.  Every workgroup first rotates its 32 queries itself
+// (each wavefront a 32 x 32 block of Q' at a time, operands straight from memory) and keeps Q' in LDS; the
+// workgroups of the first list group also store Q', and the list groups share the queries' representation.  Then each wavefront
+// contracts Q' with 32 centroids.  Both contractions issue v_mfma_f32_32x32x2_f32 over k = 0, 2, 4, ... exactly as
+// gemm_kernel does and finish with the same expressions, so every number is the one the three separate kernels
+// produce, bit for bit.
+// ---------------------------------------------------------------------------------
+template <int F>
+__global__ __launch_bounds__(256) void small_front_kernel(const float* __restrict__ queries, int nq, int D, int nlist,
+                                                          const float* __restrict__ P, const float* __restrict__ mean_rot,
+                                                          const float* __restrict__ ct, const float* __restrict__ csq,
+                                                          int metric, float* __restrict__ q_rot, rabitq_query_repr o,
+                                                          float* __restrict__ scores) {
+  extern __shared__ float qs[];  // [32][D + 1] rotated queries, then [32] squared norms
+  const int ld = D + 1;
+  float* s_sq = qs + 32 * ld;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m0 = 32 * blockIdx.y;
+  const int half = lane >> 5, l32 = lane & 31;
+  // rotation: block cb of Q' = rows m0.. x columns 32cb..
+  for (int cb = wave; cb < D / 32; cb += 4) {
+    floatx16 acc = {0};
+    const bool row_ok = m0 + l32 < nq;
+    const float* a_ptr = queries + (int64_t)(row_ok ? m0 + l32 : 0) * D + half;  // (an absent row reads row 0, unused)
+    const float* b_ptr = P + (int64_t)half * D + 32 * cb + l32;
+    // (a small batch waits for memory round trips, not for the matrix cores: the operands of the next 32 values of
+    // k are requested before the current 32 are multiplied; D is a multiple of 32)
+    constexpr int KU = 16;
+    auto load = [&](float (&a_)[KU], float (&b_)[KU], int k0) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        a_[u] = a_ptr[k0 + 2 * u];
+        b_[u] = b_ptr[(int64_t)(k0 + 2 * u) * D];
+      }
+    };
+    auto mma = [&](float (&a_)[KU], float (&b_)[KU]) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) {
+        a_[u] = pinned(a_[u]);
+        b_[u] = pinned(b_[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < KU; ++u) acc = __builtin_amdgcn_mfma_f32_32x32x2f32(row_ok ? a_[u] : 0.f, b_[u], acc, 0, 0, 0);
+    };
+    float a0[KU], b0[KU], a1[KU], b1[KU];
+    load(a0, b0, 0);
+    for (int k0 = 0;;) {
+      if (k0 + 32 < D) load(a1, b1, k0 + 32);
+      mma(a0, b0);
+      k0 += 32;
+      if (k0 >= D) break;
+      if (k0 + 32 < D) load(a0, b0, k0 + 32);
+      mma(a1, b1);
+      k0 += 32;
+      if (k0 >= D) break;
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = 8 * (r >> 2) + 4 * half + (r & 3), col = 32 * cb + l32;
+      float v = acc[r];
+      if (mean_rot != nullptr) v = v - mean_rot[col];
+      qs[row * ld + col] = v;
+      if (blockIdx.x == 0 && m0 + row < nq) q_rot[(int64_t)(m0 + row) * D + col] = v;
+    }
+  }
+  __syncthreads();
+  // squared norms of the queries that exist (every workgroup, for its scores); the representation of query r is
+  // stored by the workgroup of list group r mod gridDim.x, so that the list groups share that work
+  const int nrows = min(32, nq - m0);
+  for (int row = wave; row < nrows; row += 4) {
+    float amax, s1, s2;
+    prep_reduce(qs + row * ld, D, lane, amax, s1, s2);
+    if (lane == 0) s_sq[row] = s2;
+  }
+  for (int row = (int)blockIdx.x + (int)gridDim.x * wave; row < nrows; row += (int)gridDim.x * 4)
+    query_prep_row<F>(qs + row * ld, m0 + row, D, o, lane);
+  __syncthreads();
+  // coarse scores: this wavefront's 32 lists
+  {
+    const int c0 = 128 * blockIdx.x + 32 * wave;
+    if (c0 >= nlist) return;
+    floatx16 acc = {0};
+    const int col = c0 + l32;
+    const bool col_ok = col < nlist;
+    const float* b_ptr = ct + (int64_t)half * nlist + min(col, nlist - 1);
+    const float* a_ptr = qs + l32 * ld + half;
+    constexpr int KU = 16;
+    auto load = [&](float (&b_)[KU], int k0) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) b_[u] = b_ptr[(int64_t)(k0 + 2 * u) * nlist];
+    };
+    auto mma = [&](float (&b_)[KU], int k0) {
+#pragma unroll
+      for (int u = 0; u < KU; ++u) b_[u] = pinned(b_[u]);
+#pragma unroll
+      for (int u = 0; u < KU; ++u)
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a_ptr[k0 + 2 * u], col_ok ? b_[u] : 0.f, acc, 0, 0, 0);
+    };
+    float b0[KU], b1[KU];
+    load(b0, 0);
+    for (int k0 = 0;;) {
+      if (k0 + 32 < D) load(b1, k0 + 32);
+      mma(b0, k0);
+      k0 += 32;
+      if (k0 >= D) break;
+      if (k0 + 32 < D) load(b0, k0 + 32);
+      mma(b1, k0);
+      k0 += 32;
+      if (k0 >= D) break;
+    }
+    const float cv = col_ok ? csq[col] : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = 8 * (r >> 2) + 4 * half + (r & 3);
+      if (m0 + row >= nq || !col_ok) continue;
+      float v = acc[r];
+      if (metric == RABITQ_L2) {
+        const float rv = s_sq[row];
+        v = rv + cv - 2.0f * v;
+      } else {
+        v = -v;
+      }
+      scores[(int64_t)(m0 + row) * nlist + col] = v;
+    }
+  }
+}
+
+int launch_small_front(const rabitq_index* ix, const float* queries, int64_t nq, float* q_rot, const rabitq_query_repr& o,
+                       float* scores, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  const int D = ix->dim;
+  const size_t smem = (size_t)(32 * (D + 1) + 32) * sizeof(float);
+  dim3 grid((unsigned)((ix->nlist + 127) / 128), (unsigned)((nq + 31) / 32));
+#define RQ_SF(F_)                                                                                                        \
+  {                                                                                                                      \
+    if (smem > 64 * 1024) RQ_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(small_front_kernel<F_>),             \
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));            \
+    hipLaunchKernelGGL(small_front_kernel<F_>, grid, dim3(256), smem, st, queries, (int)nq, D, ix->nlist, ix->rotation,  \
+                       ix->mean_rot, ix->centroids_t, ix->centroid_sq, ix->metric, q_rot, o, scores);                    \
+  }
+  switch (ix->F) {
+    case 0: RQ_SF(0) break;
+    case 2: RQ_SF(2) break;
+    case 4: RQ_SF(4) break;
+    default: RQ_SF(8) break;
+  }
+#undef RQ_SF
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
 }
 
 int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,

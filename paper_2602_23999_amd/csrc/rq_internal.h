@@ -51,7 +51,7 @@ struct rabitq_index {
   std::vector<float> host_mean;     // [D] the mean itself (empty: not centred)
   float* centroids_t = nullptr;     // [D][nlist]  (transposed c')
   float* centroid_sq = nullptr;     // [nlist]
-  int32_t* tile_off = nullptr;      // [nlist+1]
+  int32_t* tile_off = nullptr;      // [nlist+1] tile offsets | [nlist+1] scan work-item offsets | [TICKET_WORDS] zeroed ticket
   int32_t* cluster_size = nullptr;  // [nlist]
   uint32_t* short_codes = nullptr;
   float* short_factors = nullptr;
@@ -68,12 +68,15 @@ struct rabitq_index {
   int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl)
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   int64_t max_batch = 0;  // queries per pass of rabitq_search; 0 = from the workspace budget
+  int small_batch = 1;    // batches of at most SMALL_BATCH_MAX queries take the fused low-launch-count kernels
   int seg_tiles = 0;      // tiles per scan work item of a long list; 0 = chosen from the batch (see launch_scan)
   // second stream of a search (default priority) and the events that fork it from and join it to the caller's
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   static constexpr int N_STAGES = 9;
-  struct EventSet { hipEvent_t b[N_STAGES], e[N_STAGES]; };  // begin / end of every stage, on the stream it ran on
+  // begin / end of every stage, on the stream it ran on; bit s of `rec`: stage s was recorded in this search (a
+  // small batch runs several stages as one kernel, recorded under the first of them)
+  struct EventSet { hipEvent_t b[N_STAGES], e[N_STAGES]; unsigned rec; };
   std::vector<EventSet> prof_sets;  // one per recorded search
   int prof_used = 0, prof_limit = 0;
   unsigned prof_mask = 0x1ffu;  // stages whose events are recorded (bit s = stage s)
@@ -113,6 +116,10 @@ __host__ __device__ inline float ord2f(uint32_t o) {
 // mode 4 (rotation of a centred index): C = acc - colv[n].
 int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int K, int mode, const float* rowv,
                 const float* colv, hipStream_t st);
+// small batches: Q' = (Q - mean) P, the queries' representation and the coarse scores [nq][nlist] from one launch,
+// bit-identical to launch_rotate + launch_query_prep + launch_gemm (mode 1 / 2)
+int launch_small_front(const rabitq_index* ix, const float* queries, int64_t nq, float* q_rot, const rabitq_query_repr& o,
+                       float* scores, hipStream_t st);
 int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st);
 int launch_select_probes(const float* scores, const float* sq_norm, const float* centroid_sq, int64_t nq, int nlist,
                          int nprobe, int metric, int32_t* probe_ids, float* probe_G, float* probe_E, hipStream_t st);
@@ -131,7 +138,25 @@ struct ScanStreams {
   hipEvent_t join = nullptr;
   hipEvent_t setup_b = nullptr, setup_e = nullptr, scan_b = nullptr, scan_e = nullptr;
   bool counters_clear = false;  // cand_cnt was already zeroed by launch_clear_counters
+  bool setup_done = false;      // work-item offsets and counters were already prepared (launch_small_batch_lists)
 };
+// How a scan launch cuts its work: pairs per work item, tiles per segment of a long list, segments per list at most.
+struct ScanPlan { int qw, tseg, segmax; };
+ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k);
+// Batches of at most SMALL_BATCH_MAX queries: pair lists, the scan's work-item offsets and the cleared candidate
+// counters from ONE single-workgroup kernel (instead of the seven launches of launch_build_lists + the scan set-up).
+// `scratch` holds at least 2 * nlist words.  Same pair_off / pair_ids as launch_build_lists.
+constexpr int SMALL_BATCH_MAX = 64;
+constexpr int TICKET_WORDS = 4;  // words behind the two offset arrays of rabitq_index::tile_off (zero between launches)
+inline int64_t tile_off_words(int nlist) { return 2 * (int64_t)(nlist + 1) + TICKET_WORDS; }
+// The same for nprobe <= 64, k <= 64 and a bitwise scan, preceded in the same kernel by the selection of the probes
+// from the coarse scores and the seeding of the thresholds (one workgroup per query; the last one to finish builds the
+// lists): everything between the coarse scores and the scan in one launch.
+int launch_small_select_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const float* scores, int64_t nq, int k,
+                             int nprobe, int32_t* probe_ids, float* probe_G, float* probe_E, float* tau, int32_t* pair_off,
+                             int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt, hipStream_t st);
+int launch_small_batch_lists(const rabitq_index* ix, const int32_t* probe_ids, int64_t nq, int nprobe, int k,
+                             int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt, hipStream_t st);
 int launch_clear_counters(int32_t* cand_cnt, int64_t n, hipStream_t st);
 int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,

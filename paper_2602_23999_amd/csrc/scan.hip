@@ -3,6 +3,7 @@
 
 #include "rq_device.h"
 #include "rq_scan_args.h"
+#include "rq_small_batch.h"
 
 namespace rq {
 
@@ -172,19 +173,10 @@ __global__ __launch_bounds__(256) void seed_kernel(ScanArgs a) {
 // ---------------------------------------------------------------------------------
 // SPLIT (small batches): the four wavefronts of a workgroup share one query, each streaming a quarter of the
 // cluster; their sorted lists meet in LDS and the first wavefront finishes alone.
+// The work of one query (SPLIT: of the four wavefronts that share it; every one of them must call, and they meet
+// at one barrier unless no probed cluster has k vectors, which all four find alike).
 template <int W, int F, bool SPLIT>
-__global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) {
-  __shared__ uint64_t s_lists[SPLIT ? 3 * 64 : 1];
-  // (the wavefront index is the same in all lanes: saying so lets everything indexed by the query be fetched
-  // through the scalar cache)
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of queries, so that
-  // neighbouring queries (which the caller may have grouped by nearest list) share one L2
-  // (the grid is the number of workgroups rounded up to a multiple of 8)
-  const int per = (int)(gridDim.x >> 3);
-  const int blk = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
-  const int64_t q = SPLIT ? (int64_t)blk : (int64_t)blk * 4 + wave;
-  if (q >= nq) return;
+__device__ inline void seed_wave_body(const ScanArgs& a, int64_t q, int lane, int wave, uint64_t* s_lists) {
   // Lane j looks at probe j: everything the chosen probe contributes (cluster, coarse term, tile range) is fetched
   // for all probes at once and read from the chosen lane, so the walk to the first tile is two dependent loads deep.
   int rank = -1, t0 = 0, t1 = 0, n_c = 0;
@@ -324,6 +316,66 @@ __global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) 
   fin.init_sorted(rkey, lane);
   const uint64_t kth = readlane_u64(fin.v, a.k - 1);
   if (lane == 0) a.tau_out[q] = fminf(ord2f((uint32_t)(kth >> 32)), 3.402823466e+38f);
+}
+
+template <int W, int F, bool SPLIT>
+__global__ __launch_bounds__(256) void seed_wave_kernel(ScanArgs a, int64_t nq) {
+  __shared__ uint64_t s_lists[SPLIT ? 3 * 64 : 1];
+  // (the wavefront index is the same in all lanes: saying so lets everything indexed by the query be fetched
+  // through the scalar cache)
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  // workgroups are dealt round-robin to the 8 XCDs: give each XCD a contiguous range of queries, so that
+  // neighbouring queries (which the caller may have grouped by nearest list) share one L2
+  // (the grid is the number of workgroups rounded up to a multiple of 8)
+  const int per = (int)(gridDim.x >> 3);
+  const int blk = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  const int64_t q = SPLIT ? (int64_t)blk : (int64_t)blk * 4 + wave;
+  if (q >= nq) return;
+  seed_wave_body<W, F, SPLIT>(a, q, lane, wave, s_lists);
+}
+
+// ---------------------------------------------------------------------------------
+// Small batches: cluster selection (Section 3.3.2) and threshold seeding (Section 3.3.4) of one query by one
+// workgroup, and, by the workgroup that finishes last, the pair lists and the scan's work-item table of the whole
+// batch.  Nobody waits for anybody: a workgroup takes a ticket when it is done, and the holder of the last ticket
+// knows that every other workgroup's probes are in memory.  The code of each step is the general kernels' own.
+// ---------------------------------------------------------------------------------
+template <int W, int F>
+__global__ __launch_bounds__(256) void small_select_seed_kernel(ScanArgs a, SmallSelectArgs b) {
+  __shared__ uint64_t s_lists[3 * 64];
+  __shared__ uint32_t s_pairs[256], s_items[256];
+  __shared__ int s_last;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane((int)(tid >> 6));
+  const int64_t q = blockIdx.x;
+  const int nprobe = a.nprobe;
+  if (wave == 0) {
+    const WaveTopK top = stream_select_smallest(b.scores + q * a.nlist, a.nlist, nprobe, lane);
+    if (lane < nprobe) {
+      const uint64_t key = top.v;
+      const int c = (int)(uint32_t)key;
+      const float sc = ord2f((uint32_t)(key >> 32));
+      b.probe_ids[q * nprobe + lane] = c;
+      b.probe_G[q * nprobe + lane] = sc;
+      const float d2 = (b.metric == RABITQ_L2) ? sc : (b.sq_norm[q] + b.centroid_sq[c] + 2.0f * sc);
+      b.probe_E[q * nprobe + lane] = sqrtf(fmaxf(d2, 0.f));
+    }
+  }
+  __syncthreads();  // the probes are in memory for the other wavefronts of the workgroup
+  if (b.do_seed) {
+    seed_wave_body<W, F, true>(a, q, lane, wave, s_lists);
+  } else if (tid == 0) {
+    a.tau_out[q] = 3.402823466e+38f;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    __threadfence();  // this workgroup's probes are visible to the device before its ticket is
+    s_last = atomicAdd(b.ticket, 1) == (int)gridDim.x - 1;
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // and the last workgroup reads everybody's probes from memory
+  small_lists_body<256>(b.lists, s_pairs, s_items);
+  if (tid == 0) *b.ticket = 0;  // ready for the next launch
 }
 
 // ---------------------------------------------------------------------------------
@@ -1100,6 +1152,26 @@ static void scan_by_f(const ScanArgs& a, int F, int impl, unsigned grid, bool db
 bool RQ_PART_NAME(seed)(const ScanArgs& a, int W, int F, int impl, int64_t nq, hipStream_t st) {
   switch (W) {
 #define RQ_X(W_) case W_: seed_by_f<W_>(a, F, impl, nq, st); return true;
+    RQ_W_LIST(RQ_X)
+#undef RQ_X
+    default: return false;
+  }
+}
+
+template <int W>
+static void small_by_f(const ScanArgs& a, const SmallSelectArgs& b, int F, hipStream_t st) {
+  const dim3 grid((unsigned)b.lists.nq), blk(256);
+  switch (F) {
+    case 0: hipLaunchKernelGGL((small_select_seed_kernel<W, 0>), grid, blk, 0, st, a, b); break;
+    case 2: hipLaunchKernelGGL((small_select_seed_kernel<W, 2>), grid, blk, 0, st, a, b); break;
+    case 4: hipLaunchKernelGGL((small_select_seed_kernel<W, 4>), grid, blk, 0, st, a, b); break;
+    default: hipLaunchKernelGGL((small_select_seed_kernel<W, 8>), grid, blk, 0, st, a, b); break;
+  }
+}
+
+bool RQ_PART_NAME(small)(const ScanArgs& a, const SmallSelectArgs& b, int W, int F, hipStream_t st) {
+  switch (W) {
+#define RQ_X(W_) case W_: small_by_f<W_>(a, b, F, st); return true;
     RQ_W_LIST(RQ_X)
 #undef RQ_X
     default: return false;

@@ -5,6 +5,7 @@
 
 #include "rq_internal.h"
 #include "rq_scan_args.h"
+#include "rq_small_batch.h"
 
 namespace rq {
 
@@ -45,6 +46,11 @@ __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __rest
   if (tid == 255) item_off[n] = (int32_t)part[255];
 }
 
+
+__global__ __launch_bounds__(1024) void small_batch_lists_kernel(SmallListArgs b) {
+  __shared__ uint32_t s_pairs[1024], s_items[1024];
+  small_lists_body<1024>(b, s_pairs, s_items);
+}
 
 static int field_bits(int B) {  // long-code field width: B rounded up to 2, 4, 8 (0: no long code)
   if (B <= 1) return 0;
@@ -118,6 +124,67 @@ int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int
   return RABITQ_OK;
 }
 
+// Long clusters are scanned in segments of about tseg tiles by separate work items; each segment of a split cluster
+// contributes at most k keys to the pair's region of cand_stride keys (cand_cnt is advanced atomically).  The segment
+// length adapts to the batch: a large batch has more work items than the chip has wavefront slots and keeps long
+// segments (32 tiles); a small batch is cut finer, down to 2 tiles, so that about 4096 items exist.
+ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
+  ScanPlan p;
+  p.qw = effective_impl(ix) == 1 ? QM : QW;
+  const int64_t np_all = nq * nprobe;
+  const int64_t est_items = std::min<int64_t>(np_all, (np_all + p.qw - 1) / p.qw + ix->nlist);
+  const int64_t avg_tiles = std::max<int64_t>(1, ix->n_tiles / std::max(1, ix->nlist));
+  p.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
+  if (ix->seg_tiles > 0) p.tseg = ix->seg_tiles;
+  p.segmax = std::max(1, next_pow2_host(k + TILE) / k);
+  return p;
+}
+
+static SmallListArgs small_list_args(const rabitq_index* ix, const int32_t* probe_ids, int64_t nq, int nprobe, int k,
+                                     int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt) {
+  const ScanPlan p = scan_plan(ix, nq, nprobe, k);
+  SmallListArgs b{};
+  b.probe_ids = probe_ids; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = ix->nlist; b.tile_off = ix->tile_off;
+  b.qw = p.qw; b.tseg = p.tseg; b.segmax = p.segmax; b.mask = scratch; b.pair_off = pair_off; b.pair_ids = pair_ids;
+  b.item_off = ix->tile_off + (ix->nlist + 1); b.cand_cnt = cand_cnt;
+  return b;
+}
+
+int launch_small_batch_lists(const rabitq_index* ix, const int32_t* probe_ids, int64_t nq, int nprobe, int k,
+                             int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  if (nq > SMALL_BATCH_MAX) { set_error("small-batch list builder: more than 64 queries"); return RABITQ_EINVAL; }
+  const SmallListArgs b = small_list_args(ix, probe_ids, nq, nprobe, k, pair_off, pair_ids, scratch, cand_cnt);
+  hipLaunchKernelGGL(small_batch_lists_kernel, dim3(1), dim3(1024), 0, st, b);
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
+int launch_small_select_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const float* scores, int64_t nq, int k,
+                             int nprobe, int32_t* probe_ids, float* probe_G, float* probe_E, float* tau, int32_t* pair_off,
+                             int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt, hipStream_t st) {
+  if (nq <= 0) return RABITQ_OK;
+  if (nq > SMALL_BATCH_MAX || nprobe > 64 || k > 64 || effective_impl(ix) == 2) {
+    set_error("fused selection + seeding: needs at most 64 queries, nprobe <= 64, k <= 64 and a bitwise scan");
+    return RABITQ_EINVAL;
+  }
+  ScanArgs a = base_args(ix);
+  set_repr(a, ix, repr);
+  a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
+  a.nprobe = nprobe; a.k = k; a.tau_out = tau;
+  SmallSelectArgs b{};
+  b.scores = scores; b.sq_norm = repr.sq_norm; b.centroid_sq = ix->centroid_sq; b.metric = ix->metric;
+  // (with one probed list and 1-bit codes the scan's own top-k selects what a seeded threshold would: no seeding)
+  b.do_seed = (ix->prune && !(nprobe == 1 && ix->total_bits == 1)) ? 1 : 0;
+  b.probe_ids = probe_ids; b.probe_G = probe_G; b.probe_E = probe_E;
+  b.ticket = ix->tile_off + 2 * (ix->nlist + 1);
+  b.lists = small_list_args(ix, probe_ids, nq, nprobe, k, pair_off, pair_ids, scratch, cand_cnt);
+  const int W = ix->W, F = field_bits(ix->total_bits);
+  if (!(small_part0(a, b, W, F, st) || small_part1(a, b, W, F, st) || small_part2(a, b, W, F, st))) return bad_width();
+  RQ_HIP(hipGetLastError());
+  return RABITQ_OK;
+}
+
 int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const float* probe_G, const float* probe_E,
                 const int32_t* pair_off, const int32_t* pair_ids, const float* tau, int64_t nq, int k, int nprobe,
                 uint64_t* cand_keys, int32_t* cand_cnt, int32_t* dbg_ip, const int64_t* dbg_off, const ScanStreams& ss) {
@@ -140,24 +207,17 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
   a.item_off = item_off;
-  // long clusters are scanned in segments of about tseg tiles by separate work items; each segment of a split
-  // cluster contributes at most k keys to the pair's region of cand_stride keys (cand_cnt is advanced atomically)
-  // The segment length adapts to the batch: a large batch has more work items than the chip has wavefront slots and
-  // keeps long segments (32 tiles); a small batch is cut finer, down to 2 tiles, so that about 4096 items exist.
-  {
-    const int64_t np_all = nq * nprobe;
-    const int64_t est_items = std::min<int64_t>(np_all, (np_all + qw - 1) / qw + ix->nlist);
-    const int64_t avg_tiles = std::max<int64_t>(1, ix->n_tiles / std::max(1, ix->nlist));
-    a.tseg = (int)std::min<int64_t>(32, std::max<int64_t>(2, est_items * avg_tiles / 4096));
-    if (ix->seg_tiles > 0) a.tseg = ix->seg_tiles;
-  }
-  a.segmax = std::max(1, a.cand_stride / k);
+  const ScanPlan plan = scan_plan(ix, nq, nprobe, k);
+  a.tseg = plan.tseg;
+  a.segmax = plan.segmax;
   a.streaming = (nq * nprobe <= 4 * (int64_t)ix->nlist) ? 1 : 0;
   if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
-  hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
-                     a.segmax, item_off);
-  if (!ss.counters_clear) {
-    if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
+  if (!ss.setup_done) {
+    hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
+                       a.segmax, item_off);
+    if (!ss.counters_clear) {
+      if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
+    }
   }
   if (ss.setup_e) RQ_HIP(hipEventRecord(ss.setup_e, sst));
   if (sst != st) {

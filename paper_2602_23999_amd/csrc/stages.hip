@@ -16,65 +16,7 @@ __global__ __launch_bounds__(256) void query_prep_kernel(const float* __restrict
   const int lane = threadIdx.x & 63;
   const int64_t q = (int64_t)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
   if (q >= nq) return;
-  const float* x = q_rot + q * D;
-  const int W = D >> 5;
-  const int Dp = (D + 63) / 64 * 64;
-  float amax = 0.f, s1 = 0.f, s2 = 0.f;
-  for (int i = lane; i < D; i += 64) {
-    const float v = x[i];
-    amax = fmaxf(amax, fabsf(v));
-    s1 += v;
-    s2 += v * v;
-    o.q_stage[q * D + (F == 0 ? i : stage_index<(F == 0 ? 8 : F)>(i))] = v;
-  }
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) {
-    amax = fmaxf(amax, __shfl_xor(amax, d, 64));
-    s1 += __shfl_xor(s1, d, 64);
-    s2 += __shfl_xor(s2, d, 64);
-  }
-  const float dl = (amax == 0.f) ? 1.0f : __fdiv_rn(amax, 7.0f);
-  int S = 0;
-  uint32_t* pl = o.planes + q * 4 * W;
-  for (int base = 0; base < Dp; base += 64) {
-    const int i = base + lane;
-    int qh = 0;
-    if (i < D && amax != 0.f) {
-      const float t = rintf(__fdiv_rn(x[i], dl));
-      qh = (int)fminf(fmaxf(t, -7.f), 7.f);
-    }
-    S += qh;
-    o.qhat8[q * Dp + i] = (int8_t)qh;
-    const uint32_t tc = (uint32_t)qh & 15u;
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const uint64_t m = __ballot((tc >> j) & 1u);
-      const int w = base >> 5;
-      if (lane == 0 && w < W) pl[j * W + w] = (uint32_t)m;
-      if (lane == 0 && w + 1 < W) pl[j * W + w + 1] = (uint32_t)(m >> 32);
-    }
-  }
-#pragma unroll
-  for (int d = 32; d > 0; d >>= 1) S += __shfl_xor(S, d, 64);
-  // Section 3.4.1(1): lookup tables, one entry per (block of 4 dimensions, 4-bit pattern); the sum runs in
-  // fp32 over the set bits in ascending dimension order and is rounded to binary16
-  if (o.lut != nullptr) {
-    _Float16* lut = reinterpret_cast<_Float16*>(o.lut) + q * (int64_t)D * 4;
-    for (int e = lane; e < D * 4; e += 64) {
-      const int j = e >> 4, b = e & 15;
-      float acc = 0.f;
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if ((b >> i) & 1) acc += x[4 * j + i];
-      lut[e] = (_Float16)acc;
-    }
-  }
-  if (lane == 0) {
-    o.delta[q] = dl;
-    o.sum_qhat[q] = S;
-    o.sum_q[q] = s1;
-    o.sq_norm[q] = s2;
-  }
+  query_prep_row<F>(q_rot + q * D, q, D, o, lane);
 }
 
 int launch_query_prep(const float* q_rot, int64_t nq, int D, int F, const rabitq_query_repr& out, hipStream_t st) {
@@ -170,53 +112,7 @@ __global__ __launch_bounds__(256) void select_probes_stream_kernel(const float* 
   const int64_t q = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (q >= nq) return;
   const float* row = scores + q * nlist;
-  WaveTopK top;
-  // The first 16 tiles (1024 scores) are held in registers: the 64 per-lane minima start the sorted list, so
-  // its nprobe-th key is small from the outset and few of the remaining scores have to be inserted.
-  constexpr int R = 16;
-  {
-    // (unconditional loads of clamped indices, all requested before the first value is touched: a load whose value
-    // is only used under a condition would otherwise be waited for before the next one is issued)
-    float sv[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) sv[r] = row[min(r * 64 + lane, nlist - 1)];
-#pragma unroll
-    for (int r = 0; r < R; ++r) sv[r] = pinned(sv[r]);
-    uint32_t ord[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) ord[r] = (r * 64 + lane < nlist) ? f2ord(sv[r]) : 0xffffffffu;
-    uint32_t mo = ord[0];
-    int mr = 0;
-#pragma unroll
-    for (int r = 1; r < R; ++r)
-      if (ord[r] < mo) { mo = ord[r]; mr = r; }  // ties keep the lower index, as the key order does
-    top.init_sorted(mo == 0xffffffffu ? KEY_NONE : (((uint64_t)mo << 32) | (uint32_t)(mr * 64 + lane)), lane);
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      if (r * 64 < nlist) {
-        const bool take = r != mr && ord[r] != 0xffffffffu;
-        top.push_tile(take ? (((uint64_t)ord[r] << 32) | (uint32_t)(r * 64 + lane)) : KEY_NONE, nprobe, lane);
-      }
-    }
-  }
-  // the rest of the row, eight tiles of scores in flight; a tile is only looked at closely when its smallest
-  // score beats the current nprobe-th key
-  for (int tb = R * 64; tb < nlist; tb += 512) {
-    float sc[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) sc[u] = row[min(tb + u * 64 + lane, nlist - 1)];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) sc[u] = pinned(sc[u]);
-#pragma unroll
-    for (int u = 0; u < 8; ++u) sc[u] = (tb + u * 64 + lane < nlist) ? sc[u] : INFINITY;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-      if (tb + u * 64 < nlist) {
-        const int i = tb + u * 64 + lane;
-        top.push_tile((i < nlist) ? make_key(sc[u], (uint32_t)i) : KEY_NONE, nprobe, lane);
-      }
-    }
-  }
+  const WaveTopK top = stream_select_smallest(row, nlist, nprobe, lane);
   if (lane < nprobe) {
     const uint64_t key = top.v;
     const int c = (int)(uint32_t)key;
