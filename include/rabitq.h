@@ -235,8 +235,10 @@ int rabitq_rotate(rabitq_index_t index, const float* queries, int64_t nq, float*
  *   planes   [nq][4][W] u32 two's-complement bit-planes of qhat (plane 3 weighs -8)
  *   delta    [nq] fp32  = max|q'|/7 (1 if q' == 0);  qhat = clamp(rint(q'/delta),-7,7)
  *   sum_qhat [nq] i32   = S;   sum_q [nq] fp32 = sum(q');   sq_norm [nq] fp32 = ||q'||^2
- *   qhat8    [nq][rabitq_qhat_stride(D)] i8: qhat as bytes, zero padded to a multiple of 64
- *            (the operand of the matrix-core variant of the scan)
+ *   qhat8    [nq][rabitq_qhat_stride(D)] i8: qhat as bytes, zero padded to a multiple of 64 dimensions (the
+ *            operand of the matrix-core variant of the scan), in the order that variant's expansion of the sign bits
+ *            produces: within every chunk of 64 dimensions, dimension 32 w + 8 b + 4 h + i (w, h in 0..1, b, i in
+ *            0..3) sits at byte 16 (2 w + h) + 4 i + b
  *   q_stage  [nq][D] fp32: q' in the order the refinement reads it (within each long-code
  *            word, dimension b*(8/F)+s of the word sits at position 4*s+b; identity if B == 1)
  *   lut      [nq][D/4][16] binary16 bit patterns, or NULL (then not written; required by

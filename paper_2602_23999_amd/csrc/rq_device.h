@@ -353,6 +353,14 @@ struct WaveTopK {
 template <int F>
 __host__ __device__ inline int stage_index(int d);  // position of dimension d in the refinement's query order (below)
 
+// Position of dimension d in the qhat8 array (the matrix-core scan's query operand).  Within every chunk of 64
+// dimensions, dimension r = 32 w + 8 b + 4 h + i (w: word of the chunk, b = 0..3, h = 0..1, i = 0..3) sits at byte
+// 16 (2 w + h) + 4 i + b: the order in which (word >> (4h + i)) & 0x01010101 delivers the sign bits of a code word.
+__host__ __device__ inline int qhat_mfma_pos(int d) {
+  const int c = d >> 6, r = d & 63, w = r >> 5, x = r & 31;
+  return 64 * c + 16 * (2 * w + ((x >> 2) & 1)) + 4 * (x & 3) + (x >> 3);
+}
+
 // ---------------------------------------------------------------------------------
 // Section 3.3.3 / 3.4.1(2): the per-query representation of one rotated query x[0..D), by one wavefront:
 // 4-bit signed quantisation and its bit-planes, sums, the query in refinement order, lookup tables.
@@ -394,7 +402,7 @@ __device__ inline void query_prep_row(const float* x, int64_t q, int D, const ra
       qh = (int)fminf(fmaxf(t, -7.f), 7.f);
     }
     S += qh;
-    o.qhat8[q * Dp + i] = (int8_t)qh;
+    o.qhat8[q * Dp + qhat_mfma_pos(i)] = (int8_t)qh;
     const uint32_t tc = (uint32_t)qh & 15u;
 #pragma unroll
     for (int j = 0; j < 4; ++j) {

@@ -733,7 +733,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 // <x_b, qhat> of Section 3.4.1(2) is a dense contraction once the batch is grouped by
 // cluster: (queries probing the cluster) x (vectors of the cluster) over D.  One wavefront
 // takes QM = 16 pairs of one cluster; per 64-vector tile it expands the sign bits to int8
-// once (nibble * 0x204081 & 0x01010101 spreads 4 bits over 4 bytes) and issues
+// once ((word >> s) & 0x01010101, four dimensions per two instructions) and issues
 // v_mfma_i32_16x16x64_i8 with the 16 queries' qhat bytes held in registers.  Accumulator
 // r of lane l is query 4*(l/16)+r, vector 16*cb + l%16 of the tile, so a lane keeps the
 // factors of its four vectors and the scalars of its four queries.  Everything after the
@@ -749,13 +749,18 @@ constexpr int MLIST_FLUSH = 128;              // an owner list longer than this 
 // + what one round of tiles can add: every wavefront a tile, 64 vectors x QM / n queries per owner
 __host__ __device__ constexpr int mlist_cap(int n) { return MLIST_FLUSH + n * TILE * (QM / n); }
 
-__device__ inline v4i expand16(uint32_t bits16) {  // 16 sign bits -> 16 bytes of 0/1
-  v4i v;
-  v.x = (int)(__umul24(bits16 & 15u, 0x204081u) & 0x01010101u);
-  v.y = (int)(__umul24((bits16 >> 4) & 15u, 0x204081u) & 0x01010101u);
-  v.z = (int)(__umul24((bits16 >> 8) & 15u, 0x204081u) & 0x01010101u);
-  v.w = (int)(__umul24((bits16 >> 12) & 15u, 0x204081u) & 0x01010101u);
-  return v;
+// 16 sign bits of a code word -> 16 bytes of 0/1 for the matrix instruction's B operand, at two instructions per
+// four bytes: (word >> s) & 0x01010101 leaves bits s, s+8, s+16, s+24 of the word in the four bytes.  The lane
+// group with half h (0 / 1) of a word takes the shifts s = 4h .. 4h+3, so byte b of its i-th operand word is dimension
+// 4h + i + 8b of the code word, and the query's qhat bytes are stored in that same order (qhat_mfma_pos).
+__device__ inline v4i expand_half(uint32_t word, int h) {
+  const uint32_t v = word >> (4 * h);
+  v4i x;
+  x.x = (int)(v & 0x01010101u);
+  x.y = (int)((v >> 1) & 0x01010101u);
+  x.z = (int)((v >> 2) & 0x01010101u);
+  x.w = (int)((v >> 3) & 0x01010101u);
+  return x;
 }
 
 __device__ inline void wave_sync() {  // orders LDS traffic among the lanes of one wavefront
@@ -847,7 +852,8 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   const int pbeg = a.pair_off[c] + grp * QM;
   const int np = min(QM, a.pair_off[c + 1] - pbeg);
 
-  // query operand: lane (row lj, k-group g) holds qhat[16g .. 16g+15] of every 64-dim chunk
+  // query operand: lane (row lj, k-group g) holds bytes 16g .. 16g+15 of every 64-dimension chunk of qhat8, which
+  // is stored in the order the expansion of the code words produces (qhat_mfma_pos)
   v4i qa[KC];
   {
     const int pp = a.pair_ids[pbeg + min(lj, np - 1)];
@@ -906,21 +912,38 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   };
 
   // F > 0: this wavefront refines its own list (queries j with j % MWAVES == wave) into its own pools
+  // (nothing is fetched under a condition: a lane without a candidate repeats the list's last one, so a round's code
+  // words, factors and id are requested together, and the next round's before the current round is worked on)
+  struct Cand {
+    uint32_t w[RefineShape<LW>::WPL];
+    float2 lf;
+    int id, j;
+    bool valid;
+  };
   auto flush_own = [&]() {
     uint32_t* list = lists + (size_t)wave * MLIST_CAP;
     const int list_cnt = s_list_cnt[wave];
-    for (int base = 0; base < list_cnt; base += NS) {
-      const int idx = base + lane / G, t = lane % G;
-      const bool valid = idx < list_cnt;
-      const uint32_t e = valid ? list[idx] : 0u;
-      const int j = (int)(e >> 28);
+    auto request = [&](int base, Cand& c_) {
+      const int idx = base + lane / G;
+      c_.valid = idx < list_cnt;
+      const uint32_t e = list[min(idx, list_cnt - 1)];
+      c_.j = (int)(e >> 28);
       const int64_t slot = (int64_t)t0 * TILE + (e & 0x0fffffffu);
-      float part = 0.f;
-      if (valid) part = refine_lane<FF, LW>(a.long_codes + slot * LW, a.q_stage + (int64_t)qidx[j] * a.D, t);
-      const float ip = group_sum<G>(part);
-      if (valid && t == 0) {
-        const float eB = qs[2 * j] + a.long_factors[2 * slot] + a.long_factors[2 * slot + 1] * (ip - qs[2 * j + 1]);
-        const uint64_t key = make_key(eB, (uint32_t)a.ids[slot]);
+      refine_load<FF, LW>(a.long_codes + slot * LW, lane % G, c_.w);
+      c_.lf = *reinterpret_cast<const float2*>(a.long_factors + 2 * slot);
+      c_.id = a.ids[slot];
+    };
+    Cand nxt;
+    if (list_cnt > 0) request(0, nxt);
+    for (int base = 0; base < list_cnt; base += NS) {
+      const Cand cur = nxt;
+      if (base + NS < list_cnt) request(base + NS, nxt);
+      const int t = lane % G, j = cur.j;
+      const float* qrow = a.q_stage + (int64_t)qidx[j] * a.D;
+      const float ip = group_sum<G>(refine_dot<FF, LW>(cur.w, qrow, t));
+      if (cur.valid && t == 0) {
+        const float eB = qs[2 * j] + cur.lf.x + cur.lf.y * (ip - qs[2 * j + 1]);
+        const uint64_t key = make_key(eB, (uint32_t)cur.id);
         if (key <= pool_kth[j]) {
           const int pos = atomicAdd(&pool_cnt[j], 1);
           pools[(size_t)j * a.pool + pos] = key;
@@ -990,7 +1013,7 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
           const int w = 2 * kc + (g >> 1);
           uint32_t word = 0u;
           if (w < W) word = a.short_codes[((int64_t)tile * W + w) * TILE + 16 * cb + lj];
-          const v4i xb = expand16((word >> (16 * (g & 1))) & 0xffffu);
+          const v4i xb = expand_half(word, g & 1);
           acc[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa[kc], xb, acc[cb], 0, 0, 0);
         }
       }

@@ -36,13 +36,23 @@ def oracle_stages(s: search.Searcher, Q: np.ndarray, k: int, nprobe: int) -> dic
     tau = np.array([s.seed_threshold(probes[i], G[i], E[i], Qr[i], delta[i], planes[i], int(S[i]), k)
                     for i in range(nq)])
     qhat = np.zeros((nq, (D + 63) // 64 * 64), np.int8)
+    pos = qhat8_positions(D)
     for i in range(nq):
-        qhat[i, :D] = search.quantize_query(Qr[i])[1]
+        qhat[i, pos] = search.quantize_query(Qr[i])[1]
     F = 0 if ix["total_bits"] == 1 else build.long_field_bits(ix["total_bits"])
     lut = np.stack([search.lut_tables(Qr[i]) for i in range(nq)])
     return dict(lut=lut, Qr=Qr, qhat=qhat, q_stage=stage_order(Qr, F), planes=planes, delta=delta, S=S, sum_q=Qr64.sum(1),
                 sq_norm=(Qr64 ** 2).sum(1),
                 probes=probes, G=G, E=E, pair_off=pair_off, pair_ids=order, tau=tau)
+
+
+def qhat8_positions(D: int) -> np.ndarray:
+    """Byte position of every dimension in the library's qhat8 array (include/rabitq.h): within each chunk of 64
+    dimensions, dimension 32 w + 8 b + 4 h + i sits at byte 16 (2 w + h) + 4 i + b."""
+    d = np.arange(D)
+    c, r = d >> 6, d & 63
+    w, x = r >> 5, r & 31
+    return 64 * c + 16 * (2 * w + ((x >> 2) & 1)) + 4 * (x & 3) + (x >> 3)
 
 
 def stage_order(Qr: np.ndarray, F: int) -> np.ndarray:
