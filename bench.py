@@ -250,12 +250,21 @@ def stream_scan(args, n, bits, steps, warmup):
     from paper_2602_23999_amd import rabitq
     dim, nlist, k = 128, n // args.stream_list, 10
     gen = torch.Generator(device="cuda").manual_seed(1234)
+    # mixture generated on the device: N/1024 centres N(0, 16 I); a point is its centre plus a scatter inside one of 64
+    # eight-dimensional subspaces (std 3) plus a little isotropic noise (std 0.3), so that, as in descriptor data, a
+    # query has neighbours that are clearly nearer than the bulk of its list and the 1-bit filter has something to do
     centres = torch.randn((nlist, dim), generator=gen, device="cuda") * 4.0
+    basis = torch.linalg.qr(torch.randn((64, dim, 8), generator=gen, device="cuda"))[0]   # [64][dim][8] orthonormal
     X = torch.empty((n, dim), dtype=torch.float32, device="cuda")
     own = torch.randint(0, nlist, (n,), generator=gen, device="cuda")
+
+    def draw(c_idx):
+        z = torch.randn((c_idx.shape[0], 8), generator=gen, device="cuda") * 3.0
+        sub = torch.einsum("nk,ndk->nd", z, basis[c_idx % 64])
+        return centres[c_idx] + sub + 0.3 * torch.randn((c_idx.shape[0], dim), generator=gen, device="cuda")
     for s0 in range(0, n, 1 << 20):
         e0 = min(n, s0 + (1 << 20))
-        X[s0:e0] = centres[own[s0:e0]] + torch.randn((e0 - s0, dim), generator=gen, device="cuda")
+        X[s0:e0] = draw(own[s0:e0])
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     gi = rabitq.Index.build(X, nlist, bits, rotation_matrix(dim), metric="l2", kmeans_iters=4, train_size=n // 10)
@@ -264,7 +273,7 @@ def stream_scan(args, n, bits, steps, warmup):
     log(f"[bench] stream-scan index N={n} nlist={nlist} B={bits}: {build_s:.2f}s")
     cluster_sizes = cluster_sizes_of(gi)
     # one query per generating centre: a fresh draw around it
-    Qd = centres + torch.randn((nlist, dim), generator=gen, device="cuda")
+    Qd = draw(torch.arange(nlist, device="cuda"))
     del X, own
     # keep one query per distinct nearest list, so that no two pairs share a list
     first = gi.coarse_probe(gi.rotate(Qd), gi.query_prep(gi.rotate(Qd))["sq_norm"], 1)["probe_ids"].view(-1).long()
@@ -386,7 +395,7 @@ def main():
                     help="run only the streaming-regime measurement and print its own JSON line")
     ap.add_argument("--no-stream", action="store_true", help="skip the streaming-regime leg (roofline.stream)")
     ap.add_argument("--stream-n", type=int, default=0,
-                    help="vectors of the streaming index (default 24 Mi inside the default run, 64 Mi with --stream-scan)")
+                    help="vectors of the streaming index (default 32 Mi inside the default run, 64 Mi with --stream-scan)")
     ap.add_argument("--stream-bits", type=int, default=1)
     ap.add_argument("--stream-list", type=int, default=1024, help="mean inverted-list length of the streaming index")
     args = ap.parse_args()
@@ -464,7 +473,7 @@ def main():
 
     # ---- the scan kernel in the streaming regime (HBM roofline) ----
     if not args.no_stream:
-        roofline["stream"] = stream_scan(args, args.stream_n or 24 * 1024 * 1024, args.stream_bits, 20, 3)
+        roofline["stream"] = stream_scan(args, args.stream_n or 32 * 1024 * 1024, args.stream_bits, 20, 3)
         log(f"[bench] streaming scan: {roofline['stream']['achieved']:.0f} GB/s = {roofline['stream']['frac']:.3f} of peak")
 
     res = {
