@@ -112,9 +112,9 @@ def stored_traffic(workload, nprobe):
     return val, f"from profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, same kernel sources)"
 
 
-def cpu_baseline(gi, Q, k, nprobe, budget_q=200):
+def cpu_baseline(gi, Q, k, nprobe, budget_q=2000):
     """The CPU oracle as it stands, on the index the GPU leg searched (exported from the device and re-indexed into
-    the oracle's arrays) and the first min(nq, 200) of the same queries, on all host cores the process may use: the
+    the oracle's arrays) and the first min(nq, 2000) of the same queries (10 to 30 s of CPU work), on all host cores the process may use: the
     queries are dealt to one worker process per core, each running the oracle's search unchanged.  The workers are
     started afresh (spawn), load the index from a file and never touch the GPU."""
     import multiprocessing as mp

@@ -303,7 +303,7 @@ int launch_gemm(const float* A, const float* B, float* C, int64_t M, int N, int 
   // its prologue, epilogue and the write of C, where more and smaller workgroups do better; and a small problem
   // needs small tiles to give every compute unit a workgroup at all.
   auto tiles = [&](int bm, int bn) { return ((M + bm - 1) / bm) * (int64_t)((N + bn - 1) / bn); };
-  if (K >= 256 && tiles(128, 128) >= 512) return launch_gemm_tile<2, 2>(A, B, C, M, N, K, mode, rowv, colv, st);
+  if (K >= 256 && tiles(128, 128) >= 384) return launch_gemm_tile<2, 2>(A, B, C, M, N, K, mode, rowv, colv, st);
   // (64 x 128 rather than 128 x 64: a wavefront then stores 256 contiguous bytes of a row of C)
   if (tiles(64, 128) >= 512) return launch_gemm_tile<1, 2>(A, B, C, M, N, K, mode, rowv, colv, st);
   return launch_gemm_tile<1, 1>(A, B, C, M, N, K, mode, rowv, colv, st);
