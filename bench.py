@@ -223,12 +223,12 @@ def scan_roofline(gi, Qd, w, pt, cluster_sizes, args):
                              else (None, "no counter summary for this variant"))
     roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TOPS, "unit": "TOP/s (integer lane-operations)",
                 "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic, "traffic_source": traffic_note,
-                "kernel": ("scan_kernel", "scan_mfma_kernel", "scan_kernel (lookup tables)")[impl],
+                "kernel": {0: "scan_kernel", 1: "scan_mfma_kernel", 2: "scan_kernel (lookup tables)", 4: "scan_wave_mfma_kernel"}[impl],
                 "algorithmic_ops_per_launch": alu_ops, "kernel_ms": scan_ms, "query_vector_evaluations": qv,
                 "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_gbs": achieved, "peak_gbs": HBM_PEAK_GBS,
                              "frac": achieved / HBM_PEAK_GBS,
                              "note": "above 1 when the launch is cache-served; the HBM-bound regime is roofline.stream"}}
-    if impl == 1:
+    if impl in (1, 4):
         # the matrix-core scan contracts sign bytes with the int8 query: 2 D integer operations per evaluation on
         # v_mfma_i32_16x16x64_i8, priced against the dense int8 peak
         mfma_ops = qv * 2 * w.dim

@@ -15,7 +15,8 @@ LIB = os.path.join(HERE, "librabitq_hip.so")
 UNITS = [("api.hip", [], "api.o"), ("gemm.hip", [], "gemm.o"), ("stages.hip", [], "stages.o"),
          ("scan_dispatch.hip", [], "scan_dispatch.o"), ("build.hip", [], "build.o"),
          ("scan.hip", ["-DRQ_PART=0"], "scan0.o"), ("scan.hip", ["-DRQ_PART=1"], "scan1.o"),
-         ("scan.hip", ["-DRQ_PART=2"], "scan2.o")]
+         ("scan.hip", ["-DRQ_PART=2"], "scan2.o"),
+         ("estimate_mfma.hip", [], "estimate_mfma.o")]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",

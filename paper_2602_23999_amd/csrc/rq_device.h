@@ -520,6 +520,7 @@ __host__ __device__ inline int next_pow2(int v) {
 // wave-uniform, so the compiler keeps the plane words in scalar registers.
 // ---------------------------------------------------------------------------------
 typedef const uint32_t __attribute__((address_space(4)))* const_u32_ptr;
+typedef const uint64_t __attribute__((address_space(4)))* const_u64_ptr;
 
 // popcount(x) + acc in one VALU instruction (the compiler otherwise splits the add off)
 __device__ inline uint32_t bcnt_acc(uint32_t x, uint32_t acc) {
@@ -572,7 +573,10 @@ __device__ inline float dot_word(uint32_t word, const float* qw) {
   float acc = 0.f;
 #pragma unroll
   for (int s = 0; s < SPB; ++s) {
-    const uint32_t m = (word >> (s * F)) & MASK;
+    uint32_t m = (word >> (s * F)) & MASK;
+    // (kept opaque: otherwise the compiler undoes the shared mask and extracts every field on its own, two
+    // instructions per dimension instead of one byte-to-float conversion)
+    if (F < 8) asm volatile("" : "+v"(m));
     const float4 q = *reinterpret_cast<const float4*>(qw + 4 * s);
     acc += (float)(m & 255u) * q.x + (float)((m >> 8) & 255u) * q.y + (float)((m >> 16) & 255u) * q.z +
            (float)(m >> 24) * q.w;
@@ -641,15 +645,73 @@ __device__ inline float refine_dot(const uint32_t (&w)[RefineShape<LW>::WPL], co
   return acc;
 }
 
+// sum over the G = 4 or 16 adjacent lanes of a candidate, in every one of them; data-parallel moves inside a row of
+// 16 lanes (rotate by 8 and by 4, then the quad permutations [2,3,0,1] and [1,0,3,2]), no LDS round trips
+template <int CTRL>
+__device__ inline float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
 template <int G>
 __device__ inline float group_sum(float v) {
   if (G >= 16) {
-    v += __shfl_xor(v, 8, 64);
-    v += __shfl_xor(v, 4, 64);
+    v += dpp_move<0x128>(v);
+    v += dpp_move<0x124>(v);
   }
-  v += __shfl_xor(v, 2, 64);
-  v += __shfl_xor(v, 1, 64);
+  v += dpp_move<0x4E>(v);
+  v += dpp_move<0xB1>(v);
   return v;
+}
+
+// ---------------------------------------------------------------------------------
+// Shared by the matrix-core variants of the scan.
+// ---------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+// 16 sign bits of a code word -> 16 bytes of 0/1 for the matrix instruction's B operand, at two instructions per
+// four bytes: (word >> s) & 0x01010101 leaves bits s, s+8, s+16, s+24 of the word in the four bytes.  The lane
+// group with half h (0 / 1) of a word takes the shifts s = 4h .. 4h+3, so byte b of its i-th operand word is dimension
+// 4h + i + 8b of the code word, and the query's qhat bytes are stored in that same order (qhat_mfma_pos).
+__device__ inline v4i expand_half(uint32_t word, int h) {
+  const uint32_t v = word >> (4 * h);
+  v4i x;
+  x.x = (int)(v & 0x01010101u);
+  x.y = (int)((v >> 1) & 0x01010101u);
+  x.z = (int)((v >> 2) & 0x01010101u);
+  x.w = (int)((v >> 3) & 0x01010101u);
+  return x;
+}
+
+__device__ inline void wave_sync() {  // orders LDS traffic among the lanes of one wavefront
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// bitonic sort of n = 2^m keys in LDS by ONE wavefront of a larger workgroup (no workgroup barrier)
+__device__ inline void wave_bitonic_sort(uint64_t* keys, int n, int lane) {
+  for (int k = 2; k <= n; k <<= 1) {
+    for (int j = k >> 1; j > 0; j >>= 1) {
+      wave_sync();
+      for (int t = lane; t < (n >> 1); t += 64) {
+        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+        const int l = i | j;
+        const uint64_t x = keys[i], y = keys[l];
+        const bool up = (i & k) == 0;
+        if ((x > y) == up) {
+          keys[i] = y;
+          keys[l] = x;
+        }
+      }
+    }
+  }
+  wave_sync();
+}
+
+__device__ inline int wave_pool_compact(uint64_t* pool, int pool_n, int cnt, int k, int lane) {
+  wave_sync();
+  for (int i = cnt + lane; i < pool_n; i += 64) pool[i] = KEY_NONE;
+  wave_bitonic_sort(pool, pool_n, lane);
+  return min(cnt, k);
 }
 
 }  // namespace rq

@@ -52,6 +52,7 @@ struct rabitq_index {
   float* centroids_t = nullptr;     // [D][nlist]  (transposed c')
   float* centroid_sq = nullptr;     // [nlist]
   int32_t* tile_off = nullptr;      // [nlist+1] tile offsets | [nlist+1] scan work-item offsets | [TICKET_WORDS] zeroed ticket
+                                    // | [nlist+1] work items of 16 pairs | [nlist+1] first survivor block (split search)
   int32_t* cluster_size = nullptr;  // [nlist]
   uint32_t* short_codes = nullptr;
   float* short_factors = nullptr;
@@ -65,7 +66,13 @@ struct rabitq_index {
   mutable int64_t seg_total = 0;
   // options
   int prune = 1;
-  int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl)
+  int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl),
+                      // 4 estimates on the matrix cores + refinement by the popcount kernel (split search)
+  // survivor bits of the split search: blocks of 16 words; grown on demand by ensure_split_mask, kept by the handle
+  int split_min_pairs = 16;  // pairs per list, on average, from which scan_impl 4 splits the search
+  uint64_t* surv_mask = nullptr;
+  int64_t surv_mask_blocks = 0;
+  std::vector<int64_t> tiles_prefix;  // [i] = tiles of the i largest lists (host; filled on first use)
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   int64_t max_batch = 0;  // queries per pass of rabitq_search; 0 = from the workspace budget
   int small_batch = 1;    // batches of at most SMALL_BATCH_MAX queries take the fused low-launch-count kernels
@@ -89,7 +96,11 @@ namespace rq {
 // measured 3.2x faster than the popcount kernel (0.86 against 2.79 ms), and the popcount kernel below (D = 128: 0.28
 // against 0.32 ms; at D = 768 the matrix-core kernel wins where the filter works, 4.2 against 5.8 ms, and loses where
 // nearly every vector has to be refined, 32 against 22 ms).
-inline int effective_impl(const rabitq_index* ix) { return ix->scan_impl == 3 ? (ix->W >= 30 ? 1 : 0) : ix->scan_impl; }
+// (4 is the popcount kernel everywhere except in launch_scan, which splits the search when it can: see split_search)
+inline int effective_impl(const rabitq_index* ix) {
+  const int impl = ix->scan_impl == 3 ? (ix->W >= 30 ? 1 : 0) : ix->scan_impl;
+  return impl == 4 ? 0 : impl;
+}
 
 void set_error(const std::string& s);
 int hip_fail(hipError_t e, const char* what);
@@ -148,7 +159,19 @@ ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k);
 // `scratch` holds at least 2 * nlist words.  Same pair_off / pair_ids as launch_build_lists.
 constexpr int SMALL_BATCH_MAX = 64;
 constexpr int TICKET_WORDS = 4;  // words behind the two offset arrays of rabitq_index::tile_off (zero between launches)
-inline int64_t tile_off_words(int nlist) { return 2 * (int64_t)(nlist + 1) + TICKET_WORDS; }
+inline int64_t tile_off_words(int nlist) { return 4 * (int64_t)(nlist + 1) + TICKET_WORDS; }
+// Split search (scan_impl 4): the first stage runs on the matrix cores for groups of 16 pairs and hands one survivor
+// bit per (pair, vector) to the popcount kernel.  Worth it, and built, for a long code (B > 1), D <= 128 and at
+// least split_min_pairs pairs per list on average.  split_mask_blocks bounds the blocks of survivor bits a search of
+// (nq, nprobe) can need: sum_c ceil(cnt_c / 16) tiles_c <= (nq * tiles of the nprobe largest lists) / 16 + all tiles,
+// because every query probes nprobe distinct lists.
+inline bool split_built(const rabitq_index* ix) { return ix->W <= 4 && ix->total_bits > 1; }
+inline bool split_wanted(const rabitq_index* ix, int64_t nq, int nprobe) {
+  return ix->scan_impl == 4 && split_built(ix) && nq * nprobe >= (int64_t)ix->split_min_pairs * ix->nlist;
+}
+int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe);
+// makes the handle's survivor-bit buffer large enough for (nq, nprobe); may allocate (then it synchronises the device)
+int ensure_split_mask(rabitq_index* ix, int64_t nq, int nprobe);
 // The same for nprobe <= 64, k <= 64 and a bitwise scan, preceded in the same kernel by the selection of the probes
 // from the coarse scores and the seeding of the thresholds (one workgroup per query; the last one to finish builds the
 // lists): everything between the coarse scores and the scan in one launch.

@@ -41,6 +41,11 @@ struct ScanArgs {
   const int32_t* pair_off;
   const int32_t* pair_ids;
   const int32_t* item_off;
+  // split search (estimates by estimate_mfma_kernel, refinement by the popcount kernel): work items of 16 pairs,
+  // first block of survivor bits of every cluster, the bits themselves (nullptr: not split)
+  const int32_t* item_off16;
+  const uint32_t* mask_off;
+  uint64_t* surv_mask;
   int nprobe, k, pool, cand_stride;
   int streaming;     // few pairs per list: every list is read from memory about once (prefetching scan variant)
   int tseg, segmax;  // a cluster of more than tseg tiles is scanned in up to segmax segments (separate work items)
@@ -57,6 +62,10 @@ __host__ __device__ inline int seg_count(int tiles, int tseg, int segmax) {
   const int n = (tiles + tseg - 1) / tseg;
   return n < 1 ? 1 : (n > segmax ? segmax : n);
 }
+
+// impl 4: the estimates of QM pairs per wavefront on the matrix cores, leaving survivor bits for the popcount kernel;
+// false for a width it is not built for
+bool estimate_mfma(const ScanArgs& a, int W, unsigned grid, bool dbg, hipStream_t st);
 
 // impl 0: popcount kernel (QW pairs per wavefront); impl 1: matrix-core kernel (QM pairs; seeds by popcount);
 // impl 2: lookup-table kernel (QW pairs)

@@ -389,6 +389,10 @@ __global__ __launch_bounds__(256) void small_select_seed_kernel(ScanArgs a, Smal
 // Output: the surviving keys of each pair, unsorted, at most `pool` = next_pow2(k + 64) of them.
 // ---------------------------------------------------------------------------------
 constexpr int LIST_CAP = 512;
+// MASKED: MASK_BATCH words of survivor bits are turned into list entries at a time, at most 16 each
+constexpr int MASK_BATCH = 32;
+constexpr int LIST_CAP_MASKED = 256 + 16 * MASK_BATCH;
+constexpr int REFINE_AHEAD_MASKED = 2;  // refinement rounds whose loads are in flight (1 in the fused kernel)
 
 #ifdef RQ_STATS  // development counters: survivors, refine rounds, compactions, flushes
 __device__ unsigned long long g_scan_stats[8];
@@ -406,7 +410,9 @@ __device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
 
 // PFD > 0 (streaming regime, few pairs per list): the codes and factors of the next tiles are requested ahead, because
 // there the kernel waits for memory, not for the vector ALUs.
-template <int W, int F, bool DBG, int M, int PFD = 0>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
+// MASKED: the first stage has been done by estimate_mfma_kernel; the survivors of a (pair, tile) are read as one bit
+// per vector and only refinement, pools and output happen here.
+template <int W, int F, bool DBG, int M, int PFD = 0, bool MASKED = false>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
 __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF;
   constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
@@ -415,9 +421,14 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   uint64_t* pool_kth = pools + (size_t)QW * a.pool;                    // [QW] k-th best key so far
   float* qs = reinterpret_cast<float*>(pool_kth + QW);                 // [QW][2]: G, cB*sum(q')
   int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QW);                 // [QW]
-  uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QW);         // [LIST_CAP] (F > 0)
-  float* qf = reinterpret_cast<float*>(list + (F > 0 ? LIST_CAP : 0)); // [QW][D] (F > 0)
-  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + (F > 0 ? QW * a.D : 0));  // [QW][8W][16] (M = 1)
+  constexpr int LCAP = MASKED ? LIST_CAP_MASKED : LIST_CAP, AHEAD = MASKED ? REFINE_AHEAD_MASKED : 1;
+  uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QW);         // [LCAP] (F > 0)
+  // The queries in LDS, padded: a lane of the refinement reads a chunk of QCH = D / G consecutive floats, 16 bytes at
+  // a time, and the chunks of one row (and the rows) would all start in the same banks; QPAD floats after every
+  // chunk spread them over the banks.  Element e of row j sits at j * QROW + e + QPAD * (e / QCH).
+  constexpr int QCH = RefineShape<LW>::WPL * (32 / FF), QPAD = 4, QROW = 32 * W + QPAD * G;
+  float* qf = reinterpret_cast<float*>(list + (F > 0 ? LCAP : 0));     // [QW][QROW] (F > 0)
+  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + (F > 0 ? QW * QROW : 0));  // [QW][8W][16] (M = 1)
   const int lane = threadIdx.x;
 
   // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
@@ -438,6 +449,10 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int ts = t0 + sidx * seglen, te = min(tc1, ts + seglen);
   const int pbeg = a.pair_off[c] + grp * QW;
   const int np = __builtin_amdgcn_readfirstlane(min(QW, a.pair_off[c + 1] - pbeg));  // the same in all lanes
+  // MASKED: blocks of survivor bits of this item's group of 16 pairs (its 4 pairs are lane group `mg` of every word)
+  const int mg = grp & 3;
+  const uint64_t* mblk = nullptr;
+  if (MASKED) mblk = a.surv_mask + ((int64_t)a.mask_off[c] + (int64_t)(grp >> 2) * (tc1 - t0) + (ts - t0)) * 16;
 
   constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead
   uint32_t pw[PD > 0 ? PD : 1][W];
@@ -520,7 +535,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       for (int jj = 0; jj < JB; ++jj)
 #pragma unroll
         for (int u = 0; u < PER; ++u)
-          if (u * 64 + lane < DD) qf[(j0 + jj) * DD + u * 64 + lane] = sv[jj][u];
+          if (u * 64 + lane < DD) qf[(j0 + jj) * QROW + (u * 64 + lane) + QPAD * ((u * 64 + lane) / QCH)] = sv[jj][u];
     }
   }
   __syncthreads();
@@ -562,27 +577,37 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     __syncthreads();
     RQ_STAT(0, list_cnt);
     RQ_STAT(3, 1);
-    Cand nxt;
-    if (list_cnt > 0) request(0, nxt);
-    for (int base = 0; base < list_cnt; base += NS) {
-      RQ_STAT(1, 1);
-      const Cand cur = nxt;
-      if (base + NS < list_cnt) request(base + NS, nxt);
-      const int t = lane % G, j = cur.j;
-      const float ip = group_sum<G>(refine_dot<FF, LW>(cur.w, qf + j * a.D, t));
-      if (cur.valid && t == 0) {
-        const float eB = qs[2 * j] + cur.lf.x + cur.lf.y * (ip - qs[2 * j + 1]);
-        const uint64_t key = make_key(eB, (uint32_t)cur.id);
-        if (key <= pool_kth[j]) {
-          const int pos = atomicAdd(&pool_cnt[j], 1);
-          pools[(size_t)j * a.pool + pos] = key;
+    // (AHEAD rounds are in flight: where this kernel only refines, nothing else covers the latency of the scattered
+    // long-code reads)
+    Cand ring[AHEAD];
+#pragma unroll
+    for (int d = 0; d < AHEAD; ++d)
+      if (d * NS < list_cnt) request(d * NS, ring[d]);
+    for (int base = 0; base < list_cnt; base += AHEAD * NS) {
+#pragma unroll
+      for (int d = 0; d < AHEAD; ++d) {
+        const int rb = base + d * NS;
+        if (rb >= list_cnt) break;
+        RQ_STAT(1, 1);
+        const Cand cur = ring[d];
+        if (rb + AHEAD * NS < list_cnt) request(rb + AHEAD * NS, ring[d]);
+        const int t = lane % G, j = cur.j;
+        const float ip = group_sum<G>(refine_dot<FF, LW>(cur.w, qf + j * QROW + t * QPAD, t));
+        if (cur.valid && t == 0) {
+          const float eB = qs[2 * j] + cur.lf.x + cur.lf.y * (ip - qs[2 * j + 1]);
+          const uint64_t key = make_key(eB, (uint32_t)cur.id);
+          if (key <= pool_kth[j]) {
+            const int pos = atomicAdd(&pool_cnt[j], 1);
+            pools[(size_t)j * a.pool + pos] = key;
+          }
         }
       }
+      // a pool that could not take the keys of another AHEAD rounds is cut to its k best (pool >= k + 64 >= k + AHEAD * NS)
       __syncthreads();
 #pragma unroll
       for (int jj = 0; jj < QW; ++jj) {
         const int cj = pool_cnt[jj];
-        if (cj + NS > a.pool) {
+        if (cj + AHEAD * NS > a.pool) {
           RQ_STAT(2, 1);
           uint64_t* pool = pools + (size_t)jj * a.pool;
           const int nc = pool_compact(pool, a.pool, cj, a.k);
@@ -597,7 +622,37 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     list_cnt = 0;
   };
 
-  for (int tile = ts; tile < te; ++tile) {
+  if (MASKED) {
+    // The first stage is done: MASK_BATCH words of survivor bits (2 tiles) are turned into list entries at a time.  Lane
+    // l < MASK_BATCH takes word wb + l, which is (tile, pair j, column block cb) = ((wb + l) / 16, ((wb + l) / 4) % 4, (wb + l) % 4);
+    // its bits 16 mg .. 16 mg + 15 are this item's pair j against vectors 16 cb .. 16 cb + 15 of the tile.
+    const int nwords = (te - ts) * 16;
+    uint64_t wnext = (lane < MASK_BATCH && lane < nwords) ? mblk[lane] : 0ull;
+    for (int wb = 0; wb < nwords; wb += MASK_BATCH) {
+      const uint64_t wcur = wnext;
+      wnext = (lane < MASK_BATCH && wb + MASK_BATCH + lane < nwords) ? mblk[wb + MASK_BATCH + lane] : 0ull;
+      const int wi = wb + lane;
+      uint32_t field = (uint32_t)(wcur >> (16 * mg)) & 0xffffu;
+      const int mine_n = __popc(field);
+      int incl = mine_n;  // inclusive scan over the lanes
+#pragma unroll
+      for (int d = 1; d < 64; d <<= 1) {
+        const int o = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += o;
+      }
+      const int total = __shfl(incl, 63, 64);
+      if (total == 0) continue;
+      if (list_cnt + total > LCAP) flush();
+      int pos = list_cnt + incl - mine_n;
+      const uint32_t entry0 = ((uint32_t)((wi >> 2) & 3) << 30) | (uint32_t)((ts - t0 + (wi >> 4)) * TILE + 16 * (wi & 3));
+      while (field != 0u) {
+        list[pos++] = entry0 | (uint32_t)(__ffs(field) - 1);
+        field &= field - 1u;
+      }
+      list_cnt += total;
+    }
+  }
+  for (int tile = ts; !MASKED && tile < te; ++tile) {
     uint32_t cw[W];
     float fq[3];
     if (PD > 0) {
@@ -672,7 +727,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
         if (surv) pool[cnt[j] + before] = make_key(e1, (uint32_t)((tile - t0) * TILE + lane));
         cnt[j] += ns;
       } else {
-        if (list_cnt + ns > LIST_CAP) flush();
+        if (list_cnt + ns > LCAP) flush();
         if (surv) list[list_cnt + before] = ((uint32_t)j << 30) | (uint32_t)((tile - t0) * TILE + lane);
         list_cnt += ns;
       }
@@ -740,7 +795,6 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 // inner product (filter, survivor list, refinement, pools, output) is shared in form with
 // the popcount kernel; integer results are identical.
 // ---------------------------------------------------------------------------------
-typedef int v4i __attribute__((ext_vector_type(4)));
 // wavefronts per work item (they split its tiles and own QM / n of its queries each): four for short codes, two for
 // wide ones, where a tile keeps a wavefront busy for longer and the barrier after every round of tiles weighs more
 // (D = 960: 0.97 ms with four, 0.86 ms with two, 0.86 ms with one; D = 128: 0.32 / 0.38 / 0.45 ms)
@@ -748,53 +802,6 @@ __host__ __device__ constexpr int mfma_waves(int W) { return W >= 16 ? 2 : 4; }
 constexpr int MLIST_FLUSH = 128;              // an owner list longer than this is refined before the next tiles
 // + what one round of tiles can add: every wavefront a tile, 64 vectors x QM / n queries per owner
 __host__ __device__ constexpr int mlist_cap(int n) { return MLIST_FLUSH + n * TILE * (QM / n); }
-
-// 16 sign bits of a code word -> 16 bytes of 0/1 for the matrix instruction's B operand, at two instructions per
-// four bytes: (word >> s) & 0x01010101 leaves bits s, s+8, s+16, s+24 of the word in the four bytes.  The lane
-// group with half h (0 / 1) of a word takes the shifts s = 4h .. 4h+3, so byte b of its i-th operand word is dimension
-// 4h + i + 8b of the code word, and the query's qhat bytes are stored in that same order (qhat_mfma_pos).
-__device__ inline v4i expand_half(uint32_t word, int h) {
-  const uint32_t v = word >> (4 * h);
-  v4i x;
-  x.x = (int)(v & 0x01010101u);
-  x.y = (int)((v >> 1) & 0x01010101u);
-  x.z = (int)((v >> 2) & 0x01010101u);
-  x.w = (int)((v >> 3) & 0x01010101u);
-  return x;
-}
-
-__device__ inline void wave_sync() {  // orders LDS traffic among the lanes of one wavefront
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// bitonic sort of n = 2^m keys in LDS by ONE wavefront of a larger workgroup (no workgroup barrier)
-__device__ inline void wave_bitonic_sort(uint64_t* keys, int n, int lane) {
-  for (int k = 2; k <= n; k <<= 1) {
-    for (int j = k >> 1; j > 0; j >>= 1) {
-      wave_sync();
-      for (int t = lane; t < (n >> 1); t += 64) {
-        const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-        const int l = i | j;
-        const uint64_t x = keys[i], y = keys[l];
-        const bool up = (i & k) == 0;
-        if ((x > y) == up) {
-          keys[i] = y;
-          keys[l] = x;
-        }
-      }
-    }
-  }
-  wave_sync();
-}
-
-__device__ inline int wave_pool_compact(uint64_t* pool, int pool_n, int cnt, int k, int lane) {
-  wave_sync();
-  for (int i = cnt + lane; i < pool_n; i += 64) pool[i] = KEY_NONE;
-  wave_bitonic_sort(pool, pool_n, lane);
-  return min(cnt, k);
-}
 
 // A decision every wavefront of the workgroup must take alike, although each of them computes it from LDS counters
 // that faster wavefronts may already be advancing: the first wavefront to arrive fixes the value in `slot` (which
@@ -1122,10 +1129,14 @@ static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipS
 
 template <int W, int F, int M>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
+  const bool masked = M == 0 && F > 0 && W <= 4 && a.surv_mask != nullptr;  // second half of the split search
   const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
-                      (F > 0 ? LIST_CAP * sizeof(uint32_t) + (size_t)QW * a.D * sizeof(float) : 0) +
+                      (F > 0 ? (masked ? LIST_CAP_MASKED : LIST_CAP) * sizeof(uint32_t) +
+                                   (size_t)QW * (a.D + 4 * RefineShape<W * (F > 0 ? F : 8)>::G) * sizeof(float) : 0) +
                       (M == 1 ? (size_t)QW * W * 256 : 0);
-  if (dbg)
+  if (masked)  // (estimate_mfma_kernel ran)
+    hipLaunchKernelGGL((scan_kernel<W, F, false, M, 0, (M == 0 && F > 0 && W <= 4)>), dim3(grid), dim3(64), smem, st, a);
+  else if (dbg)
     hipLaunchKernelGGL((scan_kernel<W, F, true, M>), dim3(grid), dim3(64), smem, st, a);
   else if (M == 0 && a.streaming)
     hipLaunchKernelGGL((scan_kernel<W, F, false, M, (M == 0 ? 1 : 0)>), dim3(grid), dim3(64), smem, st, a);

@@ -47,6 +47,69 @@ __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __rest
 }
 
 
+// Split search: item16[c] = first work item of cluster c when an item is 16 pairs times one segment, and mask_off[c] =
+// first block of survivor bits of cluster c (a block per group of 16 pairs and tile).  (One workgroup.)
+__global__ __launch_bounds__(256) void split_offsets_kernel(const int32_t* __restrict__ pair_off,
+                                                           const int32_t* __restrict__ tile_off, int n, int tseg, int segmax,
+                                                           int32_t* __restrict__ item16, uint32_t* __restrict__ mask_off) {
+  __shared__ uint32_t part_i[256], part_b[256];
+  const int tid = threadIdx.x;
+  const int per = (n + 255) / 256;
+  const int s = tid * per, e = min(n, s + per);
+  auto groups = [&](int i) -> uint32_t { return (uint32_t)((pair_off[i + 1] - pair_off[i] + QM - 1) / QM); };
+  auto tiles = [&](int i) -> uint32_t { return (uint32_t)(tile_off[i + 1] - tile_off[i]); };
+  uint32_t si = 0, sb = 0;
+  for (int i = s; i < e; ++i) {
+    si += groups(i) * (uint32_t)seg_count((int)tiles(i), tseg, segmax);
+    sb += groups(i) * tiles(i);
+  }
+  part_i[tid] = si;
+  part_b[tid] = sb;
+  __syncthreads();
+  for (int d = 1; d < 256; d <<= 1) {
+    const uint32_t oi = (tid >= d) ? part_i[tid - d] : 0u, ob = (tid >= d) ? part_b[tid - d] : 0u;
+    __syncthreads();
+    part_i[tid] += oi;
+    part_b[tid] += ob;
+    __syncthreads();
+  }
+  uint32_t ri = part_i[tid] - si, rb = part_b[tid] - sb;
+  for (int i = s; i < e; ++i) {
+    item16[i] = (int32_t)ri;
+    mask_off[i] = rb;
+    ri += groups(i) * (uint32_t)seg_count((int)tiles(i), tseg, segmax);
+    rb += groups(i) * tiles(i);
+  }
+  if (tid == 255) {
+    item16[n] = (int32_t)part_i[255];
+    mask_off[n] = part_b[255];
+  }
+}
+
+int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe) {
+  if (ix->tiles_prefix.empty()) {
+    std::vector<int> t(ix->host_tiles.begin(), ix->host_tiles.end());
+    std::sort(t.begin(), t.end(), std::greater<int>());
+    ix->tiles_prefix.assign(t.size() + 1, 0);
+    for (size_t i = 0; i < t.size(); ++i) ix->tiles_prefix[i + 1] = ix->tiles_prefix[i] + t[i];
+  }
+  const size_t top = std::min<size_t>((size_t)nprobe, ix->tiles_prefix.size() - 1);
+  return (nq * ix->tiles_prefix[top] + QM - 1) / QM + ix->n_tiles;
+}
+
+int ensure_split_mask(rabitq_index* ix, int64_t nq, int nprobe) {
+  const int64_t need = split_mask_blocks(ix, nq, nprobe);
+  if (need <= ix->surv_mask_blocks) return RABITQ_OK;
+  if (need >= ((int64_t)1 << 32)) return RABITQ_OK;  // too many blocks for 32-bit offsets: the search is not split
+  RQ_HIP(hipDeviceSynchronize());
+  if (ix->surv_mask) (void)hipFree(ix->surv_mask);
+  ix->surv_mask = nullptr;
+  ix->surv_mask_blocks = 0;
+  RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->surv_mask), (size_t)need * 16 * sizeof(uint64_t)));
+  ix->surv_mask_blocks = need;
+  return RABITQ_OK;
+}
+
 __global__ __launch_bounds__(1024) void small_batch_lists_kernel(SmallListArgs b) {
   __shared__ uint32_t s_pairs[1024], s_items[1024];
   small_lists_body<1024>(b, s_pairs, s_items);
@@ -203,6 +266,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // tiles when there is no long code)
   a.pool = next_pow2_host(k + TILE);
   if (impl == 1 && ix->total_bits == 1) a.pool = next_pow2_host(k + 4 * TILE);
+
   a.cand_keys = cand_keys; a.cand_cnt = cand_cnt; a.dbg_ip = dbg_ip; a.dbg_off = dbg_off;
   // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
@@ -218,6 +282,21 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     if (!ss.counters_clear) {
       if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
     }
+  }
+  // Split search: the estimates of groups of 16 pairs on the matrix cores, then this kernel's refinement only.
+  // Chosen when asked for (scan_impl 4), built for the index, worth it for the batch, and the handle's buffer of
+  // survivor bits is large enough (ensure_split_mask, called by the entry points that may allocate).
+  const bool split = split_wanted(ix, nq, nprobe) && ix->surv_mask != nullptr && split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks;
+  if (split) {
+    int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
+    uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
+    hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, a.tseg, a.segmax,
+                       item16, mask_off);
+    a.item_off16 = item16;
+    a.mask_off = mask_off;
+    a.surv_mask = ix->surv_mask;
+    // (the refinement-only kernel lives on wavefronts in flight: smaller pools, checked every second round of 16 keys)
+    a.pool = std::max(64, next_pow2_host(k + 32));
   }
   if (ss.setup_e) RQ_HIP(hipEventRecord(ss.setup_e, sst));
   if (sst != st) {
@@ -251,6 +330,12 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   const unsigned grid = (unsigned)max_items;
   const bool dbg = dbg_ip != nullptr;
   const int W = ix->W, F = field_bits(ix->total_bits);
+  if (split) {
+    int64_t items16 = ix->seg_total + (nq * top + QM - 1) / QM;  // the same bound with 16 pairs per item
+    items16 = ((items16 + 7) / 8) * 8;
+    if (!estimate_mfma(a, W, (unsigned)items16, dbg, st)) return bad_width();
+    RQ_HIP(hipGetLastError());
+  }
   if (!(scan_part0(a, W, F, impl, grid, dbg, st) || scan_part1(a, W, F, impl, grid, dbg, st) ||
         scan_part2(a, W, F, impl, grid, dbg, st)))
     return bad_width();

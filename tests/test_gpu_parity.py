@@ -91,11 +91,12 @@ def test_probe_lists_bit_exact(name):
     assert np.array_equal(ids.cpu().numpy(), st["pair_ids"])
 
 
-@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("impl", [0, 1, 4])
 @pytest.mark.parametrize("name", ALL)
 def test_scan_integer_inner_products_bit_exact(name, impl):
     c = case(name)
     c["gi"].set_option("scan_impl", impl)
+    c["gi"].set_option("split_min_pairs", 1)   # scan_impl 4: also for the few pairs per list of these cases
     st, d, ix, s = c["st"], c["dev"], c["ix"], c["s"]
     nprobe, k = c["nprobe"], c["k"]
     tiles = (np.diff(ix["offsets"]) + 63) // 64
@@ -137,12 +138,13 @@ def test_seed_threshold(name):
     assert len(bad) <= 0.02 * len(tau)
 
 
-@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("impl", [0, 1, 4])
 @pytest.mark.parametrize("name", ALL)
 @pytest.mark.parametrize("prune", [True, False])
 def test_scan_and_merge_with_injected_threshold(name, prune, impl):
     c = case(name)
     c["gi"].set_option("scan_impl", impl)
+    c["gi"].set_option("split_min_pairs", 1)   # scan_impl 4: also for the few pairs per list of these cases
     st, d, s = c["st"], c["dev"], c["s"]
     nq, k, nprobe = len(c["Q"]), c["k"], c["nprobe"]
     # The injected threshold is the oracle's, moved up by a hair (as an fp32 value that both
@@ -171,13 +173,14 @@ def oracle_own(c, prune):
     return c[key]
 
 
-@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("impl", [0, 1, 4])
 @pytest.mark.parametrize("prune", [True, False])
 @pytest.mark.parametrize("name", ALL)
 def test_search_end_to_end(name, prune, impl):
     c = case(name)
     s, k, nprobe = c["s"], c["k"], c["nprobe"]
     c["gi"].set_option("scan_impl", impl)
+    c["gi"].set_option("split_min_pairs", 1)   # scan_impl 4: also for the few pairs per list of these cases
     try:
         # every difference from the oracle is accounted for stage by stage (a digit on a rounding boundary, a
         # probe or seed near-tie, a vector on the threshold, keys that tie); anything else fails inside

@@ -25,7 +25,7 @@ SHAPES = [
 ]
 
 
-@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("impl", [0, 1, 4])
 @pytest.mark.parametrize("D,B,n,nlist,k,nprobe,nq", SHAPES)
 def test_shape_end_to_end(D, B, n, nlist, k, nprobe, nq, impl):
     w = replace(synth.WORKLOADS["tiny"], dim=D, n=n, nq=nq, n_centres=max(4, nlist // 2))
@@ -34,6 +34,7 @@ def test_shape_end_to_end(D, B, n, nlist, k, nprobe, nq, impl):
     s = search.Searcher(ix)
     gi = upload(ix)
     gi.set_option("scan_impl", impl)
+    gi.set_option("split_min_pairs", 1)
     ids, dist, why = search_explained(gi, s, Q, k, nprobe)   # every difference from the oracle accounted for
     own = s.search(Q, k, nprobe, detail=True)
     o_ids = own[0]

@@ -9,7 +9,7 @@ from test_gpu_parity import case
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("impl", [0, 1, 4])
 @pytest.mark.parametrize("name,nq", [("tiny_b1", 1), ("tiny_b1", 64), ("l2_128_b4", 7), ("l2_128_b4", 64),
                                      ("l2_96_b3_k100", 33), ("l2_960_b5", 24), ("ragged_b2", 40), ("many_probes_b2", 48),
                                      ("ip_768_b8", 24), ("centred_b4", 2)])
@@ -18,6 +18,7 @@ def test_small_batch_kernels_equal_the_general_ones(name, nq, impl):
     gi, k, nprobe = c["gi"], c["k"], c["nprobe"]
     q = torch.from_numpy(c["Q"][:nq]).cuda().contiguous()
     gi.set_option("scan_impl", impl)
+    gi.set_option("split_min_pairs", 1)
     try:
         for prune in (1, 0):
             gi.set_option("prune", prune)
