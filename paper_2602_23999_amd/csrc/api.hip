@@ -63,7 +63,7 @@ static void free_workspace(Workspace& w) {
 
 static void free_index(rabitq_index* ix) {
   if (!ix) return;
-  dev_free(ix->rotation); dev_free(ix->mean_rot); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off); dev_free(ix->surv_mask);
+  dev_free(ix->rotation); dev_free(ix->mean_rot); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off); dev_free(ix->surv_mask); dev_free(ix->item_desc);
   dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
   dev_free(ix->long_factors); dev_free(ix->ids);
   free_workspace(ix->ws);
@@ -574,7 +574,7 @@ int rabitq_scan(rabitq_index_t ix, const rabitq_query_repr* repr, const float* p
   }
   if (nq * nprobe > 0x7fffffff) { set_error("scan: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
   if (split_wanted(ix, nq, nprobe))
-    if ((rc = ensure_split_mask(ix, nq, nprobe))) return rc;
+    if ((rc = ensure_split_buffers(ix, nq, nprobe, k))) return rc;
   ScanStreams ss;
   ss.main = ss.setup = (hipStream_t)stream;
   return launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
@@ -717,7 +717,7 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   const int64_t step = std::min(nq, search_batch_limit(ix, k, nprobe));
   if ((rc = ensure_workspace(ix, step, nprobe, k))) return rc;
   if (split_wanted(ix, step, nprobe))
-    if ((rc = ensure_split_mask(ix, step, nprobe))) return rc;
+    if ((rc = ensure_split_buffers(ix, step, nprobe, k))) return rc;
   for (int64_t s0 = 0; s0 < nq; s0 += step) {
     const int64_t m = std::min(step, nq - s0);
     if ((rc = search_batch(ix, ix->ws, queries + s0 * ix->dim, m, k, nprobe, out_ids + s0 * k, out_dists + s0 * k,

@@ -41,6 +41,8 @@ struct Workspace {
 
 }  // namespace rq
 
+namespace rq { struct ItemDesc; }
+
 struct rabitq_index {
   int32_t dim = 0, W = 0, nlist = 0, total_bits = 0, metric = 0, F = 0, LW = 0;  // LW = long words per slot
   int64_t n = 0, n_tiles = 0, n_slots = 0;
@@ -68,10 +70,12 @@ struct rabitq_index {
   int prune = 1;
   int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl),
                       // 4 estimates on the matrix cores + refinement by the popcount kernel (split search)
-  // survivor bits of the split search: blocks of 16 words; grown on demand by ensure_split_mask, kept by the handle
-  int split_min_pairs = 16;  // pairs per list, on average, from which scan_impl 4 splits the search
+  // survivor bits of the split search: blocks of 16 words; grown on demand by ensure_split_buffers, kept by the handle
+  int split_min_pairs = 32;  // pairs per list, on average, from which scan_impl 3 / 4 split the search
   uint64_t* surv_mask = nullptr;
   int64_t surv_mask_blocks = 0;
+  rq::ItemDesc* item_desc = nullptr;  // descriptors of the refinement kernel's work items (split search), grown with the bits
+  int64_t item_desc_cap = 0;
   std::vector<int64_t> tiles_prefix;  // [i] = tiles of the i largest lists (host; filled on first use)
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   int64_t max_batch = 0;  // queries per pass of rabitq_search; 0 = from the workspace budget
@@ -167,11 +171,12 @@ inline int64_t tile_off_words(int nlist) { return 4 * (int64_t)(nlist + 1) + TIC
 // because every query probes nprobe distinct lists.
 inline bool split_built(const rabitq_index* ix) { return ix->W <= 4 && ix->total_bits > 1; }
 inline bool split_wanted(const rabitq_index* ix, int64_t nq, int nprobe) {
-  return ix->scan_impl == 4 && split_built(ix) && nq * nprobe >= (int64_t)ix->split_min_pairs * ix->nlist;
+  return (ix->scan_impl == 4 || ix->scan_impl == 3) && split_built(ix) &&
+         nq * nprobe >= (int64_t)ix->split_min_pairs * ix->nlist;
 }
 int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe);
 // makes the handle's survivor-bit buffer large enough for (nq, nprobe); may allocate (then it synchronises the device)
-int ensure_split_mask(rabitq_index* ix, int64_t nq, int nprobe);
+int ensure_split_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k);
 // The same for nprobe <= 64, k <= 64 and a bitwise scan, preceded in the same kernel by the selection of the probes
 // from the coarse scores and the seeding of the thresholds (one workgroup per query; the last one to finish builds the
 // lists): everything between the coarse scores and the scan in one launch.

@@ -9,6 +9,18 @@ namespace rq {
 // and tau is the k-th smallest refined estimate.
 constexpr int SEED_M = 32;
 
+// What the refinement-only kernel of the split search needs to know about a work item, looked up once by a kernel of
+// its own instead of by every item through a chain of dependent loads (item -> cluster -> offsets -> ...).
+struct ItemDesc {
+  int32_t pbeg;     // first pair of the item
+  int32_t np_mg;    // pairs of the item | (group of 4 inside its group of 16) << 8
+  int32_t t0;       // first tile of the cluster
+  int32_t ts, te;   // tiles of the item's segment
+  int32_t nseg;     // segments the cluster is scanned in
+  uint32_t mblock;  // block of survivor bits of (group of 16, tile ts)
+  int32_t pad;
+};
+
 struct ScanArgs {
   // index
   const uint32_t* short_codes;
@@ -46,6 +58,7 @@ struct ScanArgs {
   const int32_t* item_off16;
   const uint32_t* mask_off;
   uint64_t* surv_mask;
+  ItemDesc* item_desc;  // [work items of 4 pairs]
   int nprobe, k, pool, cand_stride;
   int streaming;     // few pairs per list: every list is read from memory about once (prefetching scan variant)
   int tseg, segmax;  // a cluster of more than tseg tiles is scanned in up to segmax segments (separate work items)

@@ -438,21 +438,38 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   const int per = (n_items + 7) >> 3;
   const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
   if ((int)(blockIdx.x >> 3) >= per || item >= n_items) return;
-  // cluster of this item: largest c with item_off[c] <= item
-  const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
-  // a long cluster is scanned in nseg segments by separate work items
-  const int t0 = a.tile_off[c], tc1 = a.tile_off[c + 1];
-  const int nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
-  const int local = item - a.item_off[c];
-  const int grp = local / nseg, sidx = local - grp * nseg;
-  const int seglen = (tc1 - t0 + nseg - 1) / nseg;
-  const int ts = t0 + sidx * seglen, te = min(tc1, ts + seglen);
-  const int pbeg = a.pair_off[c] + grp * QW;
-  const int np = __builtin_amdgcn_readfirstlane(min(QW, a.pair_off[c + 1] - pbeg));  // the same in all lanes
+  int t0, nseg, ts, te, pbeg, np;
   // MASKED: blocks of survivor bits of this item's group of 16 pairs (its 4 pairs are lane group `mg` of every word)
-  const int mg = grp & 3;
+  int mg = 0;
   const uint64_t* mblk = nullptr;
-  if (MASKED) mblk = a.surv_mask + ((int64_t)a.mask_off[c] + (int64_t)(grp >> 2) * (tc1 - t0) + (ts - t0)) * 16;
+  if (MASKED) {
+    // (everything about the item was laid down by item_desc_kernel: one load instead of a chain of dependent ones,
+    // which is what a kernel that only refines would spend its time waiting for)
+    typedef const ItemDesc __attribute__((address_space(4)))* const_desc_ptr;
+    const_desc_ptr d = (const_desc_ptr)(a.item_desc + item);
+    pbeg = d->pbeg;
+    np = d->np_mg & 255;
+    mg = d->np_mg >> 8;
+    t0 = d->t0;
+    ts = d->ts;
+    te = d->te;
+    nseg = d->nseg;
+    mblk = a.surv_mask + (int64_t)d->mblock * 16;
+  } else {
+    // cluster of this item: largest c with item_off[c] <= item
+    const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
+    // a long cluster is scanned in nseg segments by separate work items
+    t0 = a.tile_off[c];
+    const int tc1 = a.tile_off[c + 1];
+    nseg = seg_count(tc1 - t0, a.tseg, a.segmax);
+    const int local = item - a.item_off[c];
+    const int grp = local / nseg, sidx = local - grp * nseg;
+    const int seglen = (tc1 - t0 + nseg - 1) / nseg;
+    ts = t0 + sidx * seglen;
+    te = min(tc1, ts + seglen);
+    pbeg = a.pair_off[c] + grp * QW;
+    np = __builtin_amdgcn_readfirstlane(min(QW, a.pair_off[c + 1] - pbeg));  // the same in all lanes
+  }
 
   constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead
   uint32_t pw[PD > 0 ? PD : 1][W];

@@ -86,6 +86,57 @@ __global__ __launch_bounds__(256) void split_offsets_kernel(const int32_t* __res
   }
 }
 
+// One wavefront per cluster writes the descriptors of its work items of QW pairs (split search).
+__global__ __launch_bounds__(64) void item_desc_kernel(const int32_t* __restrict__ pair_off, const int32_t* __restrict__ tile_off,
+                                                      const int32_t* __restrict__ item_off, const uint32_t* __restrict__ mask_off,
+                                                      int tseg, int segmax, ItemDesc* __restrict__ desc) {
+  const int c = blockIdx.x;
+  const int i0 = item_off[c], n = item_off[c + 1] - i0;
+  if (n <= 0) return;
+  const int t0 = tile_off[c], tiles = tile_off[c + 1] - t0;
+  const int p0 = pair_off[c], cnt = pair_off[c + 1] - p0;
+  const int nseg = seg_count(tiles, tseg, segmax);
+  const int seglen = (tiles + nseg - 1) / nseg;
+  const uint32_t m0 = mask_off[c];
+  for (int it = threadIdx.x; it < n; it += 64) {
+    const int grp = it / nseg, sidx = it - grp * nseg;
+    ItemDesc d;
+    d.pbeg = p0 + grp * QW;
+    d.np_mg = min(QW, cnt - grp * QW) | ((grp & 3) << 8);
+    d.t0 = t0;
+    d.ts = t0 + sidx * seglen;
+    d.te = min(t0 + tiles, d.ts + seglen);
+    d.nseg = nseg;
+    d.mblock = m0 + (uint32_t)((grp >> 2) * tiles + sidx * seglen);
+    d.pad = 0;
+    desc[i0 + it] = d;
+  }
+}
+
+// segments per cluster, sorted, for the work-item bound of a launch (cached per segment length and limit)
+static void update_seg_cache(const rabitq_index* ix, int tseg, int segmax) {
+  std::vector<int>& nseg = ix->seg_sorted;
+  if (ix->seg_sorted_max == segmax && ix->seg_sorted_tseg == tseg) return;
+  nseg.resize(ix->host_tiles.size());
+  for (size_t c = 0; c < nseg.size(); ++c) nseg[c] = seg_count(ix->host_tiles[c], tseg, segmax);
+  std::sort(nseg.begin(), nseg.end(), std::greater<int>());
+  ix->seg_sorted_max = segmax;
+  ix->seg_sorted_tseg = tseg;
+  ix->seg_total = 0;
+  for (int v : nseg) ix->seg_total += v;
+}
+
+// Work-item bound.  Cluster c with cnt_c pairs and nseg_c segments has ceil(cnt_c / per_item) * nseg_c work items, at
+// most (cnt_c / per_item + 1) * nseg_c.  Every query probes nprobe distinct clusters, so cnt_c <= nq and sum cnt_c =
+// nq * nprobe: the sum is largest when the nprobe clusters with the most segments are probed by every query.
+static int64_t item_bound(const rabitq_index* ix, int64_t nq, int nprobe, int per_item) {
+  const std::vector<int>& nseg = ix->seg_sorted;
+  int64_t top = 0;
+  for (int i = 0; i < nprobe && i < (int)nseg.size(); ++i) top += nseg[i];
+  const int64_t m = ix->seg_total + (nq * top + per_item - 1) / per_item;
+  return ((m + 7) / 8) * 8;
+}
+
 int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe) {
   if (ix->tiles_prefix.empty()) {
     std::vector<int> t(ix->host_tiles.begin(), ix->host_tiles.end());
@@ -97,16 +148,28 @@ int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe) {
   return (nq * ix->tiles_prefix[top] + QM - 1) / QM + ix->n_tiles;
 }
 
-int ensure_split_mask(rabitq_index* ix, int64_t nq, int nprobe) {
+int ensure_split_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k) {
   const int64_t need = split_mask_blocks(ix, nq, nprobe);
-  if (need <= ix->surv_mask_blocks) return RABITQ_OK;
-  if (need >= ((int64_t)1 << 32)) return RABITQ_OK;  // too many blocks for 32-bit offsets: the search is not split
+  const ScanPlan plan = scan_plan(ix, nq, nprobe, k);
+  update_seg_cache(ix, plan.tseg, plan.segmax);
+  const int64_t items = item_bound(ix, nq, nprobe, QW);
+  if (need <= ix->surv_mask_blocks && items <= ix->item_desc_cap) return RABITQ_OK;
+  if (need >= ((int64_t)1 << 32) || items > 0x7fffffff) return RABITQ_OK;  // beyond 32-bit offsets: the search is not split
   RQ_HIP(hipDeviceSynchronize());
-  if (ix->surv_mask) (void)hipFree(ix->surv_mask);
-  ix->surv_mask = nullptr;
-  ix->surv_mask_blocks = 0;
-  RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->surv_mask), (size_t)need * 16 * sizeof(uint64_t)));
-  ix->surv_mask_blocks = need;
+  if (need > ix->surv_mask_blocks) {
+    if (ix->surv_mask) (void)hipFree(ix->surv_mask);
+    ix->surv_mask = nullptr;
+    ix->surv_mask_blocks = 0;
+    RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->surv_mask), (size_t)need * 16 * sizeof(uint64_t)));
+    ix->surv_mask_blocks = need;
+  }
+  if (items > ix->item_desc_cap) {
+    if (ix->item_desc) (void)hipFree(ix->item_desc);
+    ix->item_desc = nullptr;
+    ix->item_desc_cap = 0;
+    RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->item_desc), (size_t)items * sizeof(ItemDesc)));
+    ix->item_desc_cap = items;
+  }
   return RABITQ_OK;
 }
 
@@ -285,16 +348,23 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   }
   // Split search: the estimates of groups of 16 pairs on the matrix cores, then this kernel's refinement only.
   // Chosen when asked for (scan_impl 4), built for the index, worth it for the batch, and the handle's buffer of
-  // survivor bits is large enough (ensure_split_mask, called by the entry points that may allocate).
-  const bool split = split_wanted(ix, nq, nprobe) && ix->surv_mask != nullptr && split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks;
+  // survivor bits is large enough (ensure_split_buffers, called by the entry points that may allocate).
+  update_seg_cache(ix, a.tseg, a.segmax);
+  const int64_t max_items = item_bound(ix, nq, nprobe, qw);
+  const bool split = split_wanted(ix, nq, nprobe) && ix->surv_mask != nullptr && ix->item_desc != nullptr &&
+                     split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks &&
+                     max_items <= ix->item_desc_cap;
   if (split) {
     int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
     uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
     hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, a.tseg, a.segmax,
                        item16, mask_off);
+    hipLaunchKernelGGL(item_desc_kernel, dim3((unsigned)ix->nlist), dim3(64), 0, sst, pair_off, ix->tile_off, item_off,
+                       mask_off, a.tseg, a.segmax, ix->item_desc);
     a.item_off16 = item16;
     a.mask_off = mask_off;
     a.surv_mask = ix->surv_mask;
+    a.item_desc = ix->item_desc;
     // (the refinement-only kernel lives on wavefronts in flight: smaller pools, checked every second round of 16 keys)
     a.pool = std::max(64, next_pow2_host(k + 32));
   }
@@ -304,25 +374,6 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     RQ_HIP(hipStreamWaitEvent(st, ss.join, 0));
   }
   if (ss.scan_b) RQ_HIP(hipEventRecord(ss.scan_b, st));
-  // Grid bound.  Cluster c with cnt_c pairs and nseg_c segments has ceil(cnt_c / qw) * nseg_c work items, at most
-  // (cnt_c / qw + 1) * nseg_c.  Every query probes nprobe distinct clusters, so cnt_c <= nq and sum cnt_c = nq * nprobe:
-  // the sum is largest when the nprobe clusters with the most segments are probed by every query.  The kernel
-  // drops the blocks beyond the true count.
-  const int64_t npairs = nq * nprobe;
-  std::vector<int>& nseg = ix->seg_sorted;
-  if (ix->seg_sorted_max != a.segmax || ix->seg_sorted_tseg != a.tseg) {
-    nseg.resize(ix->host_tiles.size());
-    for (size_t c = 0; c < nseg.size(); ++c) nseg[c] = seg_count(ix->host_tiles[c], a.tseg, a.segmax);
-    std::sort(nseg.begin(), nseg.end(), std::greater<int>());
-    ix->seg_sorted_max = a.segmax;
-    ix->seg_sorted_tseg = a.tseg;
-    ix->seg_total = 0;
-    for (int v : nseg) ix->seg_total += v;
-  }
-  int64_t top = 0;
-  for (int i = 0; i < nprobe && i < (int)nseg.size(); ++i) top += nseg[i];
-  int64_t max_items = ix->seg_total + (nq * top + qw - 1) / qw;
-  max_items = ((max_items + 7) / 8) * 8;
   if (max_items > 0x7fffffff) {
     set_error("scan: too many work items");
     return RABITQ_EINVAL;
@@ -331,8 +382,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   const bool dbg = dbg_ip != nullptr;
   const int W = ix->W, F = field_bits(ix->total_bits);
   if (split) {
-    int64_t items16 = ix->seg_total + (nq * top + QM - 1) / QM;  // the same bound with 16 pairs per item
-    items16 = ((items16 + 7) / 8) * 8;
+    const int64_t items16 = item_bound(ix, nq, nprobe, QM);  // the same bound with 16 pairs per item
     if (!estimate_mfma(a, W, (unsigned)items16, dbg, st)) return bad_width();
     RQ_HIP(hipGetLastError());
   }
