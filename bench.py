@@ -189,11 +189,13 @@ def measure_point(gi, Qd, gt, w, bits, args, label):
 
     # timed region: only the scan kernel's two events are recorded (every recorded stage costs two event records
     # per search); the other stages are timed in a separate short pass afterwards
-    gi.set_option("profile_stages", 1 << 7)
+    gi.set_option("profile_stages", (1 << 7) | (1 << 9))
     sec = timed(nprobe, args.steps, args.warmup, profile=True)
-    scan_ms = gi.stage_ms()[0]["scan"]
+    timed_ms = gi.stage_ms()[0]
+    scan_ms, est_ms = timed_ms["scan"], timed_ms["scan_estimate"]
+    split = bool(gi.index_info("last_scan_split"))
     r_op = recall(out_ids, gt)
-    gi.set_option("profile_stages", 0x1ff)
+    gi.set_option("profile_stages", 0x3ff)
     timed(nprobe, min(args.steps, 20), 0, profile=True)
     stage_ms, calls = gi.stage_ms()
     gi.set_option("profile", 0)
@@ -204,7 +206,8 @@ def measure_point(gi, Qd, gt, w, bits, args, label):
     r_unpruned = recall(out_ids, gt)
     gi.set_option("prune", 1)
     return dict(total_bits=bits, nprobe=nprobe, recall_at_k=round(r_op, 4), recall_at_k_unpruned=round(r_unpruned, 4),
-                qps=w.nq / sec, ms_per_step=sec * 1e3, scan_ms=scan_ms, nprobe_sweep=sweep,
+                qps=w.nq / sec, ms_per_step=sec * 1e3, scan_ms=scan_ms, scan_split=split, scan_estimate_ms=est_ms,
+                nprobe_sweep=sweep,
                 stage_ms={k_: round(v, 4) for k_, v in stage_ms.items()}, stage_ms_calls=calls)
 
 
@@ -219,7 +222,9 @@ def scan_roofline(gi, Qd, w, pt, cluster_sizes, args):
     impl = args.scan_impl if args.scan_impl != 3 else (1 if w.dim >= 960 else 0)
     alu_ops = qv * (8 * (w.dim // 32) + 6)
     alu_achieved = alu_ops / (scan_ms * 1e-3) / 1e12
-    traffic, traffic_note = (stored_traffic(w.name, pt["nprobe"]) if impl == 0 and pt["total_bits"] == w.total_bits
+    split = pt.get("scan_split", False)
+    traffic, traffic_note = (stored_traffic(w.name, pt["nprobe"])
+                             if impl == 0 and not split and pt["total_bits"] == w.total_bits
                              else (None, "no counter summary for this variant"))
     roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TOPS, "unit": "TOP/s (integer lane-operations)",
                 "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic, "traffic_source": traffic_note,
@@ -228,7 +233,23 @@ def scan_roofline(gi, Qd, w, pt, cluster_sizes, args):
                 "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_gbs": achieved, "peak_gbs": HBM_PEAK_GBS,
                              "frac": achieved / HBM_PEAK_GBS,
                              "note": "above 1 when the launch is cache-served; the HBM-bound regime is roofline.stream"}}
-    if impl in (1, 4):
+    if split:
+        # Split search: the estimates run as estimate_mfma_kernel (matrix cores), the refinement as scan_kernel in its
+        # refinement-only form; kernel_ms is the time of the two together (HIP events around both), and `achieved`
+        # prices the stage with the same algorithmic figure as the fused kernel, 8W + 6 lane-operations per evaluation.
+        est_ms = pt["scan_estimate_ms"]
+        mfma_ops = qv * 2 * w.dim
+        roofline.update({
+            "kernel": "estimate_mfma_kernel + scan_kernel (refinement only)",
+            "kernels_ms": {"estimate_mfma_kernel": est_ms, "scan_kernel (refinement only)": scan_ms - est_ms},
+            "note": "the 1-bit inner products of this stage run on the matrix cores, so the vector ALUs execute fewer "
+                    "operations than the algorithmic figure counts: frac is the rate of popcount-equivalent work "
+                    "against the vector peak, not the share of issue slots used",
+            "estimate_kernel_mfma_view": {"int8_ops_per_launch": mfma_ops,
+                                          "achieved_tops": mfma_ops / (est_ms * 1e-3) / 1e12 if est_ms > 0 else None,
+                                          "peak_tops": MFMA_I8_PEAK_TOPS,
+                                          "frac": mfma_ops / (est_ms * 1e-3) / 1e12 / MFMA_I8_PEAK_TOPS if est_ms > 0 else None}})
+    if impl == 1:
         # the matrix-core scan contracts sign bytes with the int8 query: 2 D integer operations per evaluation on
         # v_mfma_i32_16x16x64_i8, priced against the dense int8 peak
         mfma_ops = qv * 2 * w.dim

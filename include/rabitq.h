@@ -179,7 +179,7 @@ int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq
  *   "prune"   1 (default): filter with the per-query seeded threshold (Section 3.3.4);
  *             0: refine every vector of every probed cluster (the unpruned definition).
  *   "profile" n: see rabitq_stage_ms.
- *   "profile_stages" m: bit s of m (1..511, default all) selects whether stage s of rabitq_stage_ms is
+ *   "profile_stages" m: bit s of m (1..1023, default all) selects whether stage s of rabitq_stage_ms is
  *             recorded; unrecorded stages report 0.  Recording costs two event records per stage and search.
  *   "overlap" 1 (default): inside a search of 256 or more queries the pair lists and the scan's work-item table
  *             are built on a second stream owned by the handle (default priority), beside the threshold seeding;
@@ -215,7 +215,8 @@ int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq
 int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
 /* Host-visible sizes of an uploaded index: name in {"n","n_tiles","n_slots","dim","nlist",
- * "total_bits","long_field_bits","metric"}.  Returns the value, or a negative status. */
+ * "total_bits","long_field_bits","metric"}, or "last_scan_split": 1 if the scan of the latest rabitq_search /
+ * rabitq_scan on the handle was split ("scan_impl" 4), else 0.  Returns the value, or a negative status. */
 int64_t rabitq_index_info(rabitq_index_t index, const char* name);
 
 /* Per-stage timing.  The option "profile" = n (0..4096) makes the next n searches record
@@ -223,8 +224,9 @@ int64_t rabitq_index_info(rabitq_index_t index, const char* name);
  * search itself); setting it again restarts the recording.  rabitq_stage_ms waits for the
  * last recorded search and returns the MEAN duration in milliseconds of each stage over
  * the recorded searches.
- *   out_ms: host, [9]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
- *           scan set-up (work-item offsets), scan kernel, merge; each is the time between two events on the
+ *   out_ms: host, [10]: rotate, query_prep, coarse GEMM, probe select, list build, seed,
+ *           scan set-up (work-item offsets), scan (all its kernels), merge, and the estimate kernel of a split scan
+ *           ("scan_impl" 4; part of the scan's time, 0 when the scan was not split); each is the time between two events on the
  *           stream the stage ran on, so with "overlap" their sum exceeds the duration of the search
  *   out_calls: host, number of searches the means were taken over (may be NULL)
  * Errors: RABITQ_EINVAL (null pointer, nothing recorded), RABITQ_EHIP. */

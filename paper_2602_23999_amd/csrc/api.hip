@@ -404,7 +404,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!std::strcmp(name, "max_batch") && value >= 0 && value <= 0x7fffffff) { ix->max_batch = value; return RABITQ_OK; }
   if (!std::strcmp(name, "small_batch") && (value == 0 || value == 1)) { ix->small_batch = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "scan_segment_tiles") && value >= 0 && value <= 4096) { ix->seg_tiles = (int)value; return RABITQ_OK; }
-  if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x1ff) {
+  if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x3ff) {
     ix->prof_mask = (unsigned)value;
     ix->prof_used = 0;
     return RABITQ_OK;
@@ -440,6 +440,7 @@ int64_t rabitq_index_info(rabitq_index_t ix, const char* name) {
   if (!std::strcmp(name, "total_bits")) return ix->total_bits;
   if (!std::strcmp(name, "long_field_bits")) return ix->F;
   if (!std::strcmp(name, "metric")) return ix->metric;
+  if (!std::strcmp(name, "last_scan_split")) return ix->last_scan_split;
   set_error("index_info: unknown name");
   return RABITQ_EINVAL;
 }
@@ -577,8 +578,10 @@ int rabitq_scan(rabitq_index_t ix, const rabitq_query_repr* repr, const float* p
     if ((rc = ensure_split_buffers(ix, nq, nprobe, k))) return rc;
   ScanStreams ss;
   ss.main = ss.setup = (hipStream_t)stream;
-  return launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
-                     dbg_off, ss);
+  rc = launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
+                   dbg_off, ss);
+  ix->last_scan_split = ss.split ? 1 : 0;
+  return rc;
 }
 
 int rabitq_merge(rabitq_index_t ix, const uint64_t* cand_keys, const int32_t* cand_cnt, int64_t nq, int32_t k,
@@ -680,9 +683,12 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
   ss.setup_done = small;
   if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; ev->rec |= 1u << 6; }
   if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; ev->rec |= 1u << 7; }
+  if (ev && ((ix->prof_mask >> 9) & 1u)) { ss.est_b = ev->b[9]; ss.est_e = ev->e[9]; }
   if ((rc = launch_scan(ix, w.repr, w.probe_G, w.probe_E, w.pair_off, w.pair_ids, w.tau, nq, k, nprobe, w.cand_keys,
                         w.cand_cnt, nullptr, nullptr, ss)) != RABITQ_OK)
     return rc;
+  if (ss.est_b && ss.split) ev->rec |= 1u << 9;
+  ix->last_scan_split = ss.split ? 1 : 0;
   RQ_STAGE(8, st, launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
 #undef RQ_STAGE
   return RABITQ_OK;

@@ -71,6 +71,7 @@ struct rabitq_index {
   int scan_impl = 3;  // 0 popcount, 1 matrix cores, 2 lookup tables, 3 chosen by code width (see effective_impl),
                       // 4 estimates on the matrix cores + refinement by the popcount kernel (split search)
   // survivor bits of the split search: blocks of 16 words; grown on demand by ensure_split_buffers, kept by the handle
+  int last_scan_split = 0;   // the scan of the latest rabitq_search / rabitq_scan was split (rabitq_index_info)
   int split_min_pairs = 32;  // pairs per list, on average, from which scan_impl 3 / 4 split the search
   uint64_t* surv_mask = nullptr;
   int64_t surv_mask_blocks = 0;
@@ -84,13 +85,13 @@ struct rabitq_index {
   // second stream of a search (default priority) and the events that fork it from and join it to the caller's
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
-  static constexpr int N_STAGES = 9;
+  static constexpr int N_STAGES = 10;
   // begin / end of every stage, on the stream it ran on; bit s of `rec`: stage s was recorded in this search (a
   // small batch runs several stages as one kernel, recorded under the first of them)
   struct EventSet { hipEvent_t b[N_STAGES], e[N_STAGES]; unsigned rec; };
   std::vector<EventSet> prof_sets;  // one per recorded search
   int prof_used = 0, prof_limit = 0;
-  unsigned prof_mask = 0x1ffu;  // stages whose events are recorded (bit s = stage s)
+  unsigned prof_mask = 0x3ffu;  // stages whose events are recorded (bit s = stage s)
   rq::Workspace ws;
 };
 
@@ -152,6 +153,8 @@ struct ScanStreams {
   hipStream_t main = nullptr, setup = nullptr;
   hipEvent_t join = nullptr;
   hipEvent_t setup_b = nullptr, setup_e = nullptr, scan_b = nullptr, scan_e = nullptr;
+  hipEvent_t est_b = nullptr, est_e = nullptr;  // around the estimate kernel of a split search
+  mutable bool split = false;                  // out: the search was split
   bool counters_clear = false;  // cand_cnt was already zeroed by launch_clear_counters
   bool setup_done = false;      // work-item offsets and counters were already prepared (launch_small_batch_lists)
 };

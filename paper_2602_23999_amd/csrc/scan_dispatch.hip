@@ -354,6 +354,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   const bool split = split_wanted(ix, nq, nprobe) && ix->surv_mask != nullptr && ix->item_desc != nullptr &&
                      split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks &&
                      max_items <= ix->item_desc_cap;
+  ss.split = split;
   if (split) {
     int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
     uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
@@ -383,8 +384,10 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   const int W = ix->W, F = field_bits(ix->total_bits);
   if (split) {
     const int64_t items16 = item_bound(ix, nq, nprobe, QM);  // the same bound with 16 pairs per item
+    if (ss.est_b) RQ_HIP(hipEventRecord(ss.est_b, st));
     if (!estimate_mfma(a, W, (unsigned)items16, dbg, st)) return bad_width();
     RQ_HIP(hipGetLastError());
+    if (ss.est_e) RQ_HIP(hipEventRecord(ss.est_e, st));
   }
   if (!(scan_part0(a, W, F, impl, grid, dbg, st) || scan_part1(a, W, F, impl, grid, dbg, st) ||
         scan_part2(a, W, F, impl, grid, dbg, st)))

@@ -253,11 +253,11 @@ class Index:
         return int(v)
 
     STAGES = ["rotate", "query_prep", "coarse_gemm", "probe_select", "list_build", "seed", "scan_setup", "scan",
-              "merge"]
+              "merge", "scan_estimate"]
 
     def stage_ms(self):
         """Mean per-stage milliseconds over the searches recorded since set_option("profile", n)."""
-        buf = (C.c_float * 9)()
+        buf = (C.c_float * 10)()
         calls = C.c_int32(0)
         _check(load_library().rabitq_stage_ms(self._h, buf, C.byref(calls)))
         return dict(zip(self.STAGES, [float(x) for x in buf])), int(calls.value)

@@ -29,6 +29,15 @@ def test_l2_128_full_size_sampled_parity():
     ids2, dist2 = gi.search(Qd, k, nprobe)
     torch.cuda.synchronize()
     assert torch.equal(ids, ids2) and torch.equal(dist, dist2)          # deterministic
+    # at this size the library splits the scan (estimates on the matrix cores, then refinement only); the fused
+    # popcount kernel must give the very same answers
+    assert gi.index_info("last_scan_split") == 1
+    gi.set_option("scan_impl", 0)
+    ids0, dist0 = gi.search(Qd, k, nprobe)
+    torch.cuda.synchronize()
+    assert gi.index_info("last_scan_split") == 0
+    assert torch.equal(ids, ids0) and torch.equal(dist, dist0)
+    gi.set_option("scan_impl", 3)
     ids, dist = ids.cpu().numpy(), dist.cpu().numpy().astype(np.float64)
     # properties on every row
     assert ids.min() >= 0 and ids.max() < w.n
