@@ -5,9 +5,11 @@
 // Splitting the stages lets each run at its own occupancy: this kernel needs registers and no LDS, the refinement
 // needs LDS and many wavefronts in flight to hide the scattered long-code reads.
 //
-// Survivor bits.  A block of 16 words of 64 bits belongs to (cluster, group of 16 pairs, tile); the blocks of cluster c
-// start at mask_off[c] and are ordered [group][tile].  Word 4 r + cb of a block is the ballot of the comparison for
-// accumulator r of column block cb: bit 16 g + lj is pair 4 g + r of the group and vector 16 cb + lj of the tile.
+// Survivor bits.  A block of 128 bytes belongs to (cluster, group of 16 pairs, tile); the blocks of cluster c start at
+// mask_off[c] and are ordered [group][tile].  A block is what the 64 lanes of the wavefront hold after the tile: lane
+// 16 g + lj writes 16 bits about vectors 16 cb + lj (cb = 0..3) and pairs 4 g + r (r = 0..3) of the group; bit
+// 4 cb + r is SET when that vector does NOT survive for that pair (the sign of tau minus the bound, shifted in as the
+// comparisons are made).
 #include "rq_device.h"
 #include "rq_scan_args.h"
 
@@ -33,7 +35,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4))) void es
   const int pbeg = a.pair_off[c] + grp * QM;
   const int np = __builtin_amdgcn_readfirstlane(min(QM, a.pair_off[c + 1] - pbeg));
   // first block of this group's tiles
-  uint64_t* blocks = a.surv_mask + ((int64_t)a.mask_off[c] + (int64_t)grp * (tc1 - t0)) * 16;
+  uint16_t* blocks = reinterpret_cast<uint16_t*>(a.surv_mask + ((int64_t)a.mask_off[c] + (int64_t)grp * (tc1 - t0)) * 16);
 
   // One tile as the matrix instruction wants it: lane (lj, g) holds, for each of the 4 column blocks of 16 vectors,
   // word 2 kc + g/2 of vector 16 cb + lj (it expands half g % 2 of it) and that vector's three factors.
@@ -105,14 +107,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4))) void es
         acc[cb] = __builtin_amdgcn_mfma_i32_16x16x64_i8(qa[kc], expand_half(word, g & 1), acc[cb], 0, 0, 0);
       }
     }
-    // lane 4 r + cb collects the ballot of (cb, r): the 16 words of the tile's block go out in one store
-    uint32_t mlo = 0u, mhi = 0u;
+    // one instruction per comparison: the sign bit of tau - bound (set: the bound is above the threshold; minus
+    // infinity for padding, whose f_add is +inf) is shifted into the lane's word.  No operand can be a NaN: the
+    // radius Er is positive, so an infinite error factor gives a bound of minus infinity, not inf * 0.
+    // (the last comparison ends up in bit 0: descending order leaves (cb, r) in bit 4 cb + r)
+    uint32_t bits = 0u;
 #pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
+    for (int cb = 3; cb >= 0; --cb) {
       const int v = 16 * cb + lj;
       const float fa = t.fa[cb], fr = t.fr[cb], fe = t.fe[cb];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
+      for (int r = 3; r >= 0; --r) {
         const int I = acc[cb][r];
         if (DBG) {
           if (4 * g + r < np) a.dbg_ip[a.dbg_off[pbeg + 4 * g + r] + (int64_t)(tile - t0) * TILE + v] = I;
@@ -120,13 +125,10 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4))) void es
         const float x = fmaf(al[r], (float)I, -be[r]);  // delta * (I - S/2)
         const float e1 = fmaf(fr, x, fa + Gr[r]);
         const float filt = fmaf(-fe, Er[r], e1);
-        const uint64_t m = __ballot(filt <= tr[r]);
-        const bool here = lane == 4 * r + cb;
-        mlo = here ? (uint32_t)m : mlo;
-        mhi = here ? (uint32_t)(m >> 32) : mhi;
+        bits = __builtin_amdgcn_alignbit(bits, __float_as_uint(tr[r] - filt), 31);  // (bits << 1) | sign
       }
     }
-    if (lane < 16) blocks[(int64_t)(tile - t0) * 16 + lane] = ((uint64_t)mhi << 32) | mlo;
+    blocks[(int64_t)(tile - t0) * TILE + lane] = (uint16_t)bits;
   };
 
   // two tiles per iteration, so that the registers of the tile in flight and of the tile in work swap roles

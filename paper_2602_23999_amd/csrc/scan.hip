@@ -441,7 +441,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   int t0, nseg, ts, te, pbeg, np;
   // MASKED: blocks of survivor bits of this item's group of 16 pairs (its 4 pairs are lane group `mg` of every word)
   int mg = 0;
-  const uint64_t* mblk = nullptr;
+  const uint16_t* mblk = nullptr;
   if (MASKED) {
     // (everything about the item was laid down by item_desc_kernel: one load instead of a chain of dependent ones,
     // which is what a kernel that only refines would spend its time waiting for)
@@ -454,7 +454,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     ts = d->ts;
     te = d->te;
     nseg = d->nseg;
-    mblk = a.surv_mask + (int64_t)d->mblock * 16;
+    mblk = reinterpret_cast<const uint16_t*>(a.surv_mask + (int64_t)d->mblock * 16);
   } else {
     // cluster of this item: largest c with item_off[c] <= item
     const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
@@ -640,16 +640,21 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   };
 
   if (MASKED) {
-    // The first stage is done: MASK_BATCH words of survivor bits (2 tiles) are turned into list entries at a time.  Lane
-    // l < MASK_BATCH takes word wb + l, which is (tile, pair j, column block cb) = ((wb + l) / 16, ((wb + l) / 4) % 4, (wb + l) % 4);
-    // its bits 16 mg .. 16 mg + 15 are this item's pair j against vectors 16 cb .. 16 cb + 15 of the tile.
+    // The first stage is done: the survivor bits of MASK_BATCH / 16 tiles are turned into list entries at a time.  A
+    // block holds, for each of the 4 groups of 4 pairs and each lj = 0..15, a 16-bit word about vectors 16 cb + lj and
+    // pairs r of the group: bit 4 cb + r set = does not survive.  Lane l < MASK_BATCH takes word (tile wb / 16 + l / 16,
+    // this item's group mg, lj = l % 16).
     const int nwords = (te - ts) * 16;
-    uint64_t wnext = (lane < MASK_BATCH && lane < nwords) ? mblk[lane] : 0ull;
+    const uint32_t present = 0x1111u * ((1u << np) - 1u);  // bits of the pairs this item has (r < np)
+    auto word_at = [&](int wi) -> uint32_t {
+      return (lane < MASK_BATCH && wi < nwords) ? (uint32_t)mblk[(int64_t)(wi >> 4) * TILE + 16 * mg + (wi & 15)] : 0xffffu;
+    };
+    uint32_t wnext = word_at(lane);
     for (int wb = 0; wb < nwords; wb += MASK_BATCH) {
-      const uint64_t wcur = wnext;
-      wnext = (lane < MASK_BATCH && wb + MASK_BATCH + lane < nwords) ? mblk[wb + MASK_BATCH + lane] : 0ull;
+      const uint32_t wcur = wnext;
+      wnext = word_at(wb + MASK_BATCH + lane);
       const int wi = wb + lane;
-      uint32_t field = (uint32_t)(wcur >> (16 * mg)) & 0xffffu;
+      uint32_t field = ~wcur & present;
       const int mine_n = __popc(field);
       int incl = mine_n;  // inclusive scan over the lanes
 #pragma unroll
@@ -661,9 +666,10 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       if (total == 0) continue;
       if (list_cnt + total > LCAP) flush();
       int pos = list_cnt + incl - mine_n;
-      const uint32_t entry0 = ((uint32_t)((wi >> 2) & 3) << 30) | (uint32_t)((ts - t0 + (wi >> 4)) * TILE + 16 * (wi & 3));
+      const uint32_t pos0 = (uint32_t)((ts - t0 + (wi >> 4)) * TILE + (wi & 15));
       while (field != 0u) {
-        list[pos++] = entry0 | (uint32_t)(__ffs(field) - 1);
+        const int b = __ffs(field) - 1;  // bit 4 cb + r
+        list[pos++] = ((uint32_t)(b & 3) << 30) | (pos0 + 16u * (uint32_t)(b >> 2));
         field &= field - 1u;
       }
       list_cnt += total;
