@@ -68,7 +68,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4))) void es
   v4i qa[KC];
   {
     const int pp = a.pair_ids[pbeg + min(lj, np - 1)];
-    const int64_t q = pp / a.nprobe;
+    const int64_t q = pair_query(a, pp);
     const int8_t* src = a.qhat8 + q * a.Dp + 16 * g;
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
@@ -82,7 +82,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(4))) void es
   for (int r = 0; r < 4; ++r) {
     const int qi = 4 * g + r;
     const int pp = a.pair_ids[pbeg + min(qi, np - 1)];
-    const int64_t q = pp / a.nprobe;
+    const int64_t q = pair_query(a, pp);
     const float dl = a.delta[q];
     al[r] = dl;
     be[r] = 0.5f * dl * (float)a.sum_qhat[q];

@@ -60,6 +60,10 @@ struct ScanArgs {
   uint64_t* surv_mask;
   ItemDesc* item_desc;  // [work items of 4 pairs]
   int nprobe, k, pool, cand_stride;
+  // pair / nprobe without a division: (pair * nprobe_mul) >> nprobe_shift is exact for pair < 2^31 when nprobe_mul =
+  // ceil(2^(31 + L) / nprobe), nprobe_shift = 31 + L and 2^L >= nprobe (set_nprobe)
+  uint64_t nprobe_mul;
+  int nprobe_shift;
   int streaming;     // few pairs per list: every list is read from memory about once (prefetching scan variant)
   int tseg, segmax;  // a cluster of more than tseg tiles is scanned in up to segmax segments (separate work items)
   // outputs
@@ -69,6 +73,18 @@ struct ScanArgs {
   int32_t* dbg_ip;
   const int64_t* dbg_off;
 };
+
+inline void set_nprobe(ScanArgs& a, int nprobe) {
+  int L = 0;
+  while ((1 << L) < nprobe) ++L;
+  a.nprobe = nprobe;
+  a.nprobe_shift = 31 + L;
+  a.nprobe_mul = (((uint64_t)1 << (31 + L)) + (uint64_t)nprobe - 1) / (uint64_t)nprobe;  // L <= 31: no overflow
+}
+// query of a pair (pairs are numbered query * nprobe + rank)
+__host__ __device__ inline int pair_query(const ScanArgs& a, int pair) {
+  return (int)(((uint64_t)(uint32_t)pair * a.nprobe_mul) >> a.nprobe_shift);
+}
 
 // number of segments a cluster of `tiles` tiles is split into
 __host__ __device__ inline int seg_count(int tiles, int tseg, int segmax) {

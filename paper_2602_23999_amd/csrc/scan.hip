@@ -492,7 +492,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
 #pragma unroll
   for (int j = 0; j < QW; ++j) {
     const int pp = a.pair_ids[pbeg + min(j, np - 1)];
-    const int64_t q = pp / a.nprobe;
+    const int64_t q = pair_query(a, pp);
     pj[j] = pp;
     qj[j] = q;
     Gj[j] = a.probe_G[pp];
@@ -655,15 +655,15 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       wnext = word_at(wb + MASK_BATCH + lane);
       const int wi = wb + lane;
       uint32_t field = ~wcur & present;
+      if (__ballot(field != 0u) == 0ull) continue;
       const int mine_n = __popc(field);
-      int incl = mine_n;  // inclusive scan over the lanes
+      int incl = mine_n;  // inclusive scan over the lanes that carry words
 #pragma unroll
-      for (int d = 1; d < 64; d <<= 1) {
+      for (int d = 1; d < MASK_BATCH; d <<= 1) {
         const int o = __shfl_up(incl, d, 64);
         if (lane >= d) incl += o;
       }
-      const int total = __shfl(incl, 63, 64);
-      if (total == 0) continue;
+      const int total = __builtin_amdgcn_readlane(incl, MASK_BATCH - 1);
       if (list_cnt + total > LCAP) flush();
       int pos = list_cnt + incl - mine_n;
       const uint32_t pos0 = (uint32_t)((ts - t0 + (wi >> 4)) * TILE + (wi & 15));
@@ -887,7 +887,7 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   v4i qa[KC];
   {
     const int pp = a.pair_ids[pbeg + min(lj, np - 1)];
-    const int64_t q = pp / a.nprobe;
+    const int64_t q = pair_query(a, pp);
     const int8_t* src = a.qhat8 + q * a.Dp + 16 * g;
 #pragma unroll
     for (int kc = 0; kc < KC; ++kc) {
@@ -910,7 +910,7 @@ __global__ __launch_bounds__(64 * mfma_waves(W)) void scan_mfma_kernel(ScanArgs 
   for (int r = 0; r < 4; ++r) {
     const int qi = 4 * g + r;
     const int pp = a.pair_ids[pbeg + min(qi, np - 1)];
-    const int64_t q = pp / a.nprobe;
+    const int64_t q = pair_query(a, pp);
     const float dl = a.delta[q];
     al[r] = dl;
     be[r] = 0.5f * dl * (float)a.sum_qhat[q];

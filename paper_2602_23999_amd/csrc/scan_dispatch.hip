@@ -241,7 +241,7 @@ int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
   a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
-  a.nprobe = nprobe; a.k = k; a.tau_out = tau;
+  set_nprobe(a, nprobe); a.k = k; a.tau_out = tau;
   const int W = ix->W, F = field_bits(ix->total_bits);
   const int impl = effective_impl(ix);
   if (!(seed_part0(a, W, F, impl, nq, st) || seed_part1(a, W, F, impl, nq, st) || seed_part2(a, W, F, impl, nq, st)))
@@ -297,7 +297,7 @@ int launch_small_select_seed(const rabitq_index* ix, const rabitq_query_repr& re
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
   a.probe_ids = probe_ids; a.probe_G = probe_G; a.probe_E = probe_E;
-  a.nprobe = nprobe; a.k = k; a.tau_out = tau;
+  set_nprobe(a, nprobe); a.k = k; a.tau_out = tau;
   SmallSelectArgs b{};
   b.scores = scores; b.sq_norm = repr.sq_norm; b.centroid_sq = ix->centroid_sq; b.metric = ix->metric;
   // (with one probed list and 1-bit codes the scan's own top-k selects what a seeded threshold would: no seeding)
@@ -322,7 +322,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   const int impl = effective_impl(ix);
   const int qw = impl == 1 ? QM : QW;
   a.probe_G = probe_G; a.probe_E = probe_E; a.pair_off = pair_off; a.pair_ids = pair_ids; a.tau = tau;
-  a.nprobe = nprobe; a.k = k;
+  set_nprobe(a, nprobe); a.k = k;
   a.cand_stride = next_pow2_host(k + TILE);
   // LDS pool entries per pair: the popcount kernel may append a whole tile at once
   // (the matrix-core kernel's four wavefronts may together append 4 x 16 refined keys per round, or four whole
