@@ -87,12 +87,12 @@ def scan_algorithmic_bytes(gi, Qd, nprobe, cluster_sizes, dim):
 def kernel_source_hash():
     """Identifies the scan kernel a stored counter reading belongs to."""
     h = hashlib.sha256()
-    for fn in ("scan.hip", "rq_device.h", "rq_scan_args.h", "scan_dispatch.hip"):
+    for fn in ("scan.hip", "estimate_mfma.hip", "rq_device.h", "rq_scan_args.h", "scan_dispatch.hip"):
         h.update(open(os.path.join(ROOT, "paper_2602_23999_amd", "csrc", fn), "rb").read())
     return h.hexdigest()[:16]
 
 
-def stored_traffic(workload, nprobe):
+def stored_traffic(workload, nprobe, split=False):
     """Fabric traffic per scan launch (bytes) from the rocprofv3 --pmc summary under profiles/, if that summary was
     taken with the kernel sources as they are now; else None."""
     path = os.path.join(ROOT, "profiles", f"scan_kernel_{workload}_traffic.txt")
@@ -103,7 +103,7 @@ def stored_traffic(workload, nprobe):
         f = line.split()
         if len(f) >= 2 and f[0] == "kernel_source_hash":
             src = f[1]
-        if len(f) >= 2 and f[0] == f"nprobe_{nprobe}":
+        if len(f) >= 2 and f[0] == f"nprobe_{nprobe}" + ("_split" if split else ""):
             val = int(f[1])
     if val is None:
         return None, "no counter reading for this nprobe"
@@ -223,8 +223,8 @@ def scan_roofline(gi, Qd, w, pt, cluster_sizes, args):
     alu_ops = qv * (8 * (w.dim // 32) + 6)
     alu_achieved = alu_ops / (scan_ms * 1e-3) / 1e12
     split = pt.get("scan_split", False)
-    traffic, traffic_note = (stored_traffic(w.name, pt["nprobe"])
-                             if impl == 0 and not split and pt["total_bits"] == w.total_bits
+    traffic, traffic_note = (stored_traffic(w.name, pt["nprobe"], split)
+                             if impl == 0 and pt["total_bits"] == w.total_bits
                              else (None, "no counter summary for this variant"))
     roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TOPS, "unit": "TOP/s (integer lane-operations)",
                 "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic, "traffic_source": traffic_note,
