@@ -228,7 +228,7 @@ def scan_roofline(gi, Qd, w, pt, cluster_sizes, args):
                              else (None, "no counter summary for this variant"))
     roofline = {"bound": "alu", "achieved": alu_achieved, "peak": ALU_PEAK_TOPS, "unit": "TOP/s (integer lane-operations)",
                 "frac": alu_achieved / ALU_PEAK_TOPS, "traffic": traffic, "traffic_source": traffic_note,
-                "kernel": {0: "scan_kernel", 1: "scan_mfma_kernel", 2: "scan_kernel (lookup tables)", 4: "scan_wave_mfma_kernel"}[impl],
+                "kernel": {0: "scan_kernel", 1: "scan_mfma_kernel", 2: "scan_kernel (lookup tables)", 4: "scan_kernel"}[impl],
                 "algorithmic_ops_per_launch": alu_ops, "kernel_ms": scan_ms, "query_vector_evaluations": qv,
                 "hbm_view": {"algorithmic_bytes_per_launch": alg_bytes, "achieved_gbs": achieved, "peak_gbs": HBM_PEAK_GBS,
                              "frac": achieved / HBM_PEAK_GBS,
