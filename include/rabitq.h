@@ -200,12 +200,12 @@ int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq
  *             qhat with v_mfma_i32_16x16x64_i8).  Results of 0 and 1 are identical; only speed differs.
  *             4: split search: the estimates and the filter run on the matrix cores as a kernel of their own (one
  *             wavefront per 16 pairs of a cluster, next tile requested ahead, no LDS) and leave one bit per (pair,
- *             vector); the kernel of 0 then only refines the survivors.  Taken for B > 1, D <= 128 and at least
+ *             vector); the kernel of 0 then only refines the survivors.  Taken for B > 1 and at least
  *             "split_min_pairs" (an option; default 32) pairs per list on average, otherwise as 0.  Same results.  The
  *             survivor bits and the work-item descriptors live in buffers the handle grows on demand (rabitq_search
  *             and rabitq_scan may allocate when a larger batch arrives; rabitq_search_noalloc never does and splits
  *             only if the buffers are already large enough).
- *             3 (default): the faster in measurements: 1 for D >= 960; 4 where it is taken (see above); else 0.
+ *             3 (default): the faster in measurements: 1 for D >= 960; below that 4 where it is taken (see above), else 0.
  *             2: the lookup-table scheme of Section 3.4.1(1) instead of the quantised query:
  *             <x_b, q'> is the fp32 sum, in ascending block order, of one binary16 table entry per
  *             4 dimensions (tables in LDS, 4 queries per wavefront).  Used by the threshold

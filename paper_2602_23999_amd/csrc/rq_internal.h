@@ -168,13 +168,14 @@ constexpr int SMALL_BATCH_MAX = 64;
 constexpr int TICKET_WORDS = 4;  // words behind the two offset arrays of rabitq_index::tile_off (zero between launches)
 inline int64_t tile_off_words(int nlist) { return 4 * (int64_t)(nlist + 1) + TICKET_WORDS; }
 // Split search (scan_impl 4): the first stage runs on the matrix cores for groups of 16 pairs and hands one survivor
-// bit per (pair, vector) to the popcount kernel.  Worth it, and built, for a long code (B > 1), D <= 128 and at
-// least split_min_pairs pairs per list on average.  split_mask_blocks bounds the blocks of survivor bits a search of
+// bit per (pair, vector) to the popcount kernel.  Built for every code with a long part (B > 1); taken on request (4) and,
+// by default (3), below D = 960 (there the four-wavefront matrix-core kernel is faster) from split_min_pairs pairs per
+// list on average.  split_mask_blocks bounds the blocks of survivor bits a search of
 // (nq, nprobe) can need: sum_c ceil(cnt_c / 16) tiles_c <= (nq * tiles of the nprobe largest lists) / 16 + all tiles,
 // because every query probes nprobe distinct lists.
-inline bool split_built(const rabitq_index* ix) { return ix->W <= 4 && ix->total_bits > 1; }
+inline bool split_built(const rabitq_index* ix) { return ix->total_bits > 1; }
 inline bool split_wanted(const rabitq_index* ix, int64_t nq, int nprobe) {
-  return (ix->scan_impl == 4 || ix->scan_impl == 3) && split_built(ix) &&
+  return (ix->scan_impl == 4 || (ix->scan_impl == 3 && ix->W < 30)) && split_built(ix) &&
          nq * nprobe >= (int64_t)ix->split_min_pairs * ix->nlist;
 }
 int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe);

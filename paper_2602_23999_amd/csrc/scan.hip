@@ -1152,13 +1152,13 @@ static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipS
 
 template <int W, int F, int M>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
-  const bool masked = M == 0 && F > 0 && W <= 4 && a.surv_mask != nullptr;  // second half of the split search
+  const bool masked = M == 0 && F > 0 && a.surv_mask != nullptr;  // second half of the split search
   const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
                       (F > 0 ? (masked ? LIST_CAP_MASKED : LIST_CAP) * sizeof(uint32_t) +
                                    (size_t)QW * (a.D + 4 * RefineShape<W * (F > 0 ? F : 8)>::G) * sizeof(float) : 0) +
                       (M == 1 ? (size_t)QW * W * 256 : 0);
   if (masked)  // (estimate_mfma_kernel ran)
-    hipLaunchKernelGGL((scan_kernel<W, F, false, M, 0, (M == 0 && F > 0 && W <= 4)>), dim3(grid), dim3(64), smem, st, a);
+    hipLaunchKernelGGL((scan_kernel<W, F, false, M, 0, (M == 0 && F > 0)>), dim3(grid), dim3(64), smem, st, a);
   else if (dbg)
     hipLaunchKernelGGL((scan_kernel<W, F, true, M>), dim3(grid), dim3(64), smem, st, a);
   else if (M == 0 && a.streaming)
