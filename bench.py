@@ -305,6 +305,10 @@ def stream_scan(args, n, bits, steps, warmup):
     out_ids = torch.empty((nq, k), dtype=torch.int64, device="cuda")
     out_d = torch.empty((nq, k), dtype=torch.float32, device="cuda")
     gi.set_option("scan_impl", 0)  # D = 128: the popcount kernel (the library's own choice at this width)
+    if args.stream_seg_tiles > 0:
+        gi.set_option("scan_segment_tiles", args.stream_seg_tiles)
+    if not args.stream_longest_first:
+        gi.set_option("longest_first", 0)
     for _ in range(warmup):
         gi.search(Qd, k, 1, out_ids, out_d)
     gi.set_option("profile", steps)
@@ -418,6 +422,10 @@ def main():
     ap.add_argument("--stream-n", type=int, default=0,
                     help="vectors of the streaming index (default 32 Mi inside the default run, 64 Mi with --stream-scan)")
     ap.add_argument("--stream-bits", type=int, default=1)
+    ap.add_argument("--stream-seg-tiles", type=int, default=0,
+                    help="segment length (tiles) of the streaming leg's work items; 0 = the library's choice")
+    ap.add_argument("--stream-longest-first", type=int, default=1,
+                    help="0: the streaming leg's work items in cluster order instead of longest list first")
     ap.add_argument("--stream-list", type=int, default=1024, help="mean inverted-list length of the streaming index")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -501,7 +509,8 @@ def main():
         "metric": "queries/sec at recall@10~0.95 (1 GPU); code-scan HBM GB/s vs peak",
         "value": pt["qps"], "unit": "queries/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": pt["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": ("u32 popcount + f32", "i8 matrix cores + f32", "f16 tables + f32")[impl], "data": "synthetic",
+        "dtype": ("i8 matrix cores + f32" if pt.get("scan_split") or impl == 1 else
+                  "f16 tables + f32" if impl == 2 else "u32 popcount + f32"), "data": "synthetic",
         "config": config, "roofline": roofline,
     }
     if cpu is not None:

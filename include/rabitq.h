@@ -194,6 +194,10 @@ int rabitq_search_noalloc(rabitq_index_t index, const float* queries, int64_t nq
  *             0: always the general kernels.
  *   "scan_segment_tiles" n: a list longer than n tiles of 64 vectors is scanned by several work items of about n tiles
  *             each (at most cand_capacity(k) / k of them); 0 (default): chosen from the batch size, 2..32.
+ *   "longest_first" 1 (default): when a batch has at most four pairs per list on average, so that every probed list
+ *             is read from memory about once (Section 3.4.2's coalesced cluster reads are then what bounds the scan),
+ *             the popcount kernel takes one pair per work item and is handed the lists longest first, so that its
+ *             launch ends everywhere at about the same time.  0: in cluster order.  Same results.
  *   "scan_impl" 0: bit-plane AND + popcount inner products (Section 3.4.1(2)), 4 queries per
  *             wavefront; 1: the same integer inner products on the matrix cores (the sign
  *             bits of a tile are expanded to int8 once and contracted against 16 queries'
@@ -216,7 +220,8 @@ int rabitq_set_option(rabitq_index_t index, const char* name, int64_t value);
 
 /* Host-visible sizes of an uploaded index: name in {"n","n_tiles","n_slots","dim","nlist",
  * "total_bits","long_field_bits","metric"}, or "last_scan_split": 1 if the scan of the latest rabitq_search /
- * rabitq_scan on the handle was split ("scan_impl" 4), else 0.  Returns the value, or a negative status. */
+ * rabitq_scan on the handle was split ("scan_impl" 4), else 0; "last_scan_stream": 1 if it was the popcount kernel's
+ * one-pair-per-work-item form (see "longest_first"), else 0.  Returns the value, or a negative status. */
 int64_t rabitq_index_info(rabitq_index_t index, const char* name);
 
 /* Per-stage timing.  The option "profile" = n (0..4096) makes the next n searches record

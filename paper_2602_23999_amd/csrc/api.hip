@@ -64,7 +64,7 @@ static void free_workspace(Workspace& w) {
 static void free_index(rabitq_index* ix) {
   if (!ix) return;
   dev_free(ix->rotation); dev_free(ix->mean_rot); dev_free(ix->centroids_t); dev_free(ix->centroid_sq); dev_free(ix->tile_off); dev_free(ix->surv_mask); dev_free(ix->item_desc);
-  dev_free(ix->cluster_size); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
+  dev_free(ix->cluster_size); dev_free(ix->cluster_order); dev_free(ix->short_codes); dev_free(ix->short_factors); dev_free(ix->long_codes);
   dev_free(ix->long_factors); dev_free(ix->ids);
   free_workspace(ix->ws);
   for (auto& set : ix->prof_sets) {
@@ -197,6 +197,16 @@ static int init_streams(rabitq_index* ix) {
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_fork, hipEventDisableTiming));
   RQ_HIP(hipEventCreateWithFlags(&ix->ev_join, hipEventDisableTiming));
   ix->seg_sorted.reserve(ix->host_tiles.size());  // so that a search never grows a host vector either
+  {
+    // clusters by descending length: the order in which a scan that reads every list once hands them out (launch_scan)
+    std::vector<int32_t> order(ix->host_tiles.size());
+    for (size_t c = 0; c < order.size(); ++c) order[c] = (int32_t)c;
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t x, int32_t y) { return ix->host_tiles[x] > ix->host_tiles[y]; });
+    if (int rc = dev_alloc(&ix->cluster_order, (int64_t)order.size())) return rc;
+    if (!order.empty())
+      RQ_HIP(hipMemcpy(ix->cluster_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
   unsigned char* sp = nullptr;  // the allocation-free search's workspace on this device
   return noalloc_scratch(ix->device, &sp);
 }
@@ -403,6 +413,7 @@ int rabitq_set_option(rabitq_index_t ix, const char* name, int64_t value) {
   if (!std::strcmp(name, "overlap") && (value == 0 || value == 1)) { ix->overlap = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "max_batch") && value >= 0 && value <= 0x7fffffff) { ix->max_batch = value; return RABITQ_OK; }
   if (!std::strcmp(name, "small_batch") && (value == 0 || value == 1)) { ix->small_batch = (int)value; return RABITQ_OK; }
+  if (!std::strcmp(name, "longest_first") && (value == 0 || value == 1)) { ix->longest_first = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "scan_segment_tiles") && value >= 0 && value <= 4096) { ix->seg_tiles = (int)value; return RABITQ_OK; }
   if (!std::strcmp(name, "profile_stages") && value >= 1 && value <= 0x3ff) {
     ix->prof_mask = (unsigned)value;
@@ -441,6 +452,7 @@ int64_t rabitq_index_info(rabitq_index_t ix, const char* name) {
   if (!std::strcmp(name, "long_field_bits")) return ix->F;
   if (!std::strcmp(name, "metric")) return ix->metric;
   if (!std::strcmp(name, "last_scan_split")) return ix->last_scan_split;
+  if (!std::strcmp(name, "last_scan_stream")) return ix->last_scan_stream;
   set_error("index_info: unknown name");
   return RABITQ_EINVAL;
 }
@@ -576,11 +588,13 @@ int rabitq_scan(rabitq_index_t ix, const rabitq_query_repr* repr, const float* p
   if (nq * nprobe > 0x7fffffff) { set_error("scan: nq*nprobe exceeds 2^31-1"); return RABITQ_EINVAL; }
   if (split_wanted(ix, nq, nprobe))
     if ((rc = ensure_split_buffers(ix, nq, nprobe, k))) return rc;
+  if ((rc = ensure_stream_buffers(ix, nq, nprobe, k))) return rc;
   ScanStreams ss;
   ss.main = ss.setup = (hipStream_t)stream;
   rc = launch_scan(ix, *repr, probe_G, probe_E, pair_off, pair_ids, tau, nq, k, nprobe, cand_keys, cand_cnt, dbg_ip,
                    dbg_off, ss);
   ix->last_scan_split = ss.split ? 1 : 0;
+  ix->last_scan_stream = ss.streamed ? 1 : 0;
   return rc;
 }
 
@@ -681,6 +695,7 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
   ss.main = st; ss.setup = lst; ss.join = ix->ev_join;
   ss.counters_clear = early_clear;
   ss.setup_done = small;
+  ss.desc_done = small_fused;
   if (ev && ((ix->prof_mask >> 6) & 1u)) { ss.setup_b = ev->b[6]; ss.setup_e = ev->e[6]; ev->rec |= 1u << 6; }
   if (ev && ((ix->prof_mask >> 7) & 1u)) { ss.scan_b = ev->b[7]; ss.scan_e = ev->e[7]; ev->rec |= 1u << 7; }
   if (ev && ((ix->prof_mask >> 9) & 1u)) { ss.est_b = ev->b[9]; ss.est_e = ev->e[9]; }
@@ -689,6 +704,7 @@ static int search_batch_body(rabitq_index* ix, Workspace& w, const float* querie
     return rc;
   if (ss.est_b && ss.split) ev->rec |= 1u << 9;
   ix->last_scan_split = ss.split ? 1 : 0;
+  ix->last_scan_stream = ss.streamed ? 1 : 0;
   RQ_STAGE(8, st, launch_merge(w.cand_keys, w.cand_cnt, nq, k, nprobe, ix->metric, out_ids, out_dists, st));
 #undef RQ_STAGE
   return RABITQ_OK;
@@ -724,6 +740,7 @@ int rabitq_search(rabitq_index_t ix, const float* queries, int64_t nq, int32_t k
   if ((rc = ensure_workspace(ix, step, nprobe, k))) return rc;
   if (split_wanted(ix, step, nprobe))
     if ((rc = ensure_split_buffers(ix, step, nprobe, k))) return rc;
+  if ((rc = ensure_stream_buffers(ix, step, nprobe, k))) return rc;
   for (int64_t s0 = 0; s0 < nq; s0 += step) {
     const int64_t m = std::min(step, nq - s0);
     if ((rc = search_batch(ix, ix->ws, queries + s0 * ix->dim, m, k, nprobe, out_ids + s0 * k, out_dists + s0 * k,

@@ -56,6 +56,7 @@ struct rabitq_index {
   int32_t* tile_off = nullptr;      // [nlist+1] tile offsets | [nlist+1] scan work-item offsets | [TICKET_WORDS] zeroed ticket
                                     // | [nlist+1] work items of 16 pairs | [nlist+1] first survivor block (split search)
   int32_t* cluster_size = nullptr;  // [nlist]
+  int32_t* cluster_order = nullptr; // [nlist] clusters by descending tile count, equal counts by ascending id
   uint32_t* short_codes = nullptr;
   float* short_factors = nullptr;
   uint32_t* long_codes = nullptr;
@@ -72,6 +73,7 @@ struct rabitq_index {
                       // 4 estimates on the matrix cores + refinement by the popcount kernel (split search)
   // survivor bits of the split search: blocks of 16 words; grown on demand by ensure_split_buffers, kept by the handle
   int last_scan_split = 0;   // the scan of the latest rabitq_search / rabitq_scan was split (rabitq_index_info)
+  int last_scan_stream = 0;  // ... was the prefetching variant of the popcount kernel (one pair per work item)
   int split_min_pairs = 32;  // pairs per list, on average, from which scan_impl 3 / 4 split the search
   uint64_t* surv_mask = nullptr;
   int64_t surv_mask_blocks = 0;
@@ -81,6 +83,7 @@ struct rabitq_index {
   int overlap = 1;  // list building and scan set-up run beside the seeding on `side`
   int64_t max_batch = 0;  // queries per pass of rabitq_search; 0 = from the workspace budget
   int small_batch = 1;    // batches of at most SMALL_BATCH_MAX queries take the fused low-launch-count kernels
+  int longest_first = 1;  // a scan that reads every list about once hands out its work items longest list first
   int seg_tiles = 0;      // tiles per scan work item of a long list; 0 = chosen from the batch (see launch_scan)
   // second stream of a search (default priority) and the events that fork it from and join it to the caller's
   hipStream_t side = nullptr;
@@ -155,11 +158,13 @@ struct ScanStreams {
   hipEvent_t setup_b = nullptr, setup_e = nullptr, scan_b = nullptr, scan_e = nullptr;
   hipEvent_t est_b = nullptr, est_e = nullptr;  // around the estimate kernel of a split search
   mutable bool split = false;                  // out: the search was split
+  mutable bool streamed = false;               // out: the prefetching variant of the popcount kernel ran
   bool counters_clear = false;  // cand_cnt was already zeroed by launch_clear_counters
+  bool desc_done = false;       // ... and so were the descriptors of the prefetching scan's work items (launch_small_select_seed)
   bool setup_done = false;      // work-item offsets and counters were already prepared (launch_small_batch_lists)
 };
 // How a scan launch cuts its work: pairs per work item, tiles per segment of a long list, segments per list at most.
-struct ScanPlan { int qw, tseg, segmax; };
+struct ScanPlan { int qw, tseg, segmax; bool streaming; };
 ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k);
 // Batches of at most SMALL_BATCH_MAX queries: pair lists, the scan's work-item offsets and the cleared candidate
 // counters from ONE single-workgroup kernel (instead of the seven launches of launch_build_lists + the scan set-up).
@@ -181,6 +186,9 @@ inline bool split_wanted(const rabitq_index* ix, int64_t nq, int nprobe) {
 int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe);
 // makes the handle's survivor-bit buffer large enough for (nq, nprobe); may allocate (then it synchronises the device)
 int ensure_split_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k);
+// makes the handle's descriptor memory large enough for the prefetching scan of (nq, nprobe, k), when that is the shape;
+// may allocate (then it synchronises the device)
+int ensure_stream_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k);
 // The same for nprobe <= 64, k <= 64 and a bitwise scan, preceded in the same kernel by the selection of the probes
 // from the coarse scores and the seeding of the thresholds (one workgroup per query; the last one to finish builds the
 // lists): everything between the coarse scores and the scan in one launch.

@@ -21,6 +21,21 @@ struct ItemDesc {
   int32_t pad;
 };
 
+// The same for the prefetching variant of the popcount kernel (one pair per work item, lists read from memory about
+// once): the item's tiles and the scalars of its pair, 64 bytes that one scalar load brings in.
+struct StreamDesc {
+  int32_t pp, q;    // the pair and its query
+  int32_t t0;       // first tile of the cluster
+  int32_t ts, te;   // tiles of the item's segment
+  int32_t nseg;     // segments the cluster is scanned in
+  int32_t ppos;     // position of the pair in the pair list
+  int32_t S;        // sum of the query's 4-bit digits
+  float G, E;       // coarse score of the pair and ||q' - c'||
+  float delta;      // step of the query's 4-bit grid
+  float sumq;       // sum of the rotated query
+  int32_t pad[4];
+};
+
 struct ScanArgs {
   // index
   const uint32_t* short_codes;
@@ -53,12 +68,16 @@ struct ScanArgs {
   const int32_t* pair_off;
   const int32_t* pair_ids;
   const int32_t* item_off;
+  // nullptr: item_off[c] is the first work item of cluster c.  Otherwise item_off[r] is the first work item of cluster
+  // order[r], the clusters being handed out longest first (a launch whose lists are each read about once)
+  const int32_t* order;
   // split search (estimates by estimate_mfma_kernel, refinement by the popcount kernel): work items of 16 pairs,
   // first block of survivor bits of every cluster, the bits themselves (nullptr: not split)
   const int32_t* item_off16;
   const uint32_t* mask_off;
   uint64_t* surv_mask;
   ItemDesc* item_desc;  // [work items of 4 pairs]
+  const StreamDesc* stream_desc;  // [work items of one pair] (prefetching variant; the same memory as item_desc)
   int nprobe, k, pool, cand_stride;
   // pair / nprobe without a division: (pair * nprobe_mul) >> nprobe_shift is exact for pair < 2^31 when nprobe_mul =
   // ceil(2^(31 + L) / nprobe), nprobe_shift = 31 + L and 2^L >= nprobe (set_nprobe)

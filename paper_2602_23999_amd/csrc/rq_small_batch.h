@@ -17,6 +17,10 @@ struct SmallListArgs {
   int32_t* pair_ids;         // [nq * nprobe] out
   int32_t* item_off;         // [nlist + 1] out
   int32_t* cand_cnt;         // [nq * nprobe] out: zeros
+  // work items of one pair (qw == 1): their descriptors for the prefetching scan, nullptr = not written here
+  StreamDesc* desc;
+  const float *probe_G, *probe_E, *delta, *sum_q;
+  const int32_t* sum_qhat;
 };
 
 // A query probes a list at most once, so the queries of a list are one 64-bit mask; a pair's place in its list is
@@ -76,6 +80,26 @@ __device__ inline void small_lists_body(const SmallListArgs& b, uint32_t* s_pair
     const uint32_t lo = mask_at(2 * c), hi = mask_at(2 * c + 1);
     const int below = q < 32 ? __popc(lo & ((1u << q) - 1u)) : __popc(lo) + __popc(hi & ((1u << (q - 32)) - 1u));
     b.pair_ids[b.pair_off[c] + below] = p;
+    if (b.desc) {
+      const int t0 = b.tile_off[c], tiles = b.tile_off[c + 1] - t0;
+      const int nseg = seg_count(tiles, b.tseg, b.segmax), seglen = (tiles + nseg - 1) / nseg;
+      StreamDesc d{};
+      d.pp = p;
+      d.q = q;
+      d.t0 = t0;
+      d.nseg = nseg;
+      d.ppos = b.pair_off[c] + below;
+      d.S = b.sum_qhat[q];
+      d.G = b.probe_G[p];
+      d.E = b.probe_E[p];
+      d.delta = b.delta[q];
+      d.sumq = b.sum_q[q];
+      for (int sidx = 0; sidx < nseg; ++sidx) {
+        d.ts = t0 + sidx * seglen;
+        d.te = min(t0 + tiles, d.ts + seglen);
+        b.desc[b.item_off[c] + below * nseg + sidx] = d;
+      }
+    }
   }
 }
 

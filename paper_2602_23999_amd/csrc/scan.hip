@@ -394,6 +394,12 @@ constexpr int MASK_BATCH = 32;
 constexpr int LIST_CAP_MASKED = 256 + 16 * MASK_BATCH;
 constexpr int REFINE_AHEAD_MASKED = 2;  // refinement rounds whose loads are in flight (1 in the fused kernel)
 
+#ifdef RQ_TIMELINE  // development: when each work item of the popcount kernel started, began to scan and ended
+__device__ unsigned long long g_timeline[1 << 16][4];
+#define RQ_TL(i, slot, v) do { if (threadIdx.x == 0 && (i) < (1 << 16)) g_timeline[i][slot] = (unsigned long long)(v); } while (0)
+#else
+#define RQ_TL(i, slot, v) do { } while (0)
+#endif
 #ifdef RQ_STATS  // development counters: survivors, refine rounds, compactions, flushes
 __device__ unsigned long long g_scan_stats[8];
 #define RQ_STAT(i, v) do { if (threadIdx.x == 0) atomicAdd(&g_scan_stats[i], (unsigned long long)(v)); } while (0)
@@ -413,35 +419,34 @@ __device__ inline int pool_compact(uint64_t* pool, int pool_n, int cnt, int k) {
 // MASKED: the first stage has been done by estimate_mfma_kernel; the survivors of a (pair, tile) are read as one bit
 // per vector and only refinement, pools and output happen here.
 template <int W, int F, bool DBG, int M, int PFD = 0, bool MASKED = false>  // M = 1: lookup-table inner product (tables of the QW queries in LDS)
-__global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
+__device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
+  // pairs per work item: QW, or one where every list is read about once (each pair then streams its list by itself,
+  // with a quarter of the scalar state, which is what lets eight wavefronts share a SIMD)
+  constexpr int QN = PFD > 0 ? 1 : QW;
   constexpr int FF = (F > 0 ? F : 8), LW = W * FF;
   constexpr int G = RefineShape<LW>::G, NS = RefineShape<LW>::NS;
   extern __shared__ unsigned char smem_raw[];
-  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);             // [QW][pool]
-  uint64_t* pool_kth = pools + (size_t)QW * a.pool;                    // [QW] k-th best key so far
-  float* qs = reinterpret_cast<float*>(pool_kth + QW);                 // [QW][2]: G, cB*sum(q')
-  int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QW);                 // [QW]
+  uint64_t* pools = reinterpret_cast<uint64_t*>(smem_raw);             // [QN][pool]
+  uint64_t* pool_kth = pools + (size_t)QN * a.pool;                    // [QN] k-th best key so far
+  float* qs = reinterpret_cast<float*>(pool_kth + QN);                 // [QN][2]: G, cB*sum(q')
+  int* pool_cnt = reinterpret_cast<int*>(qs + 2 * QN);                 // [QN]
   constexpr int LCAP = MASKED ? LIST_CAP_MASKED : LIST_CAP, AHEAD = MASKED ? REFINE_AHEAD_MASKED : 1;
-  uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QW);         // [LCAP] (F > 0)
+  uint32_t* list = reinterpret_cast<uint32_t*>(pool_cnt + QN);         // [LCAP] (F > 0)
   // The queries in LDS, padded: a lane of the refinement reads a chunk of QCH = D / G consecutive floats, 16 bytes at
   // a time, and the chunks of one row (and the rows) would all start in the same banks; QPAD floats after every
   // chunk spread them over the banks.  Element e of row j sits at j * QROW + e + QPAD * (e / QCH).
   constexpr int QCH = RefineShape<LW>::WPL * (32 / FF), QPAD = 4, QROW = 32 * W + QPAD * G;
-  float* qf = reinterpret_cast<float*>(list + (F > 0 ? LCAP : 0));     // [QW][QROW] (F > 0)
-  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + (F > 0 ? QW * QROW : 0));  // [QW][8W][16] (M = 1)
+  float* qf = reinterpret_cast<float*>(list + (F > 0 ? LCAP : 0));     // [QN][QROW] (F > 0)
+  _Float16* lut_s = reinterpret_cast<_Float16*>(qf + (F > 0 ? QN * QROW : 0));  // [QN][8W][16] (M = 1)
   const int lane = threadIdx.x;
 
-  // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
-  // contiguous range of work items; items of one cluster then share one L2.
-  // (the grid is an upper bound of the number of work items; the ranges are cut from the true count)
-  const int n_items = a.item_off[a.nlist];
-  const int per = (n_items + 7) >> 3;
-  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-  if ((int)(blockIdx.x >> 3) >= per || item >= n_items) return;
+  RQ_TL(item, 0, wall_clock64());
   int t0, nseg, ts, te, pbeg, np;
   // MASKED: blocks of survivor bits of this item's group of 16 pairs (its 4 pairs are lane group `mg` of every word)
   int mg = 0;
   const uint16_t* mblk = nullptr;
+  typedef const StreamDesc __attribute__((address_space(4)))* const_sdesc_ptr;
+  const_sdesc_ptr sdp = (const_sdesc_ptr)(a.stream_desc + (PFD > 0 ? item : 0));  // (read only where PFD > 0)
   if (MASKED) {
     // (everything about the item was laid down by item_desc_kernel: one load instead of a chain of dependent ones,
     // which is what a kernel that only refines would spend its time waiting for)
@@ -455,6 +460,15 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     te = d->te;
     nseg = d->nseg;
     mblk = reinterpret_cast<const uint16_t*>(a.surv_mask + (int64_t)d->mblock * 16);
+  } else if (PFD > 0) {
+    // (one load, as above: this variant waits for memory, and a chain of look-ups before the first tile is requested
+    // is time in which the wavefront has nothing in flight)
+    t0 = sdp->t0;
+    ts = sdp->ts;
+    te = sdp->te;
+    nseg = sdp->nseg;
+    pbeg = sdp->ppos;
+    np = 1;
   } else {
     // cluster of this item: largest c with item_off[c] <= item
     const int c = wave_upper_cluster(a.item_off, a.nlist, item, lane);
@@ -467,11 +481,11 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     const int seglen = (tc1 - t0 + nseg - 1) / nseg;
     ts = t0 + sidx * seglen;
     te = min(tc1, ts + seglen);
-    pbeg = a.pair_off[c] + grp * QW;
-    np = __builtin_amdgcn_readfirstlane(min(QW, a.pair_off[c + 1] - pbeg));  // the same in all lanes
+    pbeg = a.pair_off[c] + grp * QN;
+    np = __builtin_amdgcn_readfirstlane(min(QN, a.pair_off[c + 1] - pbeg));  // the same in all lanes
   }
 
-  constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead
+  constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead (three and four: no faster)
   uint32_t pw[PD > 0 ? PD : 1][W];
   float pf[PD > 0 ? PD : 1][3];
   auto fetch = [&](uint32_t (&w_)[W], float (&f_)[3], int tile) {
@@ -486,40 +500,43 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     for (int d = 0; d < PD; ++d) fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(ts + d, te - 1));
   }
 
-  int pj[QW], Sj[QW], cnt[QW];
-  float Gj[QW], Ej[QW], dlj[QW], bej[QW], tauj[QW], hsqj[QW];
-  int64_t qj[QW];
+  int pj[QN], Sj[QN], cnt[QN];
+  float Gj[QN], Ej[QN], dlj[QN], bej[QN], tauj[QN], hsqj[QN];
+  int64_t qj[QN];
 #pragma unroll
-  for (int j = 0; j < QW; ++j) {
-    const int pp = a.pair_ids[pbeg + min(j, np - 1)];
-    const int64_t q = pair_query(a, pp);
+  for (int j = 0; j < QN; ++j) {
+    // (the prefetching variant has its pair's scalars in the descriptor; only the threshold, which the seeding writes
+    // while the descriptors are being made, is fetched here)
+    const int pp = PFD > 0 ? sdp->pp : a.pair_ids[pbeg + min(j, np - 1)];
+    const int64_t q = PFD > 0 ? (int64_t)sdp->q : (int64_t)pair_query(a, pp);
     pj[j] = pp;
     qj[j] = q;
-    Gj[j] = a.probe_G[pp];
-    dlj[j] = a.delta[q];
+    Gj[j] = PFD > 0 ? sdp->G : a.probe_G[pp];
+    dlj[j] = PFD > 0 ? sdp->delta : a.delta[q];
     {  // radius of the bound: ||q'-c'|| widened by the rounding error of the 4-bit query
-      const float e = a.probe_E[pp];
+      const float e = PFD > 0 ? sdp->E : a.probe_E[pp];
       Ej[j] = sqrtf(fmaf(a.qerr, dlj[j] * dlj[j], e * e));
     }
-    Sj[j] = a.sum_qhat[q];
+    Sj[j] = PFD > 0 ? sdp->S : a.sum_qhat[q];
+    const float sumq = PFD > 0 ? sdp->sumq : a.sum_q[q];
     bej[j] = 0.5f * dlj[j] * (float)Sj[j];
-    hsqj[j] = 0.5f * a.sum_q[q];
+    hsqj[j] = 0.5f * sumq;
     tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
     cnt[j] = 0;
     if (lane == 0) {
       pool_kth[j] = KEY_NONE;
       pool_cnt[j] = 0;
       qs[2 * j] = Gj[j];
-      qs[2 * j + 1] = a.cB * a.sum_q[q];
+      qs[2 * j + 1] = a.cB * sumq;
     }
   }
   if (M == 1) {
-    // the lookup tables of the QW queries (W * 64 dwords each) go to LDS, all words of a batch requested before the
+    // the lookup tables of the QN queries (W * 64 dwords each) go to LDS, all words of a batch requested before the
     // first one is stored
-    constexpr int JB = (W * QW <= 16) ? QW : 1;
+    constexpr int JB = (W * QN <= 16) ? QN : 1;
     uint32_t* d32 = reinterpret_cast<uint32_t*>(lut_s);
 #pragma unroll
-    for (int j0 = 0; j0 < QW; j0 += JB) {
+    for (int j0 = 0; j0 < QN; j0 += JB) {
       uint32_t tv[JB][W];
 #pragma unroll
       for (int jj = 0; jj < JB; ++jj) {
@@ -535,10 +552,10 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   }
   if (F > 0) {
     // the rotated queries go to LDS for the refinement: every word is requested before the first one is stored
-    // (copied one after the other, each word would wait for its own round trip, 2 QW of them for D = 128)
-    constexpr int DD = 32 * W, PER = (DD + 63) / 64, JB = (PER * QW <= 16) ? QW : 1;
+    // (copied one after the other, each word would wait for its own round trip, 2 QN of them for D = 128)
+    constexpr int DD = 32 * W, PER = (DD + 63) / 64, JB = (PER * QN <= 16) ? QN : 1;
 #pragma unroll
-    for (int j0 = 0; j0 < QW; j0 += JB) {
+    for (int j0 = 0; j0 < QN; j0 += JB) {
       float sv[JB][PER];
 #pragma unroll
       for (int jj = 0; jj < JB; ++jj)
@@ -556,6 +573,8 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     }
   }
   __syncthreads();
+  RQ_TL(item, 1, wall_clock64());
+  RQ_TL(item, 3, te - ts);
 
   int list_cnt = 0;
   // Streaming variant with 1-bit codes and k <= 64: the k best keys of each pair are kept in registers (lane l holds
@@ -563,10 +582,10 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   // sorts; its k-th key tightens the filter as the pools' compaction does.
   constexpr bool REGK_VARIANT = (F == 0 && PFD > 0);
   const bool regk = REGK_VARIANT && a.k <= 64;
-  WaveTopK top[QW];
-  bool started[QW];
+  WaveTopK top[QN];
+  bool started[QN];
 #pragma unroll
-  for (int j = 0; j < QW; ++j) {
+  for (int j = 0; j < QN; ++j) {
     top[j].v = KEY_NONE;
     started[j] = false;
   }
@@ -622,7 +641,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       // a pool that could not take the keys of another AHEAD rounds is cut to its k best (pool >= k + 64 >= k + AHEAD * NS)
       __syncthreads();
 #pragma unroll
-      for (int jj = 0; jj < QW; ++jj) {
+      for (int jj = 0; jj < QN; ++jj) {
         const int cj = pool_cnt[jj];
         if (cj + AHEAD * NS > a.pool) {
           RQ_STAT(2, 1);
@@ -675,34 +694,17 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       list_cnt += total;
     }
   }
-  for (int tile = ts; !MASKED && tile < te; ++tile) {
-    uint32_t cw[W];
-    float fq[3];
-    if (PD > 0) {
-#pragma unroll
-      for (int w = 0; w < W; ++w) cw[w] = pw[0][w];
-#pragma unroll
-      for (int f = 0; f < 3; ++f) fq[f] = pf[0][f];
-#pragma unroll
-      for (int d = 0; d + 1 < PD; ++d) {
-#pragma unroll
-        for (int w = 0; w < W; ++w) pw[d][w] = pw[PD > 1 ? d + 1 : 0][w];
-#pragma unroll
-        for (int f = 0; f < 3; ++f) pf[d][f] = pf[PD > 1 ? d + 1 : 0][f];
-      }
-      fetch(pw[PD > 0 ? PD - 1 : 0], pf[PD > 0 ? PD - 1 : 0], min(tile + PD, te - 1));  // past the end: a harmless re-read
-    } else {
-      fetch(cw, fq, tile);
-    }
+  // one 64-vector tile: first stage for the item's pairs, survivors filed (or, 1-bit codes, kept)
+  auto scan_tile = [&](const uint32_t (&cw)[W], const float (&fq)[3], const int tile) {
     const float fa = fq[0], fr = fq[1], fe = fq[2];
     // The plane words are re-read through the scalar cache for every (tile, query): an
-    // opaque zero keeps the compiler from hoisting QW*4*W scalar registers out of the loop.
+    // opaque zero keeps the compiler from hoisting QN*4*W scalar registers out of the loop.
     // (the streaming variant runs one or two queries per item and waits for memory, not for registers: there the
     // plane words may stay in scalar registers across tiles)
     int opaque0 = 0;
     if (!(PFD > 0 && W <= 4)) asm volatile("s_mov_b32 %0, 0" : "=s"(opaque0));
 #pragma unroll
-    for (int j = 0; j < QW; ++j) {
+    for (int j = 0; j < QN; ++j) {
       // pairs the item does not have (the last group of a list; most groups when a list is probed by one or two
       // queries only) are not estimated at all
       if (j >= np) break;
@@ -755,11 +757,38 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
         list_cnt += ns;
       }
     }
+  };
+  if (!MASKED && PD >= 2) {
+    // PD tiles ahead, in PD sets of registers that take turns (a set is requested again as soon as its tile is done;
+    // rotating the sets instead would make every tile wait for the loads of the next one too)
+    for (int tile = ts; tile < te; tile += PD) {
+#pragma unroll
+      for (int d = 0; d < PD; ++d) {
+        if (tile + d < te) {
+          scan_tile(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d);
+          fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(tile + d + PD, te - 1));  // past the end: a harmless re-read
+        }
+      }
+    }
+  }
+  for (int tile = ts; !MASKED && PD < 2 && tile < te; ++tile) {
+    uint32_t cw[W];
+    float fq[3];
+    if (PD > 0) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) cw[w] = pw[0][w];
+#pragma unroll
+      for (int f = 0; f < 3; ++f) fq[f] = pf[0][f];
+      fetch(pw[0], pf[0], min(tile + PD, te - 1));  // (PD == 1)
+    } else {
+      fetch(cw, fq, tile);
+    }
+    scan_tile(cw, fq, tile);
   }
   if (F > 0) {
     flush();
 #pragma unroll
-    for (int j = 0; j < QW; ++j) cnt[j] = pool_cnt[j];
+    for (int j = 0; j < QN; ++j) cnt[j] = pool_cnt[j];
   }
   // every key still in a pool goes out, unsorted; the per-query merge selects among them.
   // The segments of a split cluster share the pair's region (cand_cnt starts at 0 and is
@@ -767,7 +796,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   if (REGK_VARIANT && regk) {
     // the register lists go out through the pools' memory, so that one output path serves both
 #pragma unroll
-    for (int j = 0; j < QW; ++j) {
+    for (int j = 0; j < QN; ++j) {
       if (j >= np) break;
       const bool have = lane < a.k && top[j].v != KEY_NONE;
       cnt[j] = __popcll(__ballot(have));
@@ -775,7 +804,7 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
     }
   }
 #pragma unroll
-  for (int j = 0; j < QW; ++j) {
+  for (int j = 0; j < QN; ++j) {
     if (j >= np) break;
     if (nseg > 1 && cnt[j] > a.k) cnt[j] = pool_compact(pools + (size_t)j * a.pool, a.pool, cnt[j], a.k);
   }
@@ -783,18 +812,18 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
   // lane j reserves pair j's part of its candidate region: the atomics of the work item are in flight together
   int mine = 0, base_l = 0;
 #pragma unroll
-  for (int j = 0; j < QW; ++j)
+  for (int j = 0; j < QN; ++j)
     if (lane == j && j < np) mine = cnt[j];
   if (mine > 0) {
     int pp = pj[0];
 #pragma unroll
-    for (int j = 1; j < QW; ++j)
+    for (int j = 1; j < QN; ++j)
       if (lane == j) pp = pj[j];
     if (nseg > 1) base_l = atomicAdd(&a.cand_cnt[pp], mine);
     else a.cand_cnt[pp] = mine;  // the only work item of this pair: its region starts at 0 and nobody else counts
   }
 #pragma unroll
-  for (int j = 0; j < QW; ++j) {
+  for (int j = 0; j < QN; ++j) {
     if (j >= np) break;
     const uint64_t* pool = pools + (size_t)j * a.pool;
     const int base = __builtin_amdgcn_readlane(base_l, j);
@@ -804,6 +833,46 @@ __global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
       a.cand_keys[(int64_t)pj[j] * a.cand_stride + base + e] = key;
     }
   }
+  RQ_TL(item, 2, wall_clock64());
+}
+
+template <int W, int F, bool DBG, int M, int PFD = 0, bool MASKED = false>
+__global__ __launch_bounds__(64) void scan_kernel(ScanArgs a) {
+  // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD a
+  // contiguous range of work items; items of one cluster then share one L2.
+  // (the grid is an upper bound of the number of work items; the ranges are cut from the true count)
+  const int n_items = a.item_off[a.nlist];
+  const int per = (n_items + 7) >> 3;
+  const int item = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  if ((int)(blockIdx.x >> 3) >= per || item >= n_items) return;
+  scan_item<W, F, DBG, M, PFD, MASKED>(a, item);
+}
+
+// The prefetching variant (few pairs per list: every list is read from memory about once) as a kernel of its own: one
+// pair per work item.  It waits for memory, so what it needs is wavefronts in flight, and the scalar state of four
+// pairs (their plane words above all) costs more than 100 scalar registers, which admits six wavefronts per SIMD.
+// One workgroup per item, in the order of the descriptors (longest list first when the host has that order, so that
+// the short items come last and the launch ends everywhere at about the same time).  The number of items is only known
+// on the device and its upper bound is several times the usual count (all queries might probe the longest list), so
+// the grid is sized for the usual case and a workgroup goes on to item + grid size while there is one: a grid sized
+// from the bound would end in empty workgroups that cost more dispatch time than the scan takes.
+template <int W, int F, bool DBG>
+__device__ __forceinline__ void scan_stream_items(const ScanArgs& a) {
+  const int n_items = a.item_off[a.nlist];
+  for (int item = (int)blockIdx.x; item < n_items; item += (int)gridDim.x) {
+    scan_item<W, F, DBG, 0, 1, false>(a, item);
+    __syncthreads();  // (a further item starts by overwriting what this one read from LDS last)
+  }
+}
+// (1-bit codes: the kernel is held to the registers with which eight wavefronts share a SIMD; with a long code the
+// refinement's registers would spill to memory under that limit, so that form is left to the compiler)
+template <int W, bool DBG>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(8))) void scan_stream_kernel(ScanArgs a) {
+  scan_stream_items<W, 0, DBG>(a);
+}
+template <int W, int F, bool DBG>
+__global__ __launch_bounds__(64) void scan_stream_long_kernel(ScanArgs a) {
+  scan_stream_items<W, F, DBG>(a);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1153,16 +1222,24 @@ static void launch_scan_mfma_wf(const ScanArgs& a, unsigned grid, bool dbg, hipS
 template <int W, int F, int M>
 static void launch_scan_wf(const ScanArgs& a, unsigned grid, bool dbg, hipStream_t st) {
   const bool masked = M == 0 && F > 0 && a.surv_mask != nullptr;  // second half of the split search
-  const size_t smem = (size_t)QW * a.pool * sizeof(uint64_t) + QW * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
+  const bool stream = M == 0 && a.streaming && !masked;
+  const int qn = stream ? 1 : QW;  // pairs per work item
+  const size_t smem = (size_t)qn * a.pool * sizeof(uint64_t) + qn * (sizeof(uint64_t) + 2 * sizeof(float) + sizeof(int)) +
                       (F > 0 ? (masked ? LIST_CAP_MASKED : LIST_CAP) * sizeof(uint32_t) +
-                                   (size_t)QW * (a.D + 4 * RefineShape<W * (F > 0 ? F : 8)>::G) * sizeof(float) : 0) +
-                      (M == 1 ? (size_t)QW * W * 256 : 0);
+                                   (size_t)qn * (a.D + 4 * RefineShape<W * (F > 0 ? F : 8)>::G) * sizeof(float) : 0) +
+                      (M == 1 ? (size_t)qn * W * 256 : 0);
   if (masked)  // (estimate_mfma_kernel ran)
     hipLaunchKernelGGL((scan_kernel<W, F, false, M, 0, (M == 0 && F > 0)>), dim3(grid), dim3(64), smem, st, a);
+  else if (stream && F == 0 && dbg)
+    hipLaunchKernelGGL((scan_stream_kernel<W, true>), dim3(grid), dim3(64), smem, st, a);
+  else if (stream && F == 0)
+    hipLaunchKernelGGL((scan_stream_kernel<W, false>), dim3(grid), dim3(64), smem, st, a);
+  else if (stream && dbg)
+    hipLaunchKernelGGL((scan_stream_long_kernel<W, F, true>), dim3(grid), dim3(64), smem, st, a);
+  else if (stream)
+    hipLaunchKernelGGL((scan_stream_long_kernel<W, F, false>), dim3(grid), dim3(64), smem, st, a);
   else if (dbg)
     hipLaunchKernelGGL((scan_kernel<W, F, true, M>), dim3(grid), dim3(64), smem, st, a);
-  else if (M == 0 && a.streaming)
-    hipLaunchKernelGGL((scan_kernel<W, F, false, M, (M == 0 ? 1 : 0)>), dim3(grid), dim3(64), smem, st, a);
   else
     hipLaunchKernelGGL((scan_kernel<W, F, false, M>), dim3(grid), dim3(64), smem, st, a);
 }
@@ -1244,6 +1321,11 @@ bool RQ_PART_NAME(scan)(const ScanArgs& a, int W, int F, int impl, unsigned grid
   }
 }
 
+#if defined(RQ_TIMELINE)
+extern "C" int RQ_PART_NAME(rabitq_debug_timeline)(unsigned long long* out) {
+  return hipMemcpyFromSymbol(out, HIP_SYMBOL(g_timeline), sizeof(g_timeline)) == hipSuccess ? 0 : -3;
+}
+#endif
 #if defined(RQ_STATS)
 // development only: one counter block per translation unit (part), summed by the caller
 extern "C" int RQ_PART_NAME(rabitq_debug_scan_stats)(unsigned long long* out, int reset) {

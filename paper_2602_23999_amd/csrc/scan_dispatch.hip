@@ -18,14 +18,17 @@ __global__ void zero_i32_kernel(int32_t* p, int64_t n) {
 }
 
 __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off,
-                                                          const int32_t* __restrict__ tile_off, int n, int qw, int tseg,
+                                                          const int32_t* __restrict__ tile_off,
+                                                          const int32_t* __restrict__ order, int n, int qw, int tseg,
                                                           int segmax, int32_t* __restrict__ item_off) {
   __shared__ uint32_t part[256];
   const int tid = threadIdx.x;
   const int per = (n + 255) / 256;
   const int s = tid * per, e = min(n, s + per);
   uint32_t sum = 0;
-  auto items = [&](int i) -> uint32_t {
+  // (entry i is about cluster i, or about the i-th longest cluster when an order is given)
+  auto items = [&](int r) -> uint32_t {
+    const int i = order ? order[r] : r;
     return (uint32_t)((pair_off[i + 1] - pair_off[i] + qw - 1) / qw) *
            (uint32_t)seg_count(tile_off[i + 1] - tile_off[i], tseg, segmax);
   };
@@ -113,6 +116,38 @@ __global__ __launch_bounds__(64) void item_desc_kernel(const int32_t* __restrict
   }
 }
 
+// One wavefront per entry r of the item table (cluster order[r], or cluster r without an order) writes the descriptors
+// of its work items of one pair (prefetching variant of the popcount kernel).
+__global__ __launch_bounds__(64) void stream_desc_kernel(ScanArgs a, StreamDesc* __restrict__ desc) {
+  const int r = blockIdx.x;
+  const int i0 = a.item_off[r], n = a.item_off[r + 1] - i0;
+  if (n <= 0) return;
+  const int c = a.order ? a.order[r] : r;
+  const int t0 = a.tile_off[c], tiles = a.tile_off[c + 1] - t0;
+  const int p0 = a.pair_off[c];
+  const int nseg = seg_count(tiles, a.tseg, a.segmax);
+  const int seglen = (tiles + nseg - 1) / nseg;
+  for (int it = threadIdx.x; it < n; it += 64) {
+    const int pi = it / nseg, sidx = it - pi * nseg;
+    const int pp = a.pair_ids[p0 + pi];
+    const int q = pair_query(a, pp);
+    StreamDesc d{};
+    d.pp = pp;
+    d.q = q;
+    d.t0 = t0;
+    d.ts = t0 + sidx * seglen;
+    d.te = min(t0 + tiles, d.ts + seglen);
+    d.nseg = nseg;
+    d.ppos = p0 + pi;
+    d.S = a.sum_qhat[q];
+    d.G = a.probe_G[pp];
+    d.E = a.probe_E[pp];
+    d.delta = a.delta[q];
+    d.sumq = a.sum_q[q];
+    desc[i0 + it] = d;
+  }
+}
+
 // segments per cluster, sorted, for the work-item bound of a launch (cached per segment length and limit)
 static void update_seg_cache(const rabitq_index* ix, int tseg, int segmax) {
   std::vector<int>& nseg = ix->seg_sorted;
@@ -133,7 +168,8 @@ static int64_t item_bound(const rabitq_index* ix, int64_t nq, int nprobe, int pe
   const std::vector<int>& nseg = ix->seg_sorted;
   int64_t top = 0;
   for (int i = 0; i < nprobe && i < (int)nseg.size(); ++i) top += nseg[i];
-  const int64_t m = ix->seg_total + (nq * top + per_item - 1) / per_item;
+  // (items of one pair: exactly cnt_c * nseg_c of them)
+  const int64_t m = per_item == 1 ? nq * top : ix->seg_total + (nq * top + per_item - 1) / per_item;
   return ((m + 7) / 8) * 8;
 }
 
@@ -146,6 +182,31 @@ int64_t split_mask_blocks(rabitq_index* ix, int64_t nq, int nprobe) {
   }
   const size_t top = std::min<size_t>((size_t)nprobe, ix->tiles_prefix.size() - 1);
   return (nq * ix->tiles_prefix[top] + QM - 1) / QM + ix->n_tiles;
+}
+
+// few pairs per list, popcount kernel, not split: the shape the prefetching variant is for
+static bool stream_shape(const rabitq_index* ix, int64_t nq, int nprobe) {
+  return effective_impl(ix) == 0 && nq * nprobe <= 4 * (int64_t)ix->nlist && !split_wanted(ix, nq, nprobe);
+}
+static ScanPlan plan_for(const rabitq_index* ix, int64_t nq, int nprobe, int k, bool streaming);
+// descriptor slots (of sizeof(ItemDesc)) the prefetching variant needs for (nq, nprobe, k)
+static int64_t stream_desc_slots(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
+  const ScanPlan plan = plan_for(ix, nq, nprobe, k, true);
+  update_seg_cache(ix, plan.tseg, plan.segmax);
+  return item_bound(ix, nq, nprobe, 1) * (int64_t)(sizeof(StreamDesc) / sizeof(ItemDesc));
+}
+
+int ensure_stream_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k) {
+  if (!stream_shape(ix, nq, nprobe)) return RABITQ_OK;
+  const int64_t slots = stream_desc_slots(ix, nq, nprobe, k);
+  if (slots <= ix->item_desc_cap || slots > 0x7fffffff) return RABITQ_OK;
+  RQ_HIP(hipDeviceSynchronize());
+  if (ix->item_desc) (void)hipFree(ix->item_desc);
+  ix->item_desc = nullptr;
+  ix->item_desc_cap = 0;
+  RQ_HIP(hipMalloc(reinterpret_cast<void**>(&ix->item_desc), (size_t)slots * sizeof(ItemDesc)));
+  ix->item_desc_cap = slots;
+  return RABITQ_OK;
 }
 
 int ensure_split_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k) {
@@ -254,9 +315,10 @@ int launch_seed(const rabitq_index* ix, const rabitq_query_repr& repr, const int
 // contributes at most k keys to the pair's region of cand_stride keys (cand_cnt is advanced atomically).  The segment
 // length adapts to the batch: a large batch has more work items than the chip has wavefront slots and keeps long
 // segments (32 tiles); a small batch is cut finer, down to 2 tiles, so that about 4096 items exist.
-ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
+static ScanPlan plan_for(const rabitq_index* ix, int64_t nq, int nprobe, int k, bool streaming) {
   ScanPlan p;
-  p.qw = effective_impl(ix) == 1 ? QM : QW;
+  p.streaming = streaming;
+  p.qw = effective_impl(ix) == 1 ? QM : (p.streaming ? 1 : QW);
   const int64_t np_all = nq * nprobe;
   const int64_t est_items = std::min<int64_t>(np_all, (np_all + p.qw - 1) / p.qw + ix->nlist);
   const int64_t avg_tiles = std::max<int64_t>(1, ix->n_tiles / std::max(1, ix->nlist));
@@ -266,6 +328,16 @@ ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
   return p;
 }
 
+// Few pairs per list: every list is read from memory about once, by the prefetching variant of the popcount kernel,
+// whose work items are single pairs with a descriptor each (never together with the split search, whose items are
+// groups of pairs).  Taken when the handle's descriptor memory is large enough (ensure_stream_buffers, called by the
+// entry points that may allocate); otherwise the general kernel does the same work.
+ScanPlan scan_plan(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
+  const bool streaming = stream_shape(ix, nq, nprobe) && ix->item_desc != nullptr &&
+                         stream_desc_slots(ix, nq, nprobe, k) <= ix->item_desc_cap;
+  return plan_for(ix, nq, nprobe, k, streaming);
+}
+
 static SmallListArgs small_list_args(const rabitq_index* ix, const int32_t* probe_ids, int64_t nq, int nprobe, int k,
                                      int32_t* pair_off, int32_t* pair_ids, uint32_t* scratch, int32_t* cand_cnt) {
   const ScanPlan p = scan_plan(ix, nq, nprobe, k);
@@ -273,6 +345,7 @@ static SmallListArgs small_list_args(const rabitq_index* ix, const int32_t* prob
   b.probe_ids = probe_ids; b.nq = (int)nq; b.nprobe = nprobe; b.nlist = ix->nlist; b.tile_off = ix->tile_off;
   b.qw = p.qw; b.tseg = p.tseg; b.segmax = p.segmax; b.mask = scratch; b.pair_off = pair_off; b.pair_ids = pair_ids;
   b.item_off = ix->tile_off + (ix->nlist + 1); b.cand_cnt = cand_cnt;
+  b.desc = nullptr;
   return b;
 }
 
@@ -305,6 +378,12 @@ int launch_small_select_seed(const rabitq_index* ix, const rabitq_query_repr& re
   b.probe_ids = probe_ids; b.probe_G = probe_G; b.probe_E = probe_E;
   b.ticket = ix->tile_off + 2 * (ix->nlist + 1);
   b.lists = small_list_args(ix, probe_ids, nq, nprobe, k, pair_off, pair_ids, scratch, cand_cnt);
+  if (scan_plan(ix, nq, nprobe, k).streaming) {
+    // (the workgroup that builds the lists also writes the descriptors of the prefetching scan's work items)
+    b.lists.desc = reinterpret_cast<StreamDesc*>(ix->item_desc);
+    b.lists.probe_G = probe_G; b.lists.probe_E = probe_E;
+    b.lists.delta = repr.delta; b.lists.sum_q = repr.sum_q; b.lists.sum_qhat = repr.sum_qhat;
+  }
   const int W = ix->W, F = field_bits(ix->total_bits);
   if (!(small_part0(a, b, W, F, st) || small_part1(a, b, W, F, st) || small_part2(a, b, W, F, st))) return bad_width();
   RQ_HIP(hipGetLastError());
@@ -320,7 +399,8 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   ScanArgs a = base_args(ix);
   set_repr(a, ix, repr);
   const int impl = effective_impl(ix);
-  const int qw = impl == 1 ? QM : QW;
+  const ScanPlan plan = scan_plan(ix, nq, nprobe, k);
+  const int qw = plan.qw;
   a.probe_G = probe_G; a.probe_E = probe_E; a.pair_off = pair_off; a.pair_ids = pair_ids; a.tau = tau;
   set_nprobe(a, nprobe); a.k = k;
   a.cand_stride = next_pow2_host(k + TILE);
@@ -334,17 +414,26 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // work-item offsets live in the second half of the tile_off allocation (owned by the handle)
   int32_t* item_off = ix->tile_off + (ix->nlist + 1);
   a.item_off = item_off;
-  const ScanPlan plan = scan_plan(ix, nq, nprobe, k);
   a.tseg = plan.tseg;
   a.segmax = plan.segmax;
-  a.streaming = (nq * nprobe <= 4 * (int64_t)ix->nlist) ? 1 : 0;
+  a.streaming = plan.streaming ? 1 : 0;
+  // Few pairs per list: the lists are read from memory about once each and a work item lasts as long as its list is
+  // long, so the launch ends when its last long item does.  Handing the items out longest list first leaves the short
+  // ones for the end (the popcount kernel's own item table only: the small-batch builder and the split search keep
+  // cluster order, where items of one cluster share a cache).
+  if (a.streaming && !ss.setup_done && ix->longest_first && ix->cluster_order != nullptr) a.order = ix->cluster_order;
   if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
   if (!ss.setup_done) {
-    hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, qw, a.tseg,
-                       a.segmax, item_off);
+    hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, a.order, ix->nlist, qw,
+                       a.tseg, a.segmax, item_off);
     if (!ss.counters_clear) {
       if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
     }
+  }
+  if (a.streaming) a.stream_desc = reinterpret_cast<const StreamDesc*>(ix->item_desc);
+  if (a.streaming && !ss.desc_done) {
+    hipLaunchKernelGGL(stream_desc_kernel, dim3((unsigned)ix->nlist), dim3(64), 0, sst, a,
+                       reinterpret_cast<StreamDesc*>(ix->item_desc));
   }
   // Split search: the estimates of groups of 16 pairs on the matrix cores, then this kernel's refinement only.
   // Chosen when asked for (scan_impl 4), built for the index, worth it for the batch, and the handle's buffer of
@@ -355,6 +444,7 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
                      split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks &&
                      max_items <= ix->item_desc_cap;
   ss.split = split;
+  ss.streamed = a.streaming != 0;
   if (split) {
     int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
     uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
@@ -379,7 +469,9 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
     set_error("scan: too many work items");
     return RABITQ_EINVAL;
   }
-  const unsigned grid = (unsigned)max_items;
+  // (the prefetching variant's grid: the usual number of items, three for every two pairs, when the bound is larger;
+  // its workgroups go on to further items if there are more)
+  const unsigned grid = (unsigned)(a.streaming ? std::min<int64_t>(max_items, nq * nprobe + nq * nprobe / 2 + 1024) : max_items);
   const bool dbg = dbg_ip != nullptr;
   const int W = ix->W, F = field_bits(ix->total_bits);
   if (split) {
