@@ -339,7 +339,7 @@ def stream_scan(args, n, bits, steps, warmup):
     gi.close()
     return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": None, "traffic_source": "not counted: see profiles/scan_kernel_stream_scan.md",
-            "device_copy_gbs": copy_gbs, "kernel": "scan_kernel",
+            "device_copy_gbs": copy_gbs, "kernel": "scan_stream_kernel" if bits == 1 else "scan_stream_long_kernel",
             "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms, "query_vector_evaluations": qv,
             "workload": f"stream_scan: N={n} D={dim} nlist={nlist} B={bits} nq={nq} k={k} nprobe=1 (one query per list; "
                         f"{distinct} distinct lists probed)",
