@@ -199,6 +199,8 @@ static int init_streams(rabitq_index* ix) {
   ix->seg_sorted.reserve(ix->host_tiles.size());  // so that a search never grows a host vector either
   {
     // clusters by descending length: the order in which a scan that reads every list once hands them out (launch_scan)
+    ix->max_tiles = 0;
+    for (int32_t t : ix->host_tiles) ix->max_tiles = std::max(ix->max_tiles, t);
     std::vector<int32_t> order(ix->host_tiles.size());
     for (size_t c = 0; c < order.size(); ++c) order[c] = (int32_t)c;
     std::stable_sort(order.begin(), order.end(),

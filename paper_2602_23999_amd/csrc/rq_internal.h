@@ -63,6 +63,7 @@ struct rabitq_index {
   float* long_factors = nullptr;
   int32_t* ids = nullptr;
   std::vector<int32_t> host_tiles;  // tiles per cluster (host copy, sizes the scan grid)
+  int32_t max_tiles = 0;            // the longest list's
   // segments per cluster in descending order for the segment limit seg_sorted_max and length seg_sorted_tseg, and their sum (scan grid bound)
   mutable std::vector<int> seg_sorted;
   mutable int seg_sorted_max = -1, seg_sorted_tseg = -1;

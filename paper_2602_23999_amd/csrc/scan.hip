@@ -521,7 +521,11 @@ __device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
     const float sumq = PFD > 0 ? sdp->sumq : a.sum_q[q];
     bej[j] = 0.5f * dlj[j] * (float)Sj[j];
     hsqj[j] = 0.5f * sumq;
-    tauj[j] = (j < np) ? a.tau[q] : -3.402823466e+38f;  // an absent pair lets nothing through
+    // (the prefetching variant reads it through the scalar cache: as a vector load it would be the youngest load in
+    // flight when the tile loop starts, and every tile's wait for its own loads would become a wait for all of them)
+    typedef const float __attribute__((address_space(4)))* const_f32_sptr;
+    const float tau_q = PFD > 0 ? *(const_f32_sptr)(a.tau + q) : a.tau[q];
+    tauj[j] = (j < np) ? tau_q : -3.402823466e+38f;  // an absent pair lets nothing through
     cnt[j] = 0;
     if (lane == 0) {
       pool_kth[j] = KEY_NONE;
@@ -759,17 +763,22 @@ __device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
     }
   };
   if (!MASKED && PD >= 2) {
-    // PD tiles ahead, in PD sets of registers that take turns (a set is requested again as soon as its tile is done;
-    // rotating the sets instead would make every tile wait for the loads of the next one too)
-    for (int tile = ts; tile < te; tile += PD) {
+    // PD tiles ahead, in PD sets of registers that take turns: a set is requested again as soon as its tile is done.
+    // (Rotating the sets instead would make every tile wait for the loads of the next one too; and nothing in the
+    // main loop sits under a condition, because the compiler counts outstanding loads along the shortest path to a
+    // use, and a tile that may or may not have been requested in between makes it wait for all of them.)
+    int tile = ts;
+    for (; tile + PD <= te; tile += PD) {
 #pragma unroll
       for (int d = 0; d < PD; ++d) {
-        if (tile + d < te) {
-          scan_tile(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d);
-          fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(tile + d + PD, te - 1));  // past the end: a harmless re-read
-        }
+        scan_tile(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d);
+        fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(tile + d + PD, te - 1));  // past the end: a harmless re-read
       }
     }
+    // the last tiles (fewer than PD) are in their sets already
+#pragma unroll
+    for (int d = 0; d + 1 < PD; ++d)
+      if (tile + d < te) scan_tile(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d);
   }
   for (int tile = ts; !MASKED && PD < 2 && tile < te; ++tile) {
     uint32_t cw[W];

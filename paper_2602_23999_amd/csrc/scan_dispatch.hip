@@ -168,8 +168,7 @@ static int64_t item_bound(const rabitq_index* ix, int64_t nq, int nprobe, int pe
   const std::vector<int>& nseg = ix->seg_sorted;
   int64_t top = 0;
   for (int i = 0; i < nprobe && i < (int)nseg.size(); ++i) top += nseg[i];
-  // (items of one pair: exactly cnt_c * nseg_c of them)
-  const int64_t m = per_item == 1 ? nq * top : ix->seg_total + (nq * top + per_item - 1) / per_item;
+  const int64_t m = ix->seg_total + (nq * top + per_item - 1) / per_item;
   return ((m + 7) / 8) * 8;
 }
 
@@ -190,10 +189,14 @@ static bool stream_shape(const rabitq_index* ix, int64_t nq, int nprobe) {
 }
 static ScanPlan plan_for(const rabitq_index* ix, int64_t nq, int nprobe, int k, bool streaming);
 // descriptor slots (of sizeof(ItemDesc)) the prefetching variant needs for (nq, nprobe, k)
+// work items of one pair: a pair has as many as its list has segments, at most those of the longest list
+static int64_t stream_item_bound(const rabitq_index* ix, int64_t nq, int nprobe, const ScanPlan& plan) {
+  const int64_t m = nq * nprobe * seg_count(ix->max_tiles, plan.tseg, plan.segmax);
+  return ((m + 7) / 8) * 8;
+}
 static int64_t stream_desc_slots(const rabitq_index* ix, int64_t nq, int nprobe, int k) {
-  const ScanPlan plan = plan_for(ix, nq, nprobe, k, true);
-  update_seg_cache(ix, plan.tseg, plan.segmax);
-  return item_bound(ix, nq, nprobe, 1) * (int64_t)(sizeof(StreamDesc) / sizeof(ItemDesc));
+  return stream_item_bound(ix, nq, nprobe, plan_for(ix, nq, nprobe, k, true)) *
+         (int64_t)(sizeof(StreamDesc) / sizeof(ItemDesc));
 }
 
 int ensure_stream_buffers(rabitq_index* ix, int64_t nq, int nprobe, int k) {
@@ -438,8 +441,8 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // Split search: the estimates of groups of 16 pairs on the matrix cores, then this kernel's refinement only.
   // Chosen when asked for (scan_impl 4), built for the index, worth it for the batch, and the handle's buffer of
   // survivor bits is large enough (ensure_split_buffers, called by the entry points that may allocate).
-  update_seg_cache(ix, a.tseg, a.segmax);
-  const int64_t max_items = item_bound(ix, nq, nprobe, qw);
+  if (!a.streaming) update_seg_cache(ix, a.tseg, a.segmax);
+  const int64_t max_items = a.streaming ? stream_item_bound(ix, nq, nprobe, plan) : item_bound(ix, nq, nprobe, qw);
   const bool split = split_wanted(ix, nq, nprobe) && ix->surv_mask != nullptr && ix->item_desc != nullptr &&
                      split_mask_blocks(const_cast<rabitq_index*>(ix), nq, nprobe) <= ix->surv_mask_blocks &&
                      max_items <= ix->item_desc_cap;
