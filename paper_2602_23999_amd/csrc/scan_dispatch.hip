@@ -17,75 +17,61 @@ __global__ void zero_i32_kernel(int32_t* p, int64_t n) {
   for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) p[i] = 0;
 }
 
+// item16 != nullptr (split search): also item16[c] = first work item of cluster c when an item is 16 pairs times one
+// segment, and mask_off[c] = first block of survivor bits of cluster c (a block per group of 16 pairs and tile).
 __global__ __launch_bounds__(256) void item_offsets_kernel(const int32_t* __restrict__ pair_off,
                                                           const int32_t* __restrict__ tile_off,
                                                           const int32_t* __restrict__ order, int n, int qw, int tseg,
-                                                          int segmax, int32_t* __restrict__ item_off) {
-  __shared__ uint32_t part[256];
+                                                          int segmax, int32_t* __restrict__ item_off,
+                                                          int32_t* __restrict__ item16, uint32_t* __restrict__ mask_off) {
+  __shared__ uint32_t part[3][256];
   const int tid = threadIdx.x;
   const int per = (n + 255) / 256;
   const int s = tid * per, e = min(n, s + per);
-  uint32_t sum = 0;
   // (entry i is about cluster i, or about the i-th longest cluster when an order is given)
-  auto items = [&](int r) -> uint32_t {
+  auto counts = [&](int r, uint32_t& it, uint32_t& i16, uint32_t& mb) {
     const int i = order ? order[r] : r;
-    return (uint32_t)((pair_off[i + 1] - pair_off[i] + qw - 1) / qw) *
-           (uint32_t)seg_count(tile_off[i + 1] - tile_off[i], tseg, segmax);
+    const uint32_t pairs = (uint32_t)(pair_off[i + 1] - pair_off[i]), tiles = (uint32_t)(tile_off[i + 1] - tile_off[i]);
+    const uint32_t nseg = (uint32_t)seg_count((int)tiles, tseg, segmax), groups = (pairs + QM - 1) / QM;
+    it = ((pairs + qw - 1) / qw) * nseg;
+    i16 = groups * nseg;
+    mb = groups * tiles;
   };
-  for (int i = s; i < e; ++i) sum += items(i);
-  part[tid] = sum;
+  uint32_t sum[3] = {0, 0, 0};
+  for (int i = s; i < e; ++i) {
+    uint32_t a, b, c;
+    counts(i, a, b, c);
+    sum[0] += a; sum[1] += b; sum[2] += c;
+  }
+  const int nscan = item16 ? 3 : 1;
+  for (int v = 0; v < nscan; ++v) part[v][tid] = sum[v];
   __syncthreads();
   for (int d = 1; d < 256; d <<= 1) {
-    const uint32_t o = (tid >= d) ? part[tid - d] : 0u;
+    uint32_t o[3];
+    for (int v = 0; v < nscan; ++v) o[v] = (tid >= d) ? part[v][tid - d] : 0u;
     __syncthreads();
-    part[tid] += o;
+    for (int v = 0; v < nscan; ++v) part[v][tid] += o[v];
     __syncthreads();
   }
-  uint32_t run = part[tid] - sum;
+  uint32_t run[3];
+  for (int v = 0; v < nscan; ++v) run[v] = part[v][tid] - sum[v];
   for (int i = s; i < e; ++i) {
-    item_off[i] = (int32_t)run;
-    run += items(i);
-  }
-  if (tid == 255) item_off[n] = (int32_t)part[255];
-}
-
-
-// Split search: item16[c] = first work item of cluster c when an item is 16 pairs times one segment, and mask_off[c] =
-// first block of survivor bits of cluster c (a block per group of 16 pairs and tile).  (One workgroup.)
-__global__ __launch_bounds__(256) void split_offsets_kernel(const int32_t* __restrict__ pair_off,
-                                                           const int32_t* __restrict__ tile_off, int n, int tseg, int segmax,
-                                                           int32_t* __restrict__ item16, uint32_t* __restrict__ mask_off) {
-  __shared__ uint32_t part_i[256], part_b[256];
-  const int tid = threadIdx.x;
-  const int per = (n + 255) / 256;
-  const int s = tid * per, e = min(n, s + per);
-  auto groups = [&](int i) -> uint32_t { return (uint32_t)((pair_off[i + 1] - pair_off[i] + QM - 1) / QM); };
-  auto tiles = [&](int i) -> uint32_t { return (uint32_t)(tile_off[i + 1] - tile_off[i]); };
-  uint32_t si = 0, sb = 0;
-  for (int i = s; i < e; ++i) {
-    si += groups(i) * (uint32_t)seg_count((int)tiles(i), tseg, segmax);
-    sb += groups(i) * tiles(i);
-  }
-  part_i[tid] = si;
-  part_b[tid] = sb;
-  __syncthreads();
-  for (int d = 1; d < 256; d <<= 1) {
-    const uint32_t oi = (tid >= d) ? part_i[tid - d] : 0u, ob = (tid >= d) ? part_b[tid - d] : 0u;
-    __syncthreads();
-    part_i[tid] += oi;
-    part_b[tid] += ob;
-    __syncthreads();
-  }
-  uint32_t ri = part_i[tid] - si, rb = part_b[tid] - sb;
-  for (int i = s; i < e; ++i) {
-    item16[i] = (int32_t)ri;
-    mask_off[i] = rb;
-    ri += groups(i) * (uint32_t)seg_count((int)tiles(i), tseg, segmax);
-    rb += groups(i) * tiles(i);
+    uint32_t a, b, c;
+    counts(i, a, b, c);
+    item_off[i] = (int32_t)run[0];
+    run[0] += a;
+    if (item16) {
+      item16[i] = (int32_t)run[1];
+      mask_off[i] = run[2];
+      run[1] += b; run[2] += c;
+    }
   }
   if (tid == 255) {
-    item16[n] = (int32_t)part_i[255];
-    mask_off[n] = part_b[255];
+    item_off[n] = (int32_t)part[0][255];
+    if (item16) {
+      item16[n] = (int32_t)part[1][255];
+      mask_off[n] = part[2][255];
+    }
   }
 }
 
@@ -425,19 +411,6 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
   // ones for the end (the popcount kernel's own item table only: the small-batch builder and the split search keep
   // cluster order, where items of one cluster share a cache).
   if (a.streaming && !ss.setup_done && ix->longest_first && ix->cluster_order != nullptr) a.order = ix->cluster_order;
-  if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
-  if (!ss.setup_done) {
-    hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, a.order, ix->nlist, qw,
-                       a.tseg, a.segmax, item_off);
-    if (!ss.counters_clear) {
-      if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
-    }
-  }
-  if (a.streaming) a.stream_desc = reinterpret_cast<const StreamDesc*>(ix->item_desc);
-  if (a.streaming && !ss.desc_done) {
-    hipLaunchKernelGGL(stream_desc_kernel, dim3((unsigned)ix->nlist), dim3(64), 0, sst, a,
-                       reinterpret_cast<StreamDesc*>(ix->item_desc));
-  }
   // Split search: the estimates of groups of 16 pairs on the matrix cores, then this kernel's refinement only.
   // Chosen when asked for (scan_impl 4), built for the index, worth it for the batch, and the handle's buffer of
   // survivor bits is large enough (ensure_split_buffers, called by the entry points that may allocate).
@@ -448,11 +421,23 @@ int launch_scan(const rabitq_index* ix, const rabitq_query_repr& repr, const flo
                      max_items <= ix->item_desc_cap;
   ss.split = split;
   ss.streamed = a.streaming != 0;
+  int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
+  uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
+  if (ss.setup_b) RQ_HIP(hipEventRecord(ss.setup_b, sst));
+  // (one launch for the item table and, when the search is split, the two tables of its first half; a small batch's
+  // list builder has written the item table already, with the same values)
+  if (!ss.setup_done || split)
+    hipLaunchKernelGGL(item_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, a.order, ix->nlist, qw,
+                       a.tseg, a.segmax, item_off, split ? item16 : nullptr, split ? mask_off : nullptr);
+  if (!ss.setup_done && !ss.counters_clear) {
+    if (int rc = launch_clear_counters(cand_cnt, nq * nprobe, sst)) return rc;
+  }
+  if (a.streaming) a.stream_desc = reinterpret_cast<const StreamDesc*>(ix->item_desc);
+  if (a.streaming && !ss.desc_done) {
+    hipLaunchKernelGGL(stream_desc_kernel, dim3((unsigned)ix->nlist), dim3(64), 0, sst, a,
+                       reinterpret_cast<StreamDesc*>(ix->item_desc));
+  }
   if (split) {
-    int32_t* item16 = ix->tile_off + 2 * (ix->nlist + 1) + TICKET_WORDS;
-    uint32_t* mask_off = reinterpret_cast<uint32_t*>(item16 + (ix->nlist + 1));
-    hipLaunchKernelGGL(split_offsets_kernel, dim3(1), dim3(256), 0, sst, pair_off, ix->tile_off, ix->nlist, a.tseg, a.segmax,
-                       item16, mask_off);
     hipLaunchKernelGGL(item_desc_kernel, dim3((unsigned)ix->nlist), dim3(64), 0, sst, pair_off, ix->tile_off, item_off,
                        mask_off, a.tseg, a.segmax, ix->item_desc);
     a.item_off16 = item16;
