@@ -111,3 +111,32 @@ def test_search_independent_of_hand_out_order_and_small_batch(name, nq):
     finally:
         gi.set_option("small_batch", 1)
         gi.set_option("longest_first", 1)
+
+
+@pytest.mark.parametrize("name,nq", [("l2_128_b4", 30), ("tiny_b1", 32)])
+def test_call_that_may_not_allocate_falls_back_to_the_general_kernel(name, nq):
+    """A handle that has not yet made the descriptors' memory (no allocating call of this shape so far) searches a
+    streaming-shaped batch with the general kernel when asked through rabitq_search_noalloc; the allocating entry
+    point then takes the one-pair form.  Same results, bit for bit."""
+    from gpu_helpers import upload
+    c = case(name)
+    gi = upload(c["ix"])
+    k, nprobe = c["k"], c["nprobe"]
+    q = torch.from_numpy(c["Q"][:nq]).cuda().contiguous()
+    ids = torch.full((nq, k), -7, dtype=torch.int64, device="cuda")
+    d = torch.full((nq, k), float("nan"), dtype=torch.float32, device="cuda")
+    try:
+        gi.set_option("scan_impl", 0)
+        gi.search_noalloc(q, k, nprobe, ids, d)
+        torch.cuda.synchronize()
+        assert gi.index_info("last_scan_stream") == 0
+        want_ids, want_d = gi.search(q, k, nprobe)
+        torch.cuda.synchronize()
+        assert gi.index_info("last_scan_stream") == 1
+        assert torch.equal(ids, want_ids) and torch.equal(d, want_d)
+        gi.search_noalloc(q, k, nprobe, ids, d)   # now the memory is there
+        torch.cuda.synchronize()
+        assert gi.index_info("last_scan_stream") == 1
+        assert torch.equal(ids, want_ids) and torch.equal(d, want_d)
+    finally:
+        gi.close()
