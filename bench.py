@@ -112,6 +112,29 @@ def stored_traffic(workload, nprobe, split=False):
     return val, f"from profiles/{os.path.basename(path)} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, same kernel sources)"
 
 
+def stored_stream_traffic():
+    """Measured over algorithmic bytes of the streaming scan kernel, from the counter summary under profiles/ (taken on
+    smaller indices than the streaming leg's: the counter run does not complete at its size), if that summary was taken
+    with the kernel sources as they are now; else None."""
+    path = os.path.join(ROOT, "profiles", "scan_stream_kernel_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    src, rows = None, []
+    for line in open(path):
+        f = line.split()
+        if len(f) >= 2 and f[0] == "kernel_source_hash":
+            src = f[1]
+        if len(f) >= 7 and f[0].startswith("n_"):
+            written = 0 if f[6] == "none" else int(f[6])
+            rows.append({"n": int(f[0][2:]), "algorithmic_bytes": int(f[2]), "read_bytes": int(f[4]),
+                         "written_bytes": None if f[6] == "none" else written,
+                         "ratio": round((int(f[4]) + written) / int(f[2]), 4)})
+    if src != kernel_source_hash() or not rows:
+        return None
+    return {"source": "profiles/scan_stream_kernel_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on "
+                      "paper_2602_23999_amd/stream_probe, same kernel sources)", "launches": rows}
+
+
 def cpu_baseline(gi, Q, k, nprobe, budget_q=2000):
     """The CPU oracle as it stands, on the index the GPU leg searched (exported from the device and re-indexed into
     the oracle's arrays) and the first min(nq, 2000) of the same queries (10 to 30 s of CPU work), on all host cores the process may use: the
@@ -338,7 +361,8 @@ def stream_scan(args, n, bits, steps, warmup):
     del src, dst
     gi.close()
     return {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None, "traffic_source": "not counted: see profiles/scan_kernel_stream_scan.md",
+            "traffic": None, "traffic_source": "no counter run completes at this size: see profiles/scan_kernel_stream_scan.md",
+            "traffic_ratio": stored_stream_traffic(),
             "device_copy_gbs": copy_gbs, "kernel": "scan_stream_kernel" if bits == 1 else "scan_stream_long_kernel",
             "algorithmic_bytes_per_launch": alg_bytes, "kernel_ms": scan_ms, "query_vector_evaluations": qv,
             "workload": f"stream_scan: N={n} D={dim} nlist={nlist} B={bits} nq={nq} k={k} nprobe=1 (one query per list; "

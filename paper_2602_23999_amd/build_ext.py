@@ -11,6 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "librabitq_hip.so")
+PROBE = os.path.join(HERE, "stream_probe")
 # (source, extra defines, object name)
 UNITS = [("api.hip", [], "api.o"), ("gemm.hip", [], "gemm.o"), ("stages.hip", [], "stages.o"),
          ("scan_dispatch.hip", [], "scan_dispatch.o"), ("build.hip", [], "build.o"),
@@ -44,6 +45,9 @@ def build(verbose: bool = True, jobs: int = 7) -> str:
         list(ex.map(lambda c: _run(c, verbose), cmds))
     _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[os.path.join(OBJ, o) for _, _, o in UNITS], "-o", LIB],
          verbose)
+    # stand-alone driver of the streaming-regime scan (for counter runs under rocprofv3 without Python in the process)
+    _run([hipcc, *FLAGS, os.path.join(CSRC, "stream_probe.hip"), "-L", HERE, "-lrabitq_hip", "-Wl,-rpath,$ORIGIN",
+          "-o", PROBE], verbose)
     return LIB
 
 
