@@ -490,9 +490,15 @@ __device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
   float pf[PD > 0 ? PD : 1][3];
   auto fetch = [&](uint32_t (&w_)[W], float (&f_)[3], int tile) {
 #pragma unroll
-    for (int w = 0; w < W; ++w) w_[w] = a.short_codes[((int64_t)tile * W + w) * TILE + lane];
+    for (int w = 0; w < W; ++w) {
+      const uint32_t* p = a.short_codes + ((int64_t)tile * W + w) * TILE + lane;
+      w_[w] = PFD > 0 ? __builtin_nontemporal_load(p) : *p;
+    }
 #pragma unroll
-    for (int f = 0; f < 3; ++f) f_[f] = a.short_factors[((int64_t)tile * 3 + f) * TILE + lane];
+    for (int f = 0; f < 3; ++f) {
+      const float* p = a.short_factors + ((int64_t)tile * 3 + f) * TILE + lane;
+      f_[f] = PFD > 0 ? __builtin_nontemporal_load(p) : *p;
+    }
   };
   // (requested here, before the scalars of the pairs are fetched, so that the two waits overlap)
   if (PD > 0 && ts < te) {
@@ -763,16 +769,16 @@ __device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
     }
   };
   if (!MASKED && PD >= 2) {
-    // PD tiles ahead, in PD sets of registers that take turns: a set is requested again as soon as its tile is done.
-    // (Rotating the sets instead would make every tile wait for the loads of the next one too; and nothing in the
-    // main loop sits under a condition, because the compiler counts outstanding loads along the shortest path to a
-    // use, and a tile that may or may not have been requested in between makes it wait for all of them.)
+    // PD tiles ahead, in PD sets of registers that take turns: a set is requested again as soon as its tile is done
+    // (rotating the sets instead would make every tile wait for the loads of the next one too), and every tile of the
+    // main loop is scanned unconditionally.  Only a request past the item's end is left out: these loads carry the
+    // streaming hint, so a clamped re-read of the last tile would come from memory a second time.
     int tile = ts;
     for (; tile + PD <= te; tile += PD) {
 #pragma unroll
       for (int d = 0; d < PD; ++d) {
         scan_tile(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d);
-        fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], min(tile + d + PD, te - 1));  // past the end: a harmless re-read
+        if (tile + d + PD < te) fetch(pw[PD > 0 ? d : 0], pf[PD > 0 ? d : 0], tile + d + PD);
       }
     }
     // the last tiles (fewer than PD) are in their sets already

@@ -6,12 +6,13 @@
 // for what they show for the scan.  Data: N / 1024 centres N(0, 16 I); a point is its centre plus a scatter inside one
 // of 64 eight-dimensional subspaces (std 3) plus isotropic noise (std 0.3), from a counter-based generator.
 //
-//   stream_probe [N = 33554432] [bits = 1] [searches = 5]
+//   stream_probe [N = 33554432] [bits = 1] [searches = 5] [longest_first = 1] [scan_segment_tiles = 0] [kmeans_iters = 4]
 //
 // Prints the kernel-relevant sizes (lists probed, vectors scanned, algorithmic bytes at 24 or 28 bytes per vector) and
 // the mean time of a whole search; the scan kernel's own time is in the profiler's trace.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -51,18 +52,18 @@ __host__ __device__ inline float gauss(uint32_t a, uint32_t b) {
   return sqrtf(-2.0f * logf(u1)) * cosf(6.2831853f * u2);
 }
 
-// one wavefront-sized workgroup per vector: lane d and d + 64 are its dimensions
-__global__ __launch_bounds__(64) void make_points(float* __restrict__ x, int64_t n, int nlist, const float* __restrict__ basis) {
-  const int64_t i = blockIdx.x;
-  if (i >= n) return;
-  const uint32_t own = mix((uint32_t)i * 747796405u + 12345u) % (uint32_t)nlist;
-  float z[SUBDIM];
-  for (int t = 0; t < SUBDIM; ++t) z[t] = 3.0f * gauss((uint32_t)i, 1000u + t);
-  const float* b = basis + (size_t)(own % SUB) * D * SUBDIM;
-  for (int d = threadIdx.x; d < D; d += 64) {
-    float v = 4.0f * gauss(own, 77u + d) + 0.3f * gauss((uint32_t)i, 5000u + d);
-    for (int t = 0; t < SUBDIM; ++t) v += z[t] * b[d * SUBDIM + t];
-    x[i * D + d] = v;
+// one wavefront per vector (four to a workgroup): lane d and d + 64 are its dimensions
+__global__ __launch_bounds__(256) void make_points(float* __restrict__ x, int64_t n, int nlist, const float* __restrict__ basis) {
+  for (int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); i < n; i += (int64_t)gridDim.x * 4) {
+    const uint32_t own = mix((uint32_t)i * 747796405u + 12345u) % (uint32_t)nlist;
+    float z[SUBDIM];
+    for (int t = 0; t < SUBDIM; ++t) z[t] = 3.0f * gauss((uint32_t)i, 1000u + t);
+    const float* b = basis + (size_t)(own % SUB) * D * SUBDIM;
+    for (int d = threadIdx.x & 63; d < D; d += 64) {
+      float v = 4.0f * gauss(own, 77u + d) + 0.3f * gauss((uint32_t)i, 5000u + d);
+      for (int t = 0; t < SUBDIM; ++t) v += z[t] * b[d * SUBDIM + t];
+      x[i * D + d] = v;
+    }
   }
 }
 
@@ -84,9 +85,12 @@ int main(int argc, char** argv) {
   const int64_t n = argc > 1 ? std::atoll(argv[1]) : 33554432;
   const int bits = argc > 2 ? std::atoi(argv[2]) : 1;
   const int searches = argc > 3 ? std::atoi(argv[3]) : 5;
+  const int longest_first = argc > 4 ? std::atoi(argv[4]) : 1, seg_tiles = argc > 5 ? std::atoi(argv[5]) : 0;
+  const int kmeans_iters = argc > 6 ? std::atoi(argv[6]) : 4;  // (fewer iterations: fewer launches for a counter run to sit through)
   const int nlist = (int)(n / 1024), k = 10;
-  if (n < 65536 || n > ((int64_t)1 << 28) || bits < 1 || bits > 8 || searches < 1 || searches > 100) {
-    std::printf("usage: stream_probe [N in 65536 .. 2^28] [bits 1 .. 8] [searches 1 .. 100]\n");
+  if (n < 65536 || n > ((int64_t)1 << 28) || bits < 1 || bits > 8 || searches < 1 || searches > 100 || seg_tiles < 0 ||
+      seg_tiles > 4096 || kmeans_iters < 0 || kmeans_iters > 50) {
+    std::printf("usage: stream_probe [N in 65536 .. 2^28] [bits 1 .. 8] [searches 1 .. 100] [longest_first 0|1] [segment tiles] [k-means iterations 0 .. 50]\n");
     return 1;
   }
   // rotation: Gram-Schmidt on a Gaussian matrix; subspace bases the same way
@@ -115,7 +119,7 @@ int main(int argc, char** argv) {
   CK(hipMalloc(&d_basis, basis.size() * sizeof(float)));
   CK(hipMemcpy(d_basis, basis.data(), basis.size() * sizeof(float), hipMemcpyHostToDevice));
   CK(hipMalloc(&x, (size_t)n * D * sizeof(float)));
-  hipLaunchKernelGGL(make_points, dim3((unsigned)n), dim3(64), 0, 0, x, n, nlist, d_basis);
+  hipLaunchKernelGGL(make_points, dim3((unsigned)std::min<int64_t>((n + 3) / 4, 1 << 20)), dim3(256), 0, 0, x, n, nlist, d_basis);
   CK(hipGetLastError());
   const size_t cal_n = (size_t)64 << 20;  // 256 MiB each way
   CK(hipMalloc(&cal_in, cal_n * sizeof(float)));
@@ -124,7 +128,7 @@ int main(int argc, char** argv) {
   CK(hipDeviceSynchronize());
 
   rabitq_build_params prm{};
-  prm.dim = D; prm.nlist = nlist; prm.n = n; prm.total_bits = bits; prm.metric = RABITQ_L2; prm.kmeans_iters = 4;
+  prm.dim = D; prm.nlist = nlist; prm.n = n; prm.total_bits = bits; prm.metric = RABITQ_L2; prm.kmeans_iters = kmeans_iters;
   prm.train_size = n / 10; prm.epsilon0 = 1.9f; prm.rotation = P.data(); prm.center = 0;
   rabitq_index_t ix = nullptr;
   RQ(rabitq_index_build(&prm, x, &ix, nullptr));
@@ -158,6 +162,8 @@ int main(int argc, char** argv) {
   CK(hipMalloc(&out_ids, (size_t)nq * k * sizeof(int64_t)));
   CK(hipMalloc(&out_d, (size_t)nq * k * sizeof(float)));
   RQ(rabitq_set_option(ix, "scan_impl", 0));
+  RQ(rabitq_set_option(ix, "longest_first", longest_first != 0));
+  RQ(rabitq_set_option(ix, "scan_segment_tiles", seg_tiles));
 
   hipLaunchKernelGGL(calibration_add, dim3(8192), dim3(256), 0, 0, cal_in, cal_out, cal_n);
   RQ(rabitq_search(ix, q, nq, k, 1, out_ids, out_d, nullptr));  // (grows the workspace)
