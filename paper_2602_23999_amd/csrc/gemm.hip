@@ -111,7 +111,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(const float* __restrict__ A, 
         if (MODE == 2) v = -v;
         if (MODE == 3) v = colv[n] - 2.0f * v;
         if (MODE == 4) v = v - colv[n];
-        C[m * (int64_t)N + n] = v;
+        if (MODE == 1 || MODE == 2) __builtin_nontemporal_store(v, &C[m * (int64_t)N + n]);  // coarse scores: read once, by the selection
+        else C[m * (int64_t)N + n] = v;
       }
     }
   }

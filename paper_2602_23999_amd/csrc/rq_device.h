@@ -449,7 +449,7 @@ __device__ inline WaveTopK stream_select_smallest(const float* __restrict__ row,
     // is only used under a condition would otherwise be waited for before the next one is issued)
     float sv[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) sv[r] = row[min(r * 64 + lane, nlist - 1)];
+    for (int r = 0; r < R; ++r) sv[r] = __builtin_nontemporal_load(row + min(r * 64 + lane, nlist - 1));
 #pragma unroll
     for (int r = 0; r < R; ++r) sv[r] = pinned(sv[r]);
     uint32_t ord[R];
@@ -474,7 +474,7 @@ __device__ inline WaveTopK stream_select_smallest(const float* __restrict__ row,
   for (int tb = R * 64; tb < nlist; tb += 512) {
     float sc[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) sc[u] = row[min(tb + u * 64 + lane, nlist - 1)];
+    for (int u = 0; u < 8; ++u) sc[u] = __builtin_nontemporal_load(row + min(tb + u * 64 + lane, nlist - 1));
 #pragma unroll
     for (int u = 0; u < 8; ++u) sc[u] = pinned(sc[u]);
 #pragma unroll
