@@ -88,3 +88,14 @@ def test_binding_structures_match_the_header_member_for_member():
                          ("rabitq_build_params", rabitq._BuildParams)):
         assert [f[0] for f in ctype._fields_] == structs[cname], cname
     assert ctypes.sizeof(rabitq._QueryRepr) == 8 * len(structs["rabitq_query_repr"])
+
+
+def test_stream_probe_driver_is_built_and_links_against_the_library():
+    """The stand-alone driver of the streaming-regime scan (csrc/stream_probe.hip) is built beside the library and
+    finds it through its run path; with arguments out of range it prints its usage before any GPU call."""
+    import subprocess
+    from paper_2602_23999_amd import rabitq
+    exe = os.path.join(os.path.dirname(rabitq.LIB_PATH), "stream_probe")
+    assert os.path.exists(exe), "run __graft_entry__.build()"
+    r = subprocess.run([exe, "1"], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=60)
+    assert r.returncode == 1 and "usage: stream_probe" in r.stdout
