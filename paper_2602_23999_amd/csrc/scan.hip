@@ -488,6 +488,9 @@ __device__ __forceinline__ void scan_item(const ScanArgs& a, const int item) {
   constexpr int PD = PFD > 0 ? (W <= 8 ? 2 : 1) : 0;  // tiles requested ahead (three and four: no faster)
   uint32_t pw[PD > 0 ? PD : 1][W];
   float pf[PD > 0 ? PD : 1][3];
+  // (the prefetching variant reads every tile once and never again: with the streaming hint its codes and factors do
+  // not displace one another, the descriptors, the plane words and the ids in the L2 - the largest single gain of that
+  // variant; everywhere else a tile is shared by the pairs of its cluster and wants to stay cached)
   auto fetch = [&](uint32_t (&w_)[W], float (&f_)[3], int tile) {
 #pragma unroll
     for (int w = 0; w < W; ++w) {
